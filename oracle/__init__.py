@@ -1,0 +1,210 @@
+"""fp64 CPU oracle for the RVQ KV-cache compressor (arXiv 2410.15704).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by ``__graft_entry__.smoke`` and
+by the ``cpu_baseline`` leg of ``bench.py``.  The product package never imports
+this module and this module never imports the product package.
+
+The arithmetic lives in ``rvq_oracle.c`` (plain C, double precision, compiled
+with gcc); this file only marshals numpy arrays into it.  Function names and
+argument order mirror the C file; see its header for the paper passages each
+function follows and for the readings taken where the paper is silent.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+import sys
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "rvq_oracle.c")
+_LIB = os.path.join(_HERE, "liborvq.so")
+
+CONTIGUOUS = 0
+STRIDED = 1
+
+
+def build(force: bool = False) -> str:
+    """Compile rvq_oracle.c with gcc into oracle/liborvq.so."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        c_dp = ctypes.POINTER(ctypes.c_double)
+        c_ip = ctypes.POINTER(ctypes.c_int32)
+        i64, i32, f64 = ctypes.c_int64, ctypes.c_int, ctypes.c_double
+        lib.rvq_oracle_threads.restype = i32
+        lib.rvq_oracle_row_std.argtypes = [c_dp, i64, i64, i32, c_dp]
+        lib.rvq_oracle_encode.argtypes = [c_dp, i64, i64, i64, i32, i64, i32, i32, i32, c_dp, c_ip,
+                                          c_dp, c_dp, c_dp, c_dp]
+        lib.rvq_oracle_decode.argtypes = [c_ip, c_dp, i64, i64, i64, i32, i32, i64, i32, c_dp, c_dp]
+        lib.rvq_oracle_prefix_excess.argtypes = [c_dp, i64, i64, i64, i32, i64, i32, i32, i32, c_dp,
+                                                 c_ip, c_dp, c_dp]
+        lib.rvq_oracle_ema_update.argtypes = [c_dp, c_ip, i64, i64, i64, i64, f64, f64, c_dp, c_dp,
+                                              c_dp]
+        lib.rvq_oracle_compressed_bits.argtypes = [i64, i64, i32, i64, i32]
+        lib.rvq_oracle_compressed_bits.restype = i64
+        _lib = lib
+    return _lib
+
+
+def _dp(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double)) if a is not None else None
+
+
+def _ip(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)) if a is not None else None
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise ValueError(f"oracle {what} failed with code {rc}")
+
+
+def threads() -> int:
+    """Number of OpenMP threads the row loops use."""
+    return int(_load().rvq_oracle_threads())
+
+
+def row_std(X, ddof: int = 0):
+    X = _f64(X)
+    N, d = X.shape
+    out = np.empty(N, dtype=np.float64)
+    _check(_load().rvq_oracle_row_std(_dp(X), N, d, ddof, _dp(out)), "row_std")
+    return out
+
+
+def encode(X, C, dhat: int, grouping: int = CONTIGUOUS, scale: bool = True, ddof: int = 0,
+           want_residual: bool = False, want_gap: bool = False):
+    """Section 2.2 + Algorithm 1.  X [N][d]; C [depth][K][dhat].
+
+    Returns a dict: codes int32 [N][G][depth], std [N], and when asked
+    residual [N][G][dhat], gap and rnorm2 [N][G][depth].
+    """
+    X = _f64(X)
+    C = _f64(C)
+    N, d = X.shape
+    depth, K, dh = C.shape
+    if dh != dhat:
+        raise ValueError("codebook width differs from dhat")
+    G = d // dhat
+    codes = np.empty((N, G, depth), dtype=np.int32)
+    std = np.empty(N, dtype=np.float64)
+    resid = np.empty((N, G, dhat), dtype=np.float64) if want_residual else None
+    gap = np.empty((N, G, depth), dtype=np.float64) if want_gap else None
+    rn2 = np.empty((N, G, depth), dtype=np.float64) if want_gap else None
+    _check(_load().rvq_oracle_encode(_dp(X), N, d, dhat, depth, K, grouping, int(bool(scale)), ddof,
+                                     _dp(C), _ip(codes), _dp(std), _dp(resid), _dp(gap), _dp(rn2)),
+           "encode")
+    out = {"codes": codes, "std": std}
+    if want_residual:
+        out["residual"] = resid
+    if want_gap:
+        out["gap"] = gap
+        out["rnorm2"] = rn2
+    return out
+
+
+def decode(codes, std, C, d: int, grouping: int = CONTIGUOUS, depth_used: int | None = None):
+    """Section 2.2, last sentence.  codes [N][G][depth]; std [N]; returns [N][d] float64."""
+    codes = np.ascontiguousarray(codes, dtype=np.int32)
+    std = _f64(std)
+    C = _f64(C)
+    depth, K, dhat = C.shape
+    N = codes.shape[0]
+    if codes.shape != (N, d // dhat, depth):
+        raise ValueError("codes shape does not match [N][d/dhat][depth]")
+    if depth_used is None:
+        depth_used = depth
+    out = np.empty((N, d), dtype=np.float64)
+    _check(_load().rvq_oracle_decode(_ip(codes), _dp(std), N, d, dhat, depth, depth_used, K,
+                                     grouping, _dp(C), _dp(out)), "decode")
+    return out
+
+
+def prefix_excess(X, C, dhat: int, given_codes, grouping: int = CONTIGUOUS, scale: bool = True,
+                  ddof: int = 0):
+    """dist(given code) - min dist per (vector, group, stage), residual rebuilt from the given
+    codes of earlier stages; also the squared norm of that residual."""
+    X = _f64(X)
+    C = _f64(C)
+    N, d = X.shape
+    depth, K, _ = C.shape
+    given = np.ascontiguousarray(given_codes, dtype=np.int32)
+    G = d // dhat
+    if given.shape != (N, G, depth):
+        raise ValueError("given codes shape does not match [N][G][depth]")
+    excess = np.empty((N, G, depth), dtype=np.float64)
+    rn2 = np.empty((N, G, depth), dtype=np.float64)
+    _check(_load().rvq_oracle_prefix_excess(_dp(X), N, d, dhat, depth, K, grouping,
+                                            int(bool(scale)), ddof, _dp(C), _ip(given),
+                                            _dp(excess), _dp(rn2)), "prefix_excess")
+    return excess, rn2
+
+
+def ema_update(R, codes, K: int, decay: float, eps: float, cluster_size, embed_sum):
+    """One moving-average update of one codebook.  Returns new (cluster_size, embed_sum, codebook);
+    the inputs are not modified."""
+    R = _f64(R)
+    M, dhat = R.shape
+    codes = np.ascontiguousarray(codes, dtype=np.int32).reshape(-1)
+    if codes.shape[0] != M:
+        raise ValueError("one code per vector expected")
+    cs = _f64(cluster_size).copy()
+    es = _f64(embed_sum).copy()
+    cb = np.empty((K, dhat), dtype=np.float64)
+    _check(_load().rvq_oracle_ema_update(_dp(R), _ip(codes), 1, M, K, dhat, float(decay),
+                                         float(eps), _dp(cs), _dp(es), _dp(cb)), "ema_update")
+    return cs, es, cb
+
+
+def compressed_bits(d: int, dhat: int, depth: int, K: int, std_bits: int = 16) -> int:
+    return int(_load().rvq_oracle_compressed_bits(d, dhat, depth, K, std_bits))
+
+
+def scaled_groups(X, dhat: int, grouping: int = CONTIGUOUS, scale: bool = True, ddof: int = 0):
+    """The vectors Algorithm 1 receives: rows scaled by their std and split into groups,
+    [N*G][dhat] float64.  Obtained from the C oracle itself, as the residual a single all-zero
+    codeword leaves."""
+    zero = np.zeros((1, 1, dhat), dtype=np.float64)
+    out = encode(X, zero, dhat, grouping, scale=scale, ddof=ddof, want_residual=True)
+    return out["residual"].reshape(-1, dhat)
+
+
+def sample_init_codebooks(Z, depth: int, K: int, rng: np.random.Generator):
+    """Stage-by-stage codebooks for the synthetic workloads: stage s takes K distinct rows, drawn
+    without replacement, of the vectors that enter stage s (the scaled group vectors for s = 0,
+    then the residuals the earlier stages leave).  Z [V][dhat] float64, V >= K.
+    Returns C [depth][K][dhat] float64.  (Section 3 initialises each codebook from "the
+    corresponding inputs"; sampling stands in for the k-means the paper runs on them.)"""
+    Z = _f64(Z)
+    V, dhat = Z.shape
+    C = np.empty((depth, K, dhat), dtype=np.float64)
+    R = Z
+    for s in range(depth):
+        pick = rng.choice(V, size=K, replace=False)
+        C[s] = R[np.sort(pick)]
+        out = encode(R, C[s:s + 1], dhat, CONTIGUOUS, scale=False, want_residual=True)
+        R = out["residual"].reshape(V, dhat)
+    return C
+
+
+if __name__ == "__main__":
+    print(build(force="--force" in sys.argv))
