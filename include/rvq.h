@@ -1,0 +1,149 @@
+/*
+ * librvq - residual vector quantization of KV-cache vectors on one AMD MI355X (gfx950).
+ *
+ * C ABI of the data-parallel hot path of arXiv 2410.15704:
+ *   Section 2.2 "Proposed Method"   scale a vector x in R^d by its own standard deviation,
+ *                                   split it into groups of dhat channels, quantize every group
+ *                                   with the same residual quantizer, output = (sum of chosen
+ *                                   codewords) * std;
+ *   Algorithm 1                     greedy residual quantization of one group: per codebook
+ *                                   pick the nearest codeword, subtract it, go on;
+ *   Section 3.1                     groups are contiguous channels or channels d/dhat apart;
+ *   Section 2.1 / Section 3         codebooks learnt by exponential moving average (decay 0.99).
+ *
+ * Paper symbol -> name here: number of codebooks "K" -> depth; codes per codebook "|C_i|"
+ * (Table 2: "C") -> K; code size "\hat d" -> dhat; G = d / dhat groups per vector.
+ *
+ * Conventions for every entry point
+ *   - returns 0 on success or a negative RVQ_E* code; never throws, never aborts;
+ *   - "device" pointers are HIP device pointers on the device that was current at rvq_create,
+ *     16-byte aligned; the CALLER owns them; the library keeps no reference after the work it
+ *     enqueued has run;
+ *   - work is enqueued on the caller's stream (a hipStream_t passed as void*; NULL = the
+ *     default stream); no entry point synchronizes the device except rvq_create/rvq_destroy
+ *     and a growth of the context's internal workspace (see rvq_encode);
+ *   - the context owns its pre-processed codebook copies and workspace and frees them in
+ *     rvq_destroy; one context must not be used from two host threads at once;
+ *   - N == 0 / M == 0 is a successful no-op.
+ */
+#ifndef RVQ_H
+#define RVQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RVQ_OK 0
+#define RVQ_EINVAL (-1)      /* null pointer, bad shape / range / alignment / enum */
+#define RVQ_ENOCODEBOOK (-2) /* encode / decode / ema before rvq_set_codebooks */
+#define RVQ_EHIP (-3)        /* a HIP runtime call failed; see rvq_last_hip_error */
+#define RVQ_ENOMEM (-4)      /* host or device allocation failed */
+
+#define RVQ_MAX_DEPTH 16
+#define RVQ_MAX_K 32768 /* codes are stored as int16 */
+
+enum rvq_dtype { RVQ_F32 = 0, RVQ_BF16 = 1, RVQ_F16 = 2 };
+enum rvq_grouping {
+  RVQ_CONTIGUOUS = 0, /* channel c = g * dhat + j            (Section 3.1, values)            */
+  RVQ_STRIDED = 1     /* channel c = j * G + g: members of a group are G channels apart
+                         (Section 3.1, keys)                                                  */
+};
+enum rvq_encode_path {
+  RVQ_PATH_AUTO = 0,   /* the fastest path that supports the shape                            */
+  RVQ_PATH_EXACT = 1,  /* fp32 scan of every codeword, distances in direct form               */
+  RVQ_PATH_SCREEN = 2  /* fp16 matrix-core screen of every codeword + exact fp32 re-scoring of
+                          every codeword the screen cannot rule out (needs dhat == 32)        */
+};
+
+typedef struct rvq_ctx rvq_ctx; /* opaque */
+
+typedef struct {
+  int32_t d;         /* channels per vector; d % dhat == 0                                     */
+  int32_t dhat;      /* channels per group = codeword size; 1..64 (fast paths need 32)         */
+  int32_t depth;     /* number of codebooks (residual stages), 1..RVQ_MAX_DEPTH                */
+  int32_t K;         /* codewords per codebook, 1..RVQ_MAX_K                                   */
+  int32_t grouping;  /* enum rvq_grouping                                                      */
+  int32_t scale;     /* 1: divide each row by its std (Section 2.2); 0: rows are already scaled
+                        (std taken as 1; used for codebook learning on residuals)              */
+  int32_t std_ddof;  /* std divisor is d - std_ddof; 0 (default) or 1                          */
+  int32_t in_dtype;  /* enum rvq_dtype of X                                                    */
+  int32_t out_dtype; /* enum rvq_dtype of decode output: RVQ_F16 (paper: half precision) or
+                        RVQ_F32                                                                */
+  int32_t std_dtype; /* enum rvq_dtype of the std buffer: RVQ_F16 (Section 3.2) or RVQ_F32     */
+  int32_t encode_path; /* enum rvq_encode_path                                                 */
+  int32_t reserved;  /* must be 0                                                              */
+} rvq_config;
+
+/* Create / destroy a context for one quantizer (one codebook set; Section 3: one per key and one
+ * per value projection of an attention block).  rvq_create validates the configuration. */
+int rvq_create(rvq_ctx **out, const rvq_config *cfg);
+int rvq_destroy(rvq_ctx *ctx);
+
+/* Upload the codebooks {C_i} of Algorithm 1: dC is device memory, float [depth][K][dhat].  The
+ * context copies them and derives what its kernels need (squared norms, half-precision operand
+ * copies, rounding-error bounds); dC may be reused once the stream has passed this call.
+ * rvq_get_codebooks writes the context's current fp32 codebooks back to dC. */
+int rvq_set_codebooks(rvq_ctx *ctx, const float *dC, void *stream);
+int rvq_get_codebooks(rvq_ctx *ctx, float *dC, void *stream);
+
+/*
+ * Encode (Section 2.2 + Algorithm 1).
+ *   dX        device, [N] rows of d channels of cfg.in_dtype, row stride ldx elements (>= d)
+ *   stage_begin, stage_end   codebooks [stage_begin, stage_end) are applied; normally 0, depth.
+ *             With a range that does not start at 0 the rows are taken to be the residuals that
+ *             enter stage_begin.
+ *   dCodes    device, int16 [N][G][depth]; entries [.][.][stage_begin..stage_end) are written
+ *   dStd      device, [N] of cfg.std_dtype; written when cfg.scale == 1 (the value is the
+ *             unrounded fp32 std rounded once to std_dtype; the division always uses the fp32
+ *             value); may be NULL when cfg.scale == 0
+ *   dResidual device, optional float [N][G][dhat]: the residual left after stage_end - 1
+ *             (z_{i+1} of Algorithm 1, in group order); NULL to skip
+ * Nearest = smallest squared Euclidean distance; ties go to the smallest index.  A row whose std
+ * is below 1e-30 is scaled by 1.
+ * The context keeps an internal workspace of 4 bytes per row; when N exceeds every earlier N it
+ * is re-allocated (hipFree synchronizes the device).
+ */
+int rvq_encode(rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx, int32_t stage_begin,
+               int32_t stage_end, int16_t *dCodes, void *dStd, float *dResidual, void *stream);
+
+/*
+ * Decode (Section 2.2, last sentence): out[n][c(g,j)] = std[n] * sum_{i < depth_used}
+ * C_i[codes[n][g][i]][j], summed in stage order in fp32, rounded once to cfg.out_dtype.
+ *   dCodes  device, int16 [N][G][depth]; every code must lie in [0, K) (not checked on device
+ *           beyond a clamp that keeps reads in bounds)
+ *   dStd    device, [N] of cfg.std_dtype; NULL means std = 1
+ *   depth_used 1..depth
+ *   dOut    device, [N] rows of d channels of cfg.out_dtype, row stride ldo elements (>= d)
+ */
+int rvq_decode(rvq_ctx *ctx, const int16_t *dCodes, const void *dStd, int64_t N,
+               int32_t depth_used, void *dOut, int64_t ldo, void *stream);
+
+/*
+ * One exponential-moving-average update of codebook `stage` (Section 2.1; decay 0.99 in
+ * Section 3).  With n_k the number of inputs assigned to code k and S_k their sum:
+ *     N_k <- decay N_k + (1 - decay) n_k        M_k <- decay M_k + (1 - decay) S_k
+ *     T = sum_k N_k,   Nt_k = (N_k + eps) / (T + K eps) * T,   C_k <- M_k / Nt_k  (0 if Nt_k == 0)
+ *   dR           device, float [M][dhat]: the vectors that were quantized at this stage
+ *   dCodes       device, int16: code of vector v at dCodes[v * code_stride]
+ *   dClusterSize device, float [K], in/out (N_k)
+ *   dEmbedSum    device, float [K][dhat], in/out (M_k)
+ * The new codebook replaces codebook `stage` inside the context (and its derived copies);
+ * read it back with rvq_get_codebooks.
+ */
+int rvq_ema_update(rvq_ctx *ctx, int32_t stage, const float *dR, const int16_t *dCodes,
+                   int64_t code_stride, int64_t M, float decay, float eps, float *dClusterSize,
+                   float *dEmbedSum, void *stream);
+
+/* Text for an RVQ_E* code; the HIP error code of the last RVQ_EHIP on this context (0 if none). */
+const char *rvq_strerror(int code);
+int rvq_last_hip_error(const rvq_ctx *ctx);
+
+/* Library version, major * 1000 + minor. */
+int rvq_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RVQ_H */

@@ -1,0 +1,208 @@
+"""ctypes binding of librvq.so: the same entry points as include/rvq.h, argument marshalling only.
+
+PyTorch is used for device memory and streams; every step of the method runs inside the
+library's HIP kernels.  Importing this module fails loudly when the library has not been built
+(``python -m paper_2410_15704_amd.build``): there is no fallback of any kind.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "librvq.so")
+
+RVQ_OK, RVQ_EINVAL, RVQ_ENOCODEBOOK, RVQ_EHIP, RVQ_ENOMEM = 0, -1, -2, -3, -4
+F32, BF16, F16 = 0, 1, 2
+CONTIGUOUS, STRIDED = 0, 1
+PATH_AUTO, PATH_EXACT, PATH_SCREEN = 0, 1, 2
+DTYPES = {"fp32": F32, "bf16": BF16, "fp16": F16}
+
+EXPORTS = ("rvq_create", "rvq_destroy", "rvq_set_codebooks", "rvq_get_codebooks", "rvq_encode",
+           "rvq_decode", "rvq_ema_update", "rvq_strerror", "rvq_last_hip_error", "rvq_version")
+
+
+class rvq_config(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "d", "dhat", "depth", "K", "grouping", "scale", "std_ddof", "in_dtype", "out_dtype",
+        "std_dtype", "encode_path", "reserved")]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2410_15704_amd.build` "
+            "(hipcc, gfx950). There is no fallback path.")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_float
+    lib.rvq_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(rvq_config)]
+    lib.rvq_destroy.argtypes = [vp]
+    lib.rvq_set_codebooks.argtypes = [vp, vp, vp]
+    lib.rvq_get_codebooks.argtypes = [vp, vp, vp]
+    lib.rvq_encode.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp, vp, vp]
+    lib.rvq_decode.argtypes = [vp, vp, vp, i64, i32, vp, i64, vp]
+    lib.rvq_ema_update.argtypes = [vp, i32, vp, vp, i64, i64, f32, f32, vp, vp, vp]
+    lib.rvq_strerror.argtypes = [ctypes.c_int]
+    lib.rvq_strerror.restype = ctypes.c_char_p
+    lib.rvq_last_hip_error.argtypes = [vp]
+    lib.rvq_version.restype = ctypes.c_int
+    for name in EXPORTS:
+        getattr(lib, name)
+        if name not in ("rvq_strerror", "rvq_version"):
+            getattr(lib, name).restype = ctypes.c_int
+    return lib
+
+
+lib = _load()
+
+
+class RvqError(RuntimeError):
+    def __init__(self, code, ctx=None):
+        self.code = code
+        msg = lib.rvq_strerror(code).decode()
+        if code == RVQ_EHIP and ctx:
+            msg += f" (hipError {lib.rvq_last_hip_error(ctx)})"
+        super().__init__(f"librvq: {msg} [{code}]")
+
+
+def _ptr(t):
+    """Device pointer of a torch tensor (or None / int passthrough)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+# ---- the entry points, same names as the header -----------------------------------------------
+def rvq_version() -> int:
+    return lib.rvq_version()
+
+
+def rvq_strerror(code: int) -> str:
+    return lib.rvq_strerror(code).decode()
+
+
+def rvq_create(*, d, dhat=32, depth=8, K=2048, grouping=CONTIGUOUS, scale=1, std_ddof=0,
+               in_dtype=F32, out_dtype=F16, std_dtype=F16, encode_path=PATH_AUTO, check=True):
+    cfg = rvq_config(d, dhat, depth, K, grouping, scale, std_ddof, in_dtype, out_dtype, std_dtype,
+                     encode_path, 0)
+    ctx = ctypes.c_void_p()
+    rc = lib.rvq_create(ctypes.byref(ctx), ctypes.byref(cfg))
+    if rc != RVQ_OK:
+        if check:
+            raise RvqError(rc)
+        return rc
+    return ctx
+
+
+def rvq_destroy(ctx):
+    return lib.rvq_destroy(ctx)
+
+
+def _chk(rc, ctx):
+    if rc != RVQ_OK:
+        raise RvqError(rc, ctx)
+    return rc
+
+
+def rvq_set_codebooks(ctx, dC, stream=None):
+    return _chk(lib.rvq_set_codebooks(ctx, _ptr(dC), _stream(stream)), ctx)
+
+
+def rvq_get_codebooks(ctx, dC, stream=None):
+    return _chk(lib.rvq_get_codebooks(ctx, _ptr(dC), _stream(stream)), ctx)
+
+
+def rvq_encode(ctx, dX, N, ldx, stage_begin, stage_end, dCodes, dStd, dResidual=None, stream=None):
+    return _chk(lib.rvq_encode(ctx, _ptr(dX), N, ldx, stage_begin, stage_end, _ptr(dCodes),
+                               _ptr(dStd), _ptr(dResidual), _stream(stream)), ctx)
+
+
+def rvq_decode(ctx, dCodes, dStd, N, depth_used, dOut, ldo, stream=None):
+    return _chk(lib.rvq_decode(ctx, _ptr(dCodes), _ptr(dStd), N, depth_used, _ptr(dOut), ldo,
+                               _stream(stream)), ctx)
+
+
+def rvq_ema_update(ctx, stage, dR, dCodes, code_stride, M, decay, eps, dClusterSize, dEmbedSum,
+                   stream=None):
+    return _chk(lib.rvq_ema_update(ctx, stage, _ptr(dR), _ptr(dCodes), code_stride, M, decay, eps,
+                                   _ptr(dClusterSize), _ptr(dEmbedSum), _stream(stream)), ctx)
+
+
+class Quantizer:
+    """Owns one rvq_ctx; thin convenience over the entry points above (allocation of outputs and
+    shape bookkeeping only)."""
+
+    def __init__(self, **cfg):
+        self.cfg = dict(d=None, dhat=32, depth=8, K=2048, grouping=CONTIGUOUS, scale=1, std_ddof=0,
+                        in_dtype=F32, out_dtype=F16, std_dtype=F16, encode_path=PATH_AUTO)
+        self.cfg.update(cfg)
+        self.ctx = rvq_create(**self.cfg)
+        self.G = self.cfg["d"] // self.cfg["dhat"]
+
+    def close(self):
+        if self.ctx is not None:
+            rvq_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def set_codebooks(self, C):
+        import torch
+        assert C.dtype == torch.float32 and C.is_cuda and C.is_contiguous()
+        assert tuple(C.shape) == (self.cfg["depth"], self.cfg["K"], self.cfg["dhat"])
+        rvq_set_codebooks(self.ctx, C)
+
+    def get_codebooks(self):
+        import torch
+        C = torch.empty((self.cfg["depth"], self.cfg["K"], self.cfg["dhat"]), dtype=torch.float32,
+                        device="cuda")
+        rvq_get_codebooks(self.ctx, C)
+        return C
+
+    def _std_torch_dtype(self):
+        import torch
+        return torch.float16 if self.cfg["std_dtype"] == F16 else torch.float32
+
+    def encode(self, X, want_residual=False, stages=None, codes=None):
+        import torch
+        N = X.shape[0]
+        depth = self.cfg["depth"]
+        sb, se = stages if stages is not None else (0, depth)
+        if codes is None:
+            codes = torch.empty((N, self.G, depth), dtype=torch.int16, device=X.device)
+        std = (torch.empty((N,), dtype=self._std_torch_dtype(), device=X.device)
+               if self.cfg["scale"] else None)
+        res = (torch.empty((N, self.G, self.cfg["dhat"]), dtype=torch.float32, device=X.device)
+               if want_residual else None)
+        rvq_encode(self.ctx, X, N, X.stride(0) if N else self.cfg["d"], sb, se, codes, std, res)
+        return codes, std, res
+
+    def decode(self, codes, std, depth_used=None, out=None):
+        import torch
+        N = codes.shape[0]
+        if out is None:
+            dt = torch.float16 if self.cfg["out_dtype"] == F16 else torch.float32
+            out = torch.empty((N, self.cfg["d"]), dtype=dt, device=codes.device)
+        rvq_decode(self.ctx, codes, std, N, depth_used or self.cfg["depth"], out,
+                   out.stride(0) if N else self.cfg["d"])
+        return out
+
+    def ema_update(self, stage, R, codes, cluster_size, embed_sum, decay=0.99, eps=1e-5,
+                   code_stride=1):
+        rvq_ema_update(self.ctx, stage, R, codes, code_stride, R.shape[0], decay, eps,
+                       cluster_size, embed_sum)

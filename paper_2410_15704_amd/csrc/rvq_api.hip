@@ -1,0 +1,180 @@
+// C-ABI entry points of librvq: argument validation, context management, kernel dispatch.
+// Every step of the method runs in the kernels of the other translation units; nothing here
+// does arithmetic of the method on the host.
+#include <new>
+
+#include "rvq_internal.h"
+
+namespace {
+
+bool valid_dtype(int32_t t) { return t == RVQ_F32 || t == RVQ_BF16 || t == RVQ_F16; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int validate_config(const rvq_config *c) {
+  if (!c) return RVQ_EINVAL;
+  if (c->dhat < 1 || c->dhat > 64) return RVQ_EINVAL;
+  if (c->d < c->dhat || c->d % c->dhat) return RVQ_EINVAL;
+  if (c->depth < 1 || c->depth > RVQ_MAX_DEPTH) return RVQ_EINVAL;
+  if (c->K < 1 || c->K > RVQ_MAX_K) return RVQ_EINVAL;
+  if (c->grouping != RVQ_CONTIGUOUS && c->grouping != RVQ_STRIDED) return RVQ_EINVAL;
+  if (c->scale != 0 && c->scale != 1) return RVQ_EINVAL;
+  if (c->std_ddof != 0 && c->std_ddof != 1) return RVQ_EINVAL;
+  if (c->d - c->std_ddof <= 0) return RVQ_EINVAL;
+  if (!valid_dtype(c->in_dtype)) return RVQ_EINVAL;
+  if (c->out_dtype != RVQ_F16 && c->out_dtype != RVQ_F32) return RVQ_EINVAL;
+  if (c->std_dtype != RVQ_F16 && c->std_dtype != RVQ_F32) return RVQ_EINVAL;
+  if (c->encode_path < RVQ_PATH_AUTO || c->encode_path > RVQ_PATH_SCREEN) return RVQ_EINVAL;
+  if (c->encode_path == RVQ_PATH_SCREEN && c->dhat != 32) return RVQ_EINVAL;
+  if (c->reserved != 0) return RVQ_EINVAL;
+  return RVQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int rvq_version(void) { return 1000; }
+
+const char *rvq_strerror(int code) {
+  switch (code) {
+    case RVQ_OK: return "ok";
+    case RVQ_EINVAL: return "invalid argument";
+    case RVQ_ENOCODEBOOK: return "codebooks have not been set";
+    case RVQ_EHIP: return "HIP runtime error";
+    case RVQ_ENOMEM: return "out of memory";
+    default: return "unknown error";
+  }
+}
+
+int rvq_last_hip_error(const rvq_ctx *ctx) { return ctx ? ctx->last_hip : 0; }
+
+int rvq_create(rvq_ctx **out, const rvq_config *cfg) {
+  if (!out) return RVQ_EINVAL;
+  *out = nullptr;
+  int rc = validate_config(cfg);
+  if (rc != RVQ_OK) return rc;
+  rvq_ctx *ctx = new (std::nothrow) rvq_ctx();
+  if (!ctx) return RVQ_ENOMEM;
+  ctx->cfg = *cfg;
+  ctx->G = cfg->d / cfg->dhat;
+  ctx->have_codebooks = false;
+  ctx->last_hip = 0;
+  ctx->C = nullptr;
+  ctx->norms = nullptr;
+  ctx->ws_std = nullptr;
+  ctx->ws_rows = 0;
+  ctx->ws_ema = nullptr;
+  ctx->ws_ema_bytes = 0;
+  hipError_t e = hipGetDevice(&ctx->device);
+  const size_t cb = (size_t)cfg->depth * cfg->K * cfg->dhat * sizeof(float);
+  if (e == hipSuccess) e = hipMalloc((void **)&ctx->C, cb);
+  if (e == hipSuccess) e = hipMalloc((void **)&ctx->norms, (size_t)cfg->depth * cfg->K * sizeof(float));
+  if (e == hipSuccess) {
+    ctx->ws_ema_bytes = rvq_ema_workspace_bytes(ctx);
+    e = hipMalloc((void **)&ctx->ws_ema, ctx->ws_ema_bytes);
+  }
+  if (e != hipSuccess) {
+    if (ctx->C) (void)hipFree(ctx->C);
+    if (ctx->norms) (void)hipFree(ctx->norms);
+    if (ctx->ws_ema) (void)hipFree(ctx->ws_ema);
+    delete ctx;
+    return e == hipErrorOutOfMemory ? RVQ_ENOMEM : RVQ_EHIP;
+  }
+  *out = ctx;
+  return RVQ_OK;
+}
+
+int rvq_destroy(rvq_ctx *ctx) {
+  if (!ctx) return RVQ_EINVAL;
+  (void)hipDeviceSynchronize();
+  if (ctx->C) (void)hipFree(ctx->C);
+  if (ctx->norms) (void)hipFree(ctx->norms);
+  if (ctx->ws_std) (void)hipFree(ctx->ws_std);
+  if (ctx->ws_ema) (void)hipFree(ctx->ws_ema);
+  delete ctx;
+  return RVQ_OK;
+}
+
+int rvq_set_codebooks(rvq_ctx *ctx, const float *dC, void *stream) {
+  if (!ctx || !dC || !aligned16(dC)) return RVQ_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  const size_t cb = (size_t)ctx->cfg.depth * ctx->cfg.K * ctx->cfg.dhat * sizeof(float);
+  RVQ_HIP(ctx, hipMemcpyAsync(ctx->C, dC, cb, hipMemcpyDeviceToDevice, s));
+  RVQ_HIP(ctx, rvq_launch_prepare_codebook(ctx, 0, ctx->cfg.depth, s));
+  ctx->have_codebooks = true;
+  return RVQ_OK;
+}
+
+int rvq_get_codebooks(rvq_ctx *ctx, float *dC, void *stream) {
+  if (!ctx || !dC || !aligned16(dC)) return RVQ_EINVAL;
+  if (!ctx->have_codebooks) return RVQ_ENOCODEBOOK;
+  const size_t cb = (size_t)ctx->cfg.depth * ctx->cfg.K * ctx->cfg.dhat * sizeof(float);
+  RVQ_HIP(ctx, hipMemcpyAsync(dC, ctx->C, cb, hipMemcpyDeviceToDevice, (hipStream_t)stream));
+  return RVQ_OK;
+}
+
+int rvq_encode(rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx, int32_t stage_begin,
+               int32_t stage_end, int16_t *dCodes, void *dStd, float *dResidual, void *stream) {
+  if (!ctx || N < 0) return RVQ_EINVAL;
+  const rvq_config &c = ctx->cfg;
+  if (stage_begin < 0 || stage_end > c.depth || stage_begin >= stage_end) return RVQ_EINVAL;
+  if (ldx < c.d) return RVQ_EINVAL;
+  if (N == 0) return ctx->have_codebooks ? RVQ_OK : RVQ_ENOCODEBOOK;
+  if (!dX || !dCodes || !aligned16(dX) || !aligned16(dCodes)) return RVQ_EINVAL;
+  if (c.scale && (!dStd || !aligned16(dStd))) return RVQ_EINVAL;
+  if (dResidual && !aligned16(dResidual)) return RVQ_EINVAL;
+  if (N > (INT64_MAX / 4) / ((int64_t)c.d > ldx ? c.d : ldx)) return RVQ_EINVAL;
+  if (!ctx->have_codebooks) return RVQ_ENOCODEBOOK;
+  hipStream_t s = (hipStream_t)stream;
+  if (c.scale) {
+    if (N > ctx->ws_rows) {
+      if (ctx->ws_std) RVQ_HIP(ctx, hipFree(ctx->ws_std));
+      ctx->ws_std = nullptr;
+      ctx->ws_rows = 0;
+      RVQ_HIP(ctx, hipMalloc((void **)&ctx->ws_std, (size_t)N * sizeof(float)));
+      ctx->ws_rows = N;
+    }
+    RVQ_HIP(ctx, rvq_launch_row_std(ctx, dX, N, ldx, dStd, s));
+  }
+  RVQ_HIP(ctx, rvq_launch_encode_exact(ctx, dX, N, ldx, stage_begin, stage_end, dCodes, dResidual, s));
+  return RVQ_OK;
+}
+
+int rvq_decode(rvq_ctx *ctx, const int16_t *dCodes, const void *dStd, int64_t N,
+               int32_t depth_used, void *dOut, int64_t ldo, void *stream) {
+  if (!ctx || N < 0) return RVQ_EINVAL;
+  const rvq_config &c = ctx->cfg;
+  if (depth_used < 1 || depth_used > c.depth) return RVQ_EINVAL;
+  if (ldo < c.d) return RVQ_EINVAL;
+  if (N == 0) return ctx->have_codebooks ? RVQ_OK : RVQ_ENOCODEBOOK;
+  if (!dCodes || !dOut || !aligned16(dCodes) || !aligned16(dOut)) return RVQ_EINVAL;
+  if (dStd && !aligned16(dStd)) return RVQ_EINVAL;
+  if (N > (INT64_MAX / 4) / ldo) return RVQ_EINVAL;
+  if (!ctx->have_codebooks) return RVQ_ENOCODEBOOK;
+  RVQ_HIP(ctx, rvq_launch_decode(ctx, dCodes, dStd, N, depth_used, dOut, ldo, (hipStream_t)stream));
+  return RVQ_OK;
+}
+
+int rvq_ema_update(rvq_ctx *ctx, int32_t stage, const float *dR, const int16_t *dCodes,
+                   int64_t code_stride, int64_t M, float decay, float eps, float *dClusterSize,
+                   float *dEmbedSum, void *stream) {
+  if (!ctx || M < 0) return RVQ_EINVAL;
+  const rvq_config &c = ctx->cfg;
+  if (stage < 0 || stage >= c.depth) return RVQ_EINVAL;
+  if (!(decay >= 0.0f && decay <= 1.0f) || !(eps >= 0.0f)) return RVQ_EINVAL;
+  if (code_stride < 1) return RVQ_EINVAL;
+  if (!dClusterSize || !dEmbedSum || !aligned16(dClusterSize) || !aligned16(dEmbedSum))
+    return RVQ_EINVAL;
+  if (M > 0 && (!dR || !dCodes || !aligned16(dR) || (reinterpret_cast<uintptr_t>(dCodes) & 1u)))
+    return RVQ_EINVAL;
+  if (M > INT64_MAX / 4 / (code_stride > c.dhat ? code_stride : c.dhat)) return RVQ_EINVAL;
+  if (!ctx->have_codebooks) return RVQ_ENOCODEBOOK;
+  if (M == 0) return RVQ_OK;
+  hipStream_t s = (hipStream_t)stream;
+  RVQ_HIP(ctx, rvq_launch_ema(ctx, stage, dR, dCodes, code_stride, M, decay, eps, dClusterSize,
+                              dEmbedSum, s));
+  RVQ_HIP(ctx, rvq_launch_prepare_codebook(ctx, stage, stage + 1, s));
+  return RVQ_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,199 @@
+// Decode (Section 2.2, last sentence): out[n][c(g,j)] = std[n] * sum_i C_i[code[n][g][i]][j].
+// The sum runs in stage order in fp32 and is rounded once to the output type.
+//
+// Row-gather kernel (dhat == 32): 8 lanes own one (token, group); each lane gathers one
+// 16-byte quarter... of the 128-byte codeword row per stage, so a codeword row is exactly one
+// cache line fetched once.  Contiguous grouping stores straight from registers (8 lanes write
+// 64 contiguous bytes of fp16).  Strided grouping puts element j of group g at channel
+// j * G + g, so a wavefront first assembles the whole token row in LDS (padded rows, so the 8
+// lanes that differ in j hit different banks) and then streams it out linearly.
+#include <type_traits>
+
+#include "rvq_internal.h"
+
+namespace {
+
+__device__ __forceinline__ int clamp_code(int k, int K) { return k < 0 ? 0 : (k >= K ? K - 1 : k); }
+
+__device__ __forceinline__ float load_std(const void *std_in, int std_dtype, int64_t n) {
+  if (!std_in) return 1.0f;
+  return std_dtype == RVQ_F32 ? ((const float *)std_in)[n]
+                              : rvq_f16_bits_to_f32(((const uint16_t *)std_in)[n]);
+}
+
+// ---- generic kernel: one thread per output channel, any dhat ------------------------------
+template <bool OUT_F16>
+__global__ __launch_bounds__(256) void decode_generic_kernel(
+    const int16_t *__restrict__ codes, const void *__restrict__ std_in, int std_dtype, int64_t N,
+    int d, int G, int dhat, int grouping, const float *__restrict__ C, int K, int depth,
+    int depth_used, void *__restrict__ out, int64_t ldo) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= N * d) return;
+  const int64_t n = e / d;
+  const int c = (int)(e - n * d);
+  int g, j;
+  if (grouping == RVQ_CONTIGUOUS) {
+    g = c / dhat;
+    j = c - g * dhat;
+  } else {
+    j = c / G;
+    g = c - j * G;
+  }
+  const int16_t *cg = codes + (n * G + g) * depth;
+  float acc = 0.f;
+  for (int i = 0; i < depth_used; ++i) {
+    const int k = clamp_code(cg[i], K);
+    acc += C[((int64_t)i * K + k) * dhat + j];
+  }
+  acc *= load_std(std_in, std_dtype, n);
+  if (OUT_F16) ((uint16_t *)out)[n * ldo + c] = __half_as_ushort(__float2half_rn(acc));
+  else ((float *)out)[n * ldo + c] = acc;
+}
+
+// ---- row-gather kernel, dhat == 32 -------------------------------------------------------
+constexpr int DEC_WAVES = 4;
+
+template <bool OUT_F16, bool STRIDED, int DEPTH8>
+__global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
+    const int16_t *__restrict__ codes, const void *__restrict__ std_in, int std_dtype, int64_t N,
+    int G, const float *__restrict__ C, int K, int depth, int depth_used, void *__restrict__ out,
+    int64_t ldo, int lds_row /* padded LDS row length in elements (strided only) */) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int p = lane >> 3;  // which of the 8 groups of this pass
+  const int q = lane & 7;   // which 4-channel quarter of the codeword
+  const int d = G * 32;
+  using out_t = typename std::conditional<OUT_F16, uint16_t, float>::type;
+  out_t *stage = reinterpret_cast<out_t *>(smem) + (size_t)wave * lds_row * 32;
+
+  const int64_t wave_global = (int64_t)blockIdx.x * DEC_WAVES + wave;
+  const int64_t wave_count = (int64_t)gridDim.x * DEC_WAVES;
+  for (int64_t n = wave_global; n < N; n += wave_count) {
+    const float sd = load_std(std_in, std_dtype, n);
+    for (int g0 = 0; g0 < G; g0 += 8) {
+      const int g = g0 + p;
+      float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (g < G) {
+        const int16_t *cg = codes + (n * G + g) * depth;
+        if (DEPTH8) {
+          const int4 w = *reinterpret_cast<const int4 *>(cg);
+          const int kk[8] = {(int16_t)(w.x & 0xffff), (int16_t)(w.x >> 16),
+                             (int16_t)(w.y & 0xffff), (int16_t)(w.y >> 16),
+                             (int16_t)(w.z & 0xffff), (int16_t)(w.z >> 16),
+                             (int16_t)(w.w & 0xffff), (int16_t)(w.w >> 16)};
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            if (i < depth_used) {
+              const int k = clamp_code(kk[i], K);
+              const float4 c4 =
+                  *reinterpret_cast<const float4 *>(C + ((int64_t)i * K + k) * 32 + q * 4);
+              acc.x += c4.x; acc.y += c4.y; acc.z += c4.z; acc.w += c4.w;
+            }
+          }
+        } else {
+          for (int i = 0; i < depth_used; ++i) {
+            const int k = clamp_code(cg[i], K);
+            const float4 c4 =
+                *reinterpret_cast<const float4 *>(C + ((int64_t)i * K + k) * 32 + q * 4);
+            acc.x += c4.x; acc.y += c4.y; acc.z += c4.z; acc.w += c4.w;
+          }
+        }
+        acc.x *= sd; acc.y *= sd; acc.z *= sd; acc.w *= sd;
+        if (!STRIDED) {
+          out_t *o = reinterpret_cast<out_t *>(out) + n * ldo + (int64_t)g * 32 + q * 4;
+          if (OUT_F16) {
+            uint2 pk;
+            pk.x = (uint32_t)__half_as_ushort(__float2half_rn(acc.x)) |
+                   ((uint32_t)__half_as_ushort(__float2half_rn(acc.y)) << 16);
+            pk.y = (uint32_t)__half_as_ushort(__float2half_rn(acc.z)) |
+                   ((uint32_t)__half_as_ushort(__float2half_rn(acc.w)) << 16);
+            *reinterpret_cast<uint2 *>(o) = pk;
+          } else {
+            *reinterpret_cast<float4 *>(o) = acc;
+          }
+        } else {
+          // element j = 4q + t of group g goes to channel j * G + g: LDS row j, column g
+          const float a[4] = {acc.x, acc.y, acc.z, acc.w};
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            const int j = q * 4 + t;
+            if (OUT_F16) stage[j * lds_row + g] = (out_t)__half_as_ushort(__float2half_rn(a[t]));
+            else stage[j * lds_row + g] = (out_t)a[t];
+          }
+        }
+      }
+    }
+    if (STRIDED) {
+      // the wavefront's own LDS writes are visible to its later reads (same wave, in order)
+      __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+      out_t *o = reinterpret_cast<out_t *>(out) + n * ldo;
+      if (OUT_F16) {
+        // two fp16 channels per lane per step (G is even on this path)
+        for (int c = lane * 2; c < d; c += 128) {
+          const int j = c / G, g = c - j * G;
+          const uint32_t v = *reinterpret_cast<const uint32_t *>(&stage[j * lds_row + g]);
+          *reinterpret_cast<uint32_t *>(o + c) = v;
+        }
+      } else {
+        for (int c = lane; c < d; c += 64) {
+          const int j = c / G, g = c - j * G;
+          o[c] = stage[j * lds_row + g];
+        }
+      }
+      __builtin_amdgcn_s_waitcnt(0xc07f);
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t rvq_launch_decode(const rvq_ctx *ctx, const int16_t *dCodes, const void *dStd,
+                             int64_t N, int depth_used, void *dOut, int64_t ldo, hipStream_t s) {
+  const rvq_config &c = ctx->cfg;
+  const bool f16 = c.out_dtype == RVQ_F16;
+  const int G = ctx->G;
+  const size_t osz = f16 ? 2 : 4;
+  const bool strided = c.grouping == RVQ_STRIDED && G > 1;
+  // padded LDS row: row stride of 4 rows must move by one 16-byte bank group (see header)
+  int lds_row = 0;
+  size_t lds_bytes = 0;
+  if (strided) {
+    const int per16 = (int)(16 / osz);  // elements per 16 bytes
+    lds_row = G + (f16 ? 2 : 1);
+    (void)per16;
+    lds_bytes = (size_t)DEC_WAVES * 32 * lds_row * osz;
+  }
+  const bool rows_ok = c.dhat == 32 && (ldo * osz) % 16 == 0 && (!strided || (G % 2 == 0 && lds_bytes <= 64 * 1024));
+  if (rows_ok) {
+    int64_t blocks = (N + DEC_WAVES - 1) / DEC_WAVES;
+    const int64_t cap = 256 * 16;  // enough waves to fill the chip; the kernel strides over rows
+    if (blocks > cap) blocks = cap;
+    const dim3 grid((unsigned)blocks), block(64 * DEC_WAVES);
+    const bool d8 = c.depth == 8;
+#define RVQ_LAUNCH_ROWS(F16, STR, D8)                                                            \
+  hipLaunchKernelGGL((decode_rows32_kernel<F16, STR, D8>), grid, block, lds_bytes, s, dCodes,   \
+                     dStd, c.std_dtype, N, G, ctx->C, c.K, c.depth, depth_used, dOut, ldo, lds_row)
+    if (f16) {
+      if (strided) { if (d8) RVQ_LAUNCH_ROWS(true, true, 1); else RVQ_LAUNCH_ROWS(true, true, 0); }
+      else { if (d8) RVQ_LAUNCH_ROWS(true, false, 1); else RVQ_LAUNCH_ROWS(true, false, 0); }
+    } else {
+      if (strided) { if (d8) RVQ_LAUNCH_ROWS(false, true, 1); else RVQ_LAUNCH_ROWS(false, true, 0); }
+      else { if (d8) RVQ_LAUNCH_ROWS(false, false, 1); else RVQ_LAUNCH_ROWS(false, false, 0); }
+    }
+#undef RVQ_LAUNCH_ROWS
+    return hipGetLastError();
+  }
+  const int64_t total = N * c.d;
+  const int64_t grid64 = (total + 255) / 256;
+  if (grid64 > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (f16)
+    hipLaunchKernelGGL(decode_generic_kernel<true>, dim3((unsigned)grid64), dim3(256), 0, s, dCodes,
+                       dStd, c.std_dtype, N, c.d, G, c.dhat, c.grouping, ctx->C, c.K, c.depth,
+                       depth_used, dOut, ldo);
+  else
+    hipLaunchKernelGGL(decode_generic_kernel<false>, dim3((unsigned)grid64), dim3(256), 0, s,
+                       dCodes, dStd, c.std_dtype, N, c.d, G, c.dhat, c.grouping, ctx->C, c.K,
+                       c.depth, depth_used, dOut, ldo);
+  return hipGetLastError();
+}
