@@ -1,0 +1,258 @@
+#!/usr/bin/env python3
+"""Benchmark of the RVQ hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-decode-stream] [--no-cpu]
+
+A step is one pass of the whole hot path over one batch of workload 2 (Llama-3-8B-like key
+projection: N=32768 rows x 1024 channels, bf16, strided groups of 32, depth 8, K=2048):
+    rvq_encode   per-row std, grouping, 8 stages of distance + argmin + residual update
+    rvq_decode   gather + sum + rescale of the codes just produced, fp16 out
+    rvq_ema_update  one moving-average update of codebook 0 from the batch's 1,048,576 scaled
+                 group vectors and their stage-0 codes (scatter + blend)
+Inputs are resident in HBM before the timed region.  One JSON line is printed:
+value = group vectors per second through the whole step; `roofline` describes the encode kernel
+(the dominant one) against the dense fp16/bf16 matrix-core peak; `decode_stream` is the decode
+kernel alone over workload 3 (64 slices of 524288 tokens, 85.97 GB of traffic) against the HBM
+peak; `cpu_baseline` is the fp64 oracle timed on the host cores on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_16BIT_TFLOPS = 2500.0  # MI355X dense bf16 / fp16 matrix-core peak
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
+
+W2 = dict(N=32768, d=1024, dhat=32, depth=8, K=2048)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-decode-stream", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--decode-slices", type=int, default=64)
+    ap.add_argument("--cpu-rows", type=int, default=8192)
+    ap.add_argument("--encode-path", type=int, default=0)
+    return ap.parse_args()
+
+
+class EventTimer:
+    """HIP events on torch's current stream (the stream every library call is enqueued on)."""
+
+    def __init__(self):
+        import torch
+        self.torch = torch
+        self.pairs = {}
+
+    def record(self, name, fn):
+        a = self.torch.cuda.Event(enable_timing=True)
+        b = self.torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        self.pairs.setdefault(name, []).append((a, b))
+
+    def mean_ms(self, name):
+        p = self.pairs.get(name, [])
+        return sum(a.elapsed_time(b) for a, b in p) / max(1, len(p))
+
+
+def run_steps(args):
+    import numpy as np
+    import torch
+
+    from paper_2410_15704_amd import binding as b
+    from paper_2410_15704_amd import synth, train
+
+    N, d, dhat, depth, K = (W2[k] for k in ("N", "d", "dhat", "depth", "K"))
+    G = d // dhat
+    V = N * G
+    Xb, _ = synth.llama_key(N, d)
+    dX = torch.from_numpy(Xb.view(np.int16)).cuda().view(torch.bfloat16)
+    # sample-initialised codebooks from the first 2048 rows, built by the library itself
+    Zhead = train.scaled_groups(dX[:2048], d=d, dhat=dhat, grouping=b.STRIDED, in_dtype=b.BF16)
+    C = train.sample_init_codebooks(Zhead, depth, K, seed=synth.BASE_SEED + 2)
+    del Zhead
+    Z = train.scaled_groups(dX, d=d, dhat=dhat, grouping=b.STRIDED, in_dtype=b.BF16)  # EMA input
+
+    q = b.Quantizer(d=d, dhat=dhat, depth=depth, K=K, grouping=b.STRIDED, in_dtype=b.BF16,
+                    out_dtype=b.F16, std_dtype=b.F16, encode_path=args.encode_path)
+    q.set_codebooks(C)
+    codes = torch.empty((N, G, depth), dtype=torch.int16, device="cuda")
+    std = torch.empty((N,), dtype=torch.float16, device="cuda")
+    out = torch.empty((N, d), dtype=torch.float16, device="cuda")
+    cs = torch.ones(K, dtype=torch.float32, device="cuda")
+    es = C[0].clone()
+
+    def enc():
+        b.rvq_encode(q.ctx, dX, N, d, 0, depth, codes, std, None)
+
+    def dec():
+        b.rvq_decode(q.ctx, codes, std, N, depth, out, d)
+
+    def ema():
+        b.rvq_ema_update(q.ctx, 0, Z, codes, depth, V, 0.99, 1e-5, cs, es)  # code of vector v: codes[v * depth]
+
+    for _ in range(args.warmup):
+        enc(); dec(); ema()
+    torch.cuda.synchronize()
+    tm = EventTimer()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        tm.record("encode", enc)
+        tm.record("decode", dec)
+        tm.record("ema", ema)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = wall * 1e3 / args.steps
+    enc_ms, dec_ms, ema_ms = tm.mean_ms("encode"), tm.mean_ms("decode"), tm.mean_ms("ema")
+    flops = 2.0 * dhat * K * depth * V  # 2 * dhat * K flop per vector and stage
+    enc_tflops = flops / (enc_ms * 1e-3) / 1e12
+    dec_bytes = N * (G * depth * 2 + 2 + d * 2)
+    ema_bytes = V * (dhat * 4 + 2)
+    res = dict(
+        ms_per_step=ms_step, vec_per_step=V,
+        breakdown=dict(
+            encode_ms=enc_ms, decode_ms=dec_ms, ema_update_ms=ema_ms,
+            encode_Mvec_s=V / (enc_ms * 1e-3) / 1e6,
+            encode_tflops=enc_tflops,
+            encode_frac_of_mfma_peak=enc_tflops / PEAK_MFMA_16BIT_TFLOPS,
+            decode_GBs=dec_bytes / (dec_ms * 1e-3) / 1e9,
+            decode_frac_of_hbm_peak=dec_bytes / (dec_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+            ema_GBs=ema_bytes / (ema_ms * 1e-3) / 1e9,
+        ),
+        roofline=dict(bound="mfma", achieved=enc_tflops, peak=PEAK_MFMA_16BIT_TFLOPS,
+                      unit="TFLOP/s", frac=enc_tflops / PEAK_MFMA_16BIT_TFLOPS, traffic=None,
+                      kernel="rvq_encode (all 8 stages, one launch per call)",
+                      flops_per_launch=flops, avg_launch_ms=enc_ms),
+    )
+    q.close()
+    del dX, Z, codes, std, out
+    torch.cuda.empty_cache()
+    return res
+
+
+def run_decode_stream(args):
+    """Workload 3: decode-time reconstruction of a whole KV cache, 64 (layer, K/V) slices of
+    16 x 32768 tokens x 1024 channels, int16 codes + fp16 std -> fp16."""
+    import torch
+
+    from paper_2410_15704_amd import binding as b
+    from paper_2410_15704_amd import synth
+
+    S = args.decode_slices
+    T, d, G, depth, K = 16 * 32768, 1024, 32, 8, 2048
+    need = S * T * (G * depth * 2 + 2 + d * 2) + (2 << 30)
+    free, _ = torch.cuda.mem_get_info()
+    if need > free:
+        S = max(1, int((free - (2 << 30)) // (T * (G * depth * 2 + 2 + d * 2))))
+    Cs = torch.from_numpy(synth.decode_codebooks(S)).cuda()
+    qs = []
+    for s in range(S):
+        q = b.Quantizer(d=d, dhat=32, depth=depth, K=K, out_dtype=b.F16, std_dtype=b.F16,
+                        grouping=b.STRIDED if s % 2 == 0 else b.CONTIGUOUS)
+        q.set_codebooks(Cs[s])
+        qs.append(q)
+    codes = [synth.uniform_codes_device(T, G, depth, K, "cuda", extra=100 + s) for s in range(S)]
+    std = torch.from_numpy(synth.decode_std_fp16(S * T)).cuda().view(S, T)
+    out = torch.empty((S, T, d), dtype=torch.float16, device="cuda")
+
+    def one_pass():
+        for s in range(S):
+            b.rvq_decode(qs[s].ctx, codes[s], std[s], T, depth, out[s], d)
+
+    one_pass()
+    torch.cuda.synchronize()
+    reps = 3
+    a = torch.cuda.Event(enable_timing=True)
+    z = torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        one_pass()
+    z.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(z) / reps
+    nbytes = S * T * (G * depth * 2 + 2 + d * 2)
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    for q in qs:
+        q.close()
+    return dict(workload="decode-time reconstruction, %d slices x 524288 tokens x 1024 ch" % S,
+                slices=S, ms_per_pass=ms, bytes_per_pass=nbytes, tokens_per_s=S * T / (ms * 1e-3),
+                roofline=dict(bound="hbm", achieved=gbs, peak=PEAK_HBM_GBS, unit="GB/s",
+                              frac=gbs / PEAK_HBM_GBS, traffic=None,
+                              kernel="rvq_decode", bytes_per_launch=nbytes / S,
+                              avg_launch_ms=ms / S))
+
+
+def run_cpu_baseline(args):
+    """The fp64 oracle, as it stands, on a bounded sample of workload 2 (encode + decode)."""
+    import numpy as np
+
+    import oracle
+    from paper_2410_15704_amd import synth
+
+    rows = args.cpu_rows
+    N, d, dhat, depth, K = (W2[k] for k in ("N", "d", "dhat", "depth", "K"))
+    Xb, _ = synth.llama_key(N, d, rows=slice(0, max(rows, 2048)))
+    Xw = synth.widen(Xb, "bf16")
+    Z = oracle.scaled_groups(Xw[:2048], dhat, oracle.STRIDED)
+    C = oracle.sample_init_codebooks(Z, depth, K, np.random.Generator(np.random.PCG64(2)))
+    C = C.astype(np.float32).astype(np.float64)
+    t0 = time.perf_counter()
+    r = oracle.encode(Xw[:rows], C, dhat, oracle.STRIDED)
+    t1 = time.perf_counter()
+    oracle.decode(r["codes"], r["std"], C, d, oracle.STRIDED)
+    t2 = time.perf_counter()
+    V = rows * (d // dhat)
+    return dict(value=V / (t2 - t0) / 1e6, unit="Mvec/s", cores=oracle.threads(), kind="oracle",
+                sample="first %d of 32768 rows of workload 2 (%d group vectors): oracle encode "
+                       "%.2f s + decode %.2f s" % (rows, V, t1 - t0, t2 - t1),
+                encode_Mvec_s=V / (t1 - t0) / 1e6)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (rows shard without communication; "
+              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    r = run_steps(args)
+    line = {
+        "metric": "RVQ encode+decode+EMA step throughput, dhat=32, depth 8, K=2048 "
+                  "(encode Mvec/s with matrix-core fraction, decode GB/s with HBM fraction inside)",
+        "value": r["vec_per_step"] / (r["ms_per_step"] * 1e-3) / 1e6,
+        "unit": "Mvec/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": r["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 (distances screened on fp16 matrix cores where that path is active)",
+        "data": "synthetic",
+        "config": {"workload": "workload 2: Llama-3-8B-like key projection, N=32768 x 1024 ch "
+                               "bf16, strided groups of 32, depth 8, K=2048; encode + decode + "
+                               "one EMA update of codebook 0 per step",
+                   "vectors_per_step": r["vec_per_step"], "encode_path": args.encode_path},
+        "breakdown": r["breakdown"],
+        "roofline": r["roofline"],
+    }
+    if not args.no_decode_stream:
+        line["decode_stream"] = run_decode_stream(args)
+    line["cpu_baseline"] = None if args.no_cpu else run_cpu_baseline(args)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,86 @@
+"""Codebook-learning drivers composed from the library's entry points (host loops only; all
+arithmetic of the method runs in librvq's kernels; torch is used for device memory, seeded index
+draws and row gathers).
+
+Section 3 of the paper: each codebook is initialised from "the corresponding inputs" (the paper
+runs k-means on the first batch; the synthetic workloads sample K distinct rows instead) and is
+then updated by an exponential moving average with decay 0.99.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as b
+
+
+def scaled_groups(X: torch.Tensor, *, d: int, dhat: int, grouping: int, in_dtype: int,
+                  scale: int = 1) -> torch.Tensor:
+    """The vectors Algorithm 1 receives, float32 [N*G][dhat]: obtained from rvq_encode itself as
+    the residual that a single all-zero codeword leaves."""
+    q = b.Quantizer(d=d, dhat=dhat, depth=1, K=1, grouping=grouping, in_dtype=in_dtype,
+                    scale=scale, std_dtype=b.F32)
+    q.set_codebooks(torch.zeros((1, 1, dhat), dtype=torch.float32, device=X.device))
+    _, _, res = q.encode(X, want_residual=True)
+    torch.cuda.synchronize()
+    q.close()
+    return res.view(-1, dhat)
+
+
+def sample_init_codebooks(Z: torch.Tensor, depth: int, K: int, seed: int,
+                          encode_path: int = b.PATH_AUTO) -> torch.Tensor:
+    """Stage-by-stage sample initialisation: codebook s = K distinct seeded rows of the vectors
+    entering stage s; they are then quantized with it (rvq_encode, one stage) and the residuals
+    go on to stage s + 1.  Z float32 [V][dhat] on the device.  Returns C [depth][K][dhat]."""
+    V, dhat = Z.shape
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(seed)
+    C = torch.zeros((depth, K, dhat), dtype=torch.float32, device=Z.device)
+    q = b.Quantizer(d=dhat, dhat=dhat, depth=depth, K=K, scale=0, encode_path=encode_path)
+    R = Z.contiguous()
+    codes = torch.empty((V, 1, depth), dtype=torch.int16, device=Z.device)
+    for s in range(depth):
+        pick = torch.randperm(V, generator=gen)[:K].sort().values.to(Z.device)
+        C[s] = R.index_select(0, pick)
+        q.set_codebooks(C)
+        _, _, res = q.encode(R, want_residual=True, stages=(s, s + 1), codes=codes)
+        R = res.view(V, dhat)
+    torch.cuda.synchronize()
+    q.close()
+    return C
+
+
+def ema_train_sequential(R0: torch.Tensor, depth: int, K: int, iters: int, decay: float,
+                         eps: float, seed: int, encode_path: int = b.PATH_AUTO, timers=None):
+    """Stage-by-stage residual training: for each stage, sample-initialise its codebook from the
+    vectors entering it, run `iters` rounds of (assign, moving-average update) with state
+    N_k = 1, M_k = C_k at the start, then assign once more and pass the residuals on.
+    R0 float32 [M][dhat].  Returns the learnt codebooks [depth][K][dhat]."""
+    M, dhat = R0.shape
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(seed)
+    q = b.Quantizer(d=dhat, dhat=dhat, depth=depth, K=K, scale=0, encode_path=encode_path)
+    C = torch.zeros((depth, K, dhat), dtype=torch.float32, device=R0.device)
+    codes = torch.empty((M, 1, depth), dtype=torch.int16, device=R0.device)
+    R = R0.contiguous()
+    for s in range(depth):
+        pick = torch.randperm(M, generator=gen)[:K].sort().values.to(R.device)
+        C[s] = R.index_select(0, pick)
+        q.set_codebooks(C)
+        cs = torch.ones(K, dtype=torch.float32, device=R.device)
+        es = C[s].clone()
+        for _ in range(iters):
+            if timers:
+                timers.start("assign")
+            q.encode(R, stages=(s, s + 1), codes=codes)
+            if timers:
+                timers.stop("assign")
+                timers.start("update")
+            b.rvq_ema_update(q.ctx, s, R, codes.data_ptr() + 2 * s, depth, M, decay, eps, cs, es)
+            if timers:
+                timers.stop("update")
+        _, _, res = q.encode(R, want_residual=True, stages=(s, s + 1), codes=codes)
+        R = res.view(M, dhat)
+        C = q.get_codebooks()
+    torch.cuda.synchronize()
+    q.close()
+    return C
