@@ -136,6 +136,16 @@ int rvq_ema_update(rvq_ctx *ctx, int32_t stage, const float *dR, const int16_t *
                    int64_t code_stride, int64_t M, float decay, float eps, float *dClusterSize,
                    float *dEmbedSum, void *stream);
 
+/*
+ * Statistics of the matrix-core encode path, accumulated since rvq_create (diagnostics; this
+ * call synchronizes the device).  host_out is HOST memory, 4 values:
+ *   [0] (token, stage) searches the fp16 screen could not settle and the whole wavefront redid
+ *       exactly in fp32, [1] codewords re-scored exactly in fp32, [2] 16-codeword groups
+ *       re-scored from LDS, [3] all (token, stage) searches (padding lanes of the last
+ *       workgroup included).
+ */
+int rvq_get_counters(rvq_ctx *ctx, int64_t *host_out);
+
 /* Text for an RVQ_E* code; the HIP error code of the last RVQ_EHIP on this context (0 if none). */
 const char *rvq_strerror(int code);
 int rvq_last_hip_error(const rvq_ctx *ctx);

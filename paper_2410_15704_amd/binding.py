@@ -19,7 +19,8 @@ PATH_AUTO, PATH_EXACT, PATH_SCREEN = 0, 1, 2
 DTYPES = {"fp32": F32, "bf16": BF16, "fp16": F16}
 
 EXPORTS = ("rvq_create", "rvq_destroy", "rvq_set_codebooks", "rvq_get_codebooks", "rvq_encode",
-           "rvq_decode", "rvq_ema_update", "rvq_strerror", "rvq_last_hip_error", "rvq_version")
+           "rvq_decode", "rvq_ema_update", "rvq_strerror", "rvq_last_hip_error", "rvq_version",
+           "rvq_get_counters")
 
 
 class rvq_config(ctypes.Structure):
@@ -42,6 +43,7 @@ def _load():
     lib.rvq_encode.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp, vp, vp]
     lib.rvq_decode.argtypes = [vp, vp, vp, i64, i32, vp, i64, vp]
     lib.rvq_ema_update.argtypes = [vp, i32, vp, vp, i64, i64, f32, f32, vp, vp, vp]
+    lib.rvq_get_counters.argtypes = [vp, ctypes.POINTER(ctypes.c_int64)]
     lib.rvq_strerror.argtypes = [ctypes.c_int]
     lib.rvq_strerror.restype = ctypes.c_char_p
     lib.rvq_last_hip_error.argtypes = [vp]
@@ -137,6 +139,12 @@ def rvq_ema_update(ctx, stage, dR, dCodes, code_stride, M, decay, eps, dClusterS
                    stream=None):
     return _chk(lib.rvq_ema_update(ctx, stage, _ptr(dR), _ptr(dCodes), code_stride, M, decay, eps,
                                    _ptr(dClusterSize), _ptr(dEmbedSum), _stream(stream)), ctx)
+
+
+def rvq_get_counters(ctx):
+    out = (ctypes.c_int64 * 4)()
+    _chk(lib.rvq_get_counters(ctx, out), ctx)
+    return dict(zip(("slow_searches", "exact_rescored", "groups_rescored", "searches"), list(out)))
 
 
 class Quantizer:

@@ -61,6 +61,19 @@ int rvq_create(rvq_ctx **out, const rvq_config *cfg) {
   ctx->last_hip = 0;
   ctx->C = nullptr;
   ctx->norms = nullptr;
+  ctx->C16 = nullptr;
+  ctx->normp = nullptr;
+  ctx->stats = nullptr;
+  ctx->groupA = nullptr;
+  ctx->perm = nullptr;
+  ctx->prep_tmp = nullptr;
+  ctx->dup = nullptr;
+  ctx->counters = nullptr;
+  ctx->Kpad = (cfg->K + 31) / 32 * 32;
+  ctx->tag_bits = 1;
+  while ((1 << ctx->tag_bits) < ctx->Kpad / 32) ++ctx->tag_bits;
+  // norm rounding 2^-24, fp32 accumulation of 33 terms <= 2^-17, tile tag 2^(bits-23), 25 % spare
+  ctx->kappa = 1.25f * (5.96e-8f + 7.63e-6f + (float)(1u << ctx->tag_bits) * 1.1920929e-7f + 1.2e-7f);
   ctx->ws_std = nullptr;
   ctx->ws_rows = 0;
   ctx->ws_ema = nullptr;
@@ -69,6 +82,17 @@ int rvq_create(rvq_ctx **out, const rvq_config *cfg) {
   const size_t cb = (size_t)cfg->depth * cfg->K * cfg->dhat * sizeof(float);
   if (e == hipSuccess) e = hipMalloc((void **)&ctx->C, cb);
   if (e == hipSuccess) e = hipMalloc((void **)&ctx->norms, (size_t)cfg->depth * cfg->K * sizeof(float));
+  if (e == hipSuccess && cfg->dhat == 32) {  // operands of the matrix-core screen
+    e = hipMalloc((void **)&ctx->C16, (size_t)cfg->depth * ctx->Kpad * 32 * sizeof(uint16_t));
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->normp, (size_t)cfg->depth * ctx->Kpad * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->stats, (size_t)cfg->depth * 8 * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->dup, (size_t)cfg->depth * cfg->K * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->groupA, (size_t)cfg->depth * (ctx->Kpad / 16) * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->perm, (size_t)cfg->depth * ctx->Kpad * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->prep_tmp, (size_t)cfg->depth * ctx->Kpad * 2 * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->counters, 4 * sizeof(unsigned long long));
+    if (e == hipSuccess) e = hipMemset(ctx->counters, 0, 4 * sizeof(unsigned long long));
+  }
   if (e == hipSuccess) {
     ctx->ws_ema_bytes = rvq_ema_workspace_bytes(ctx);
     e = hipMalloc((void **)&ctx->ws_ema, ctx->ws_ema_bytes);
@@ -76,6 +100,14 @@ int rvq_create(rvq_ctx **out, const rvq_config *cfg) {
   if (e != hipSuccess) {
     if (ctx->C) (void)hipFree(ctx->C);
     if (ctx->norms) (void)hipFree(ctx->norms);
+    if (ctx->C16) (void)hipFree(ctx->C16);
+    if (ctx->normp) (void)hipFree(ctx->normp);
+    if (ctx->stats) (void)hipFree(ctx->stats);
+    if (ctx->groupA) (void)hipFree(ctx->groupA);
+    if (ctx->perm) (void)hipFree(ctx->perm);
+    if (ctx->prep_tmp) (void)hipFree(ctx->prep_tmp);
+    if (ctx->dup) (void)hipFree(ctx->dup);
+    if (ctx->counters) (void)hipFree(ctx->counters);
     if (ctx->ws_ema) (void)hipFree(ctx->ws_ema);
     delete ctx;
     return e == hipErrorOutOfMemory ? RVQ_ENOMEM : RVQ_EHIP;
@@ -89,6 +121,14 @@ int rvq_destroy(rvq_ctx *ctx) {
   (void)hipDeviceSynchronize();
   if (ctx->C) (void)hipFree(ctx->C);
   if (ctx->norms) (void)hipFree(ctx->norms);
+  if (ctx->C16) (void)hipFree(ctx->C16);
+  if (ctx->normp) (void)hipFree(ctx->normp);
+  if (ctx->stats) (void)hipFree(ctx->stats);
+  if (ctx->groupA) (void)hipFree(ctx->groupA);
+  if (ctx->perm) (void)hipFree(ctx->perm);
+  if (ctx->prep_tmp) (void)hipFree(ctx->prep_tmp);
+  if (ctx->dup) (void)hipFree(ctx->dup);
+  if (ctx->counters) (void)hipFree(ctx->counters);
   if (ctx->ws_std) (void)hipFree(ctx->ws_std);
   if (ctx->ws_ema) (void)hipFree(ctx->ws_ema);
   delete ctx;
@@ -110,6 +150,16 @@ int rvq_get_codebooks(rvq_ctx *ctx, float *dC, void *stream) {
   if (!ctx->have_codebooks) return RVQ_ENOCODEBOOK;
   const size_t cb = (size_t)ctx->cfg.depth * ctx->cfg.K * ctx->cfg.dhat * sizeof(float);
   RVQ_HIP(ctx, hipMemcpyAsync(dC, ctx->C, cb, hipMemcpyDeviceToDevice, (hipStream_t)stream));
+  return RVQ_OK;
+}
+
+int rvq_get_counters(rvq_ctx *ctx, int64_t *host_out) {
+  if (!ctx || !host_out) return RVQ_EINVAL;
+  for (int i = 0; i < 4; ++i) host_out[i] = 0;
+  if (!ctx->counters) return RVQ_OK;
+  unsigned long long tmp[4];
+  RVQ_HIP(ctx, hipMemcpy(tmp, ctx->counters, sizeof(tmp), hipMemcpyDeviceToHost));
+  for (int i = 0; i < 4; ++i) host_out[i] = (int64_t)tmp[i];
   return RVQ_OK;
 }
 
@@ -136,7 +186,11 @@ int rvq_encode(rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx, int32_t sta
     }
     RVQ_HIP(ctx, rvq_launch_row_std(ctx, dX, N, ldx, dStd, s));
   }
-  RVQ_HIP(ctx, rvq_launch_encode_exact(ctx, dX, N, ldx, stage_begin, stage_end, dCodes, dResidual, s));
+  const bool screen = c.dhat == 32 && c.encode_path != RVQ_PATH_EXACT;
+  if (screen)
+    RVQ_HIP(ctx, rvq_launch_encode_screen(ctx, dX, N, ldx, stage_begin, stage_end, dCodes, dResidual, s));
+  else
+    RVQ_HIP(ctx, rvq_launch_encode_exact(ctx, dX, N, ldx, stage_begin, stage_end, dCodes, dResidual, s));
   return RVQ_OK;
 }
 

@@ -1,0 +1,430 @@
+// Matrix-core encode path (dhat == 32): Algorithm 1 with the nearest-codeword search of every
+// stage done in two steps that together give the exact fp32 answer.
+//
+//  1. Screen.  The search minimises ||c||^2 - 2 r.c over the codebook, a dense contraction
+//     [K x 32] . [32 x tokens].  It runs on the fp16 matrix cores (v_mfma_f32_32x32x16_f16,
+//     fp32 accumulate) with fp16(-2c) as the A operand, streamed from an LDS-resident copy of
+//     the stage's codebook, fp16(r) as the B operand and ||c||^2 as the accumulator input.
+//     Codewords sit on the rows of the 32x32 tile and tokens on its columns, so a lane holds 16
+//     scores of ONE token per tile and reduces them without leaving its registers.  Per lane
+//     and tile only the smallest score is kept (v_min3 tree), tagged with the tile number in
+//     its low mantissa bits, and merged into the three smallest tile minima seen so far.
+//  2. Resolve.  With dr = r - fp16(r) and rho the largest relative rounding error of the fp16
+//     codewords, |screen(k) - exact(k)| <= e_k = g ||2 c_k|| + (kappa/4) ||2 c_k||^2 + g0 where
+//     g = ||dr|| + (rho + kappa (1 + rho)) ||fp16(r)|| and g0 = ||fp16(r)|| * (norm of codeword
+//     elements too small for a normal half) depend on the token only (Cauchy-Schwarz on both
+//     rounding terms; kappa covers fp32 accumulation and the tag bits).  Codewords are
+//     stored in order of their norm, so the 16 codewords of a (tile, lane half) group share a
+//     tight bound e_g; the quantity that is tracked per group is the lower bound
+//     LB_g = (smallest screened score of the group) - e_g.  The exact winner lies in a group
+//     with LB_g <= UB, UB = LB + 2 e of the group with the smallest LB.  Those few groups are
+//     re-scored from the same LDS copy with packed fp16 dot products, and every codeword whose
+//     own lower bound is <= UB is scored exactly (fp32, direct form sum (r - c)^2, fp32
+//     codebook), ties going to the smallest index.  A token with more candidate groups in one
+//     lane than the three tracked ones, or whose residual does not fit fp16, is searched
+//     exactly by the whole wavefront instead.
+//
+// The residual stays in registers (fp32) across all stages and is updated with the fp32
+// codeword, so stages never round-trip through memory (the fusion Section 3 of the paper
+// describes for its own kernel).
+//
+// Work decomposition: one workgroup = 8 wavefronts x 4 token tiles x 32 tokens = 1024 group
+// vectors; LDS holds one stage (up to 2048 codewords = 128 KiB of fp16 operands + 8 KiB of
+// norms); larger codebooks are swept in chunks of 2048 with the resolve step run per chunk.
+// A token is split over the lane pair (p, p + 32): each lane owns 16 of its 32 channels.
+#include "rvq_internal.h"
+
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int SCR_WAVES = 8;
+constexpr int SCR_TT = 4;                              // token tiles per wavefront
+constexpr int SCR_TOKENS = SCR_WAVES * SCR_TT * 32;    // group vectors per workgroup
+constexpr int SCR_KC = 2048;                           // codewords resident in LDS
+constexpr size_t SCR_LDS_BYTES = (size_t)SCR_KC * 64 + (size_t)SCR_KC * 4 + (size_t)(SCR_KC / 16) * 4;
+constexpr float BIG = 3.0e38f;
+
+struct ScreenArgs {
+  const void *X;
+  const float *std32;
+  const float *C32;
+  const uint4 *C16;
+  const float *normp;
+  const float *groupA;
+  const int32_t *perm;
+  const float *stats;
+  int16_t *codes;
+  float *residual;
+  unsigned long long *counters;  // [0] token-stages searched by the wavefront, [1] codewords
+                                 // scored exactly, [2] groups re-scored, [3] token-stages
+  int64_t N, ldx, V;
+  int in_dtype, G, grouping, K, Kpad, depth, stage_begin, stage_end, tag_bits;
+  float kappa;
+};
+
+__device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, 64); }
+__device__ __forceinline__ int xor32i(int v) { return __shfl_xor(v, 32, 64); }
+
+__device__ __forceinline__ float min3f(float a, float b, float c) {
+  return __builtin_fminf(__builtin_fminf(a, b), c);  // one v_min3_f32
+}
+__device__ __forceinline__ float med3f(float a, float b, float c) {
+  return __builtin_amdgcn_fmed3f(a, b, c);
+}
+
+__device__ __forceinline__ float dot8(const uint4 w, const half8 b, float acc) {
+  const half8 a = __builtin_bit_cast(half8, w);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const half2v x = {a[2 * e], a[2 * e + 1]};
+    const half2v y = {b[2 * e], b[2 * e + 1]};
+    acc = __builtin_amdgcn_fdot2(x, y, acc, false);
+  }
+  return acc;
+}
+
+template <int DT>
+__global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const ScreenArgs a) {
+  extern __shared__ uint4 smem[];
+  uint4 *lds_A = smem;                                              // SCR_KC * 4 chunks of 16 B
+  float *lds_n = reinterpret_cast<float *>(smem + SCR_KC * 4);      // SCR_KC shifted norms
+  float *lds_g = lds_n + SCR_KC;                                    // SCR_KC / 16 group bounds
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int p = lane & 31;
+  const int h = lane >> 5;
+  const int64_t vbase = (int64_t)blockIdx.x * SCR_TOKENS + wave * (SCR_TT * 32);
+
+  // ---- load this lane's 16 channels of its 4 tokens, scaled by the row std (Section 2.2)
+  float r[SCR_TT][16];
+#pragma unroll
+  for (int tt = 0; tt < SCR_TT; ++tt) {
+    const int64_t v = vbase + tt * 32 + p;
+    const bool valid = v < a.V;
+    const int64_t n = valid ? v / a.G : 0;
+    const int g = valid ? (int)(v - n * a.G) : 0;
+    const float sd = (valid && a.std32) ? a.std32[n] : 1.0f;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const int dim = 16 * h + j;
+      const int64_t ch = a.grouping == RVQ_CONTIGUOUS ? (int64_t)g * 32 + dim : (int64_t)dim * a.G + g;
+      float x = 0.f;
+      if (valid) x = rvq_load_in<DT>(a.X, n * a.ldx + ch);
+      r[tt][j] = a.std32 ? x / sd : x;
+    }
+  }
+
+  const unsigned tag_mask = ~((1u << a.tag_bits) - 1u);
+  const float k4 = 0.125f * a.kappa;  // kappa * (S T ||c||^2) = k4 * ||S 2c||^2 with T = S / 2
+
+  for (int stage = a.stage_begin; stage < a.stage_end; ++stage) {
+    const float rho = a.stats[stage * 8 + 0];
+    const bool usable = a.stats[stage * 8 + 1] != 0.0f;
+    const float Fdrop = a.stats[stage * 8 + 2];
+    const float Tscale = a.stats[stage * 8 + 4];  // power of two applied to the residuals
+
+    // ---- fp16 B operands and the per-token error bound
+    half8 B[SCR_TT][2];
+    float g1[SCR_TT];     // token part of the error bound: e_k = g1 ||2c|| + k4 ||2c||^2 + g0
+    float g0[SCR_TT];     // ||fp16(r)|| * (largest norm of codeword elements dropped to zero)
+    bool slow[SCR_TT];    // token goes to the exact wavefront search
+    float bestd[SCR_TT];
+    int bestk[SCR_TT];
+#pragma unroll
+    for (int tt = 0; tt < SCR_TT; ++tt) {
+      float s_r = 0.f, s_q = 0.f, s_d = 0.f;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const float x = r[tt][j] * Tscale;  // exact
+        const _Float16 hx = fabsf(x) < 6.103515625e-5f ? (_Float16)0.f : (_Float16)x;
+        B[tt][j >> 3][j & 7] = hx;
+        const float xr = (float)hx;
+        const float dx = x - xr;  // exact
+        s_r = fmaf(x, x, s_r);
+        s_q = fmaf(xr, xr, s_q);
+        s_d = fmaf(dx, dx, s_d);
+      }
+      s_r += xor32(s_r);
+      s_q += xor32(s_q);
+      s_d += xor32(s_d);
+      const float nq = sqrtf(s_q) * 1.000001f;
+      const float nd = sqrtf(s_d) * 1.000001f;
+      g1[tt] = (nd + (rho + a.kappa * (1.0f + rho)) * nq) * 1.000001f;
+      g0[tt] = nq * Fdrop * 1.000001f;
+      slow[tt] = !usable || !(s_r < 3.6e9f);
+      bestd[tt] = INFINITY;
+      bestk[tt] = 0;
+    }
+
+    unsigned n_slow = 0, n_exact = 0, n_groups = 0;  // wave-uniform statistics
+    for (int cbase = 0; cbase < a.Kpad; cbase += SCR_KC) {
+      const int kc = min(SCR_KC, a.Kpad - cbase);
+      const int ntiles = kc >> 5;
+      // ---- stage the chunk's operands in LDS (linear copy, already in operand order)
+      __syncthreads();
+      {
+        const uint4 *src = a.C16 + ((int64_t)stage * a.Kpad + cbase) * 4;
+        for (int i = tid; i < kc * 4; i += 64 * SCR_WAVES) lds_A[i] = src[i];
+        const float *nsrc = a.normp + (int64_t)stage * a.Kpad + cbase;
+        for (int i = tid; i < kc; i += 64 * SCR_WAVES) lds_n[i] = nsrc[i];
+        const float *gsrc = a.groupA + ((int64_t)stage * a.Kpad + cbase) / 16;
+        for (int i = tid; i < kc / 16; i += 64 * SCR_WAVES) lds_g[i] = gsrc[i];
+      }
+      __syncthreads();
+
+      // ---- sweep: three smallest tagged group lower bounds per lane and token tile
+      float m1[SCR_TT], m2[SCR_TT], m3[SCR_TT];
+#pragma unroll
+      for (int tt = 0; tt < SCR_TT; ++tt) m1[tt] = m2[tt] = m3[tt] = BIG;
+      const int tile0 = cbase >> 5;
+      for (int t = 0; t < ntiles; ++t) {
+        const half8 a0 = __builtin_bit_cast(half8, lds_A[(t * 2 + 0) * 64 + lane]);
+        const half8 a1 = __builtin_bit_cast(half8, lds_A[(t * 2 + 1) * 64 + lane]);
+        f32x16 cn;
+        const f32x4 *np = reinterpret_cast<const f32x4 *>(lds_n + (t * 2 + h) * 16);
+#pragma unroll
+        for (int b4 = 0; b4 < 4; ++b4) {
+          const f32x4 w = np[b4];
+          cn[b4 * 4 + 0] = w[0]; cn[b4 * 4 + 1] = w[1]; cn[b4 * 4 + 2] = w[2]; cn[b4 * 4 + 3] = w[3];
+        }
+        const unsigned tile_id = (unsigned)(tile0 + t);
+        const float Ag = lds_g[t * 2 + h];
+#pragma unroll
+        for (int tt = 0; tt < SCR_TT; ++tt) {
+          f32x16 acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, B[tt][0], cn, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, B[tt][1], acc, 0, 0, 0);
+          float tau = min3f(acc[0], acc[1], acc[2]);
+          tau = min3f(tau, acc[3], acc[4]);
+          tau = min3f(tau, acc[5], acc[6]);
+          tau = min3f(tau, acc[7], acc[8]);
+          tau = min3f(tau, acc[9], acc[10]);
+          tau = min3f(tau, acc[11], acc[12]);
+          tau = min3f(tau, acc[13], acc[14]);
+          tau = fminf(tau, acc[15]);
+          tau = fmaf(-g1[tt], Ag, tau);  // lower bound on the exact scores of the group
+          tau = __uint_as_float((__float_as_uint(tau) & tag_mask) | tile_id);
+          m3[tt] = med3f(m2[tt], m3[tt], tau);
+          m2[tt] = med3f(m1[tt], m2[tt], tau);
+          m1[tt] = fminf(m1[tt], tau);
+        }
+      }
+
+      // ---- resolve the chunk: groups within the window -> candidates -> exact scores
+#pragma unroll
+      for (int tt = 0; tt < SCR_TT; ++tt) {
+        const float o1 = xor32(m1[tt]), o2 = xor32(m2[tt]), o3 = xor32(m3[tt]);
+        // upper bound on the exact minimum from my best group (LB + 2 e_g, 25 % spare), then
+        // the smaller of the two lanes' bounds
+        float thr;
+        {
+          int t1 = (int)(__float_as_uint(m1[tt]) & ~tag_mask) - tile0;
+          t1 = t1 < 0 ? 0 : (t1 >= ntiles ? ntiles - 1 : t1);
+          const float A1 = lds_g[t1 * 2 + h];
+          const float mine = m1[tt] + 2.5f * (g1[tt] * A1 + k4 * A1 * A1 + g0[tt]);
+          thr = fminf(mine, xor32(mine));
+        }
+        if (m3[tt] <= thr || o3 <= thr) slow[tt] = true;
+        const float ent[4] = {h ? o1 : m1[tt], h ? o2 : m2[tt], h ? m1[tt] : o1, h ? m2[tt] : o2};
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+          const int hh = it >> 1;  // which half of the lanes owned the group
+          const float val = ent[it];
+          const bool act = !slow[tt] && val <= thr && val < 1e37f;
+          if (!__any(act)) continue;
+          n_groups += __popcll(__ballot(act && h == 0));
+          int tl = (int)(__float_as_uint(val) & ~tag_mask) - tile0;
+          tl = tl < 0 ? 0 : (tl >= ntiles ? ntiles - 1 : tl);
+          // partial fp16 dot products of my 16 channels with the 16 rows of (tl, hh)
+          float part[16];
+#pragma unroll
+          for (int rr = 0; rr < 16; ++rr) {
+            const int m = 8 * (rr >> 2) + 4 * hh + (rr & 3);
+            const uint4 x0 = lds_A[(tl * 2 + 0) * 64 + h * 32 + m];
+            const uint4 x1 = lds_A[(tl * 2 + 1) * 64 + h * 32 + m];
+            part[rr] = dot8(x1, B[tt][1], dot8(x0, B[tt][0], 0.f));
+          }
+          // lane half h finishes rows 8 h .. 8 h + 7 of the group
+          unsigned mask = 0;
+          const f32x4 *np = reinterpret_cast<const f32x4 *>(lds_n + (tl * 2 + hh) * 16 + 8 * h);
+          const f32x4 n0 = np[0], n1 = np[1];
+          const float Agrp = lds_g[tl * 2 + hh];
+          const float shift = k4 * Agrp * Agrp;
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const float mine = h ? part[8 + u] : part[u];
+            const float send = h ? part[u] : part[8 + u];
+            const float nk = (u < 4 ? n0[u & 3] : n1[u & 3]) + shift;  // S T ||c||^2
+            const float al = 2.000002f * sqrtf(fmaxf(2.0f * nk, 0.f));  // ||S 2c|| (S / T = 2)
+            const float lb = mine + xor32(send) + nk - (g1[tt] * al + k4 * al * al);
+            if (act && lb <= thr) mask |= 1u << (8 * h + u);
+          }
+          unsigned todo = mask | (unsigned)xor32i((int)mask);
+          // exact fp32 score of every surviving codeword
+          while (__any(todo != 0)) {
+            const bool has = todo != 0;
+            n_exact += __popcll(__ballot(has && h == 0));
+            const int rr = has ? __ffs(todo) - 1 : 0;
+            todo &= todo - 1;
+            const int m = 8 * (rr >> 2) + 4 * hh + (rr & 3);
+            const int k = has ? a.perm[(int64_t)stage * a.Kpad + (tile0 + tl) * 32 + m] : -1;
+            const bool real = k >= 0 && k < a.K;
+            const f32x4 *crow = reinterpret_cast<const f32x4 *>(
+                a.C32 + ((int64_t)stage * a.K + (real ? k : 0)) * 32 + 16 * h);
+            float dist = 0.f;
+#pragma unroll
+            for (int c4 = 0; c4 < 4; ++c4) {
+              const f32x4 cw = crow[c4];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const float dlt = r[tt][c4 * 4 + e] - cw[e];
+                dist = fmaf(dlt, dlt, dist);
+              }
+            }
+            dist += xor32(dist);
+            if (real && (dist < bestd[tt] || (dist == bestd[tt] && k < bestk[tt]))) {
+              bestd[tt] = dist;
+              bestk[tt] = k;
+            }
+          }
+        }
+      }
+    }
+
+    // ---- exact search by the whole wavefront for the tokens the screen could not settle
+#pragma unroll
+    for (int tt = 0; tt < SCR_TT; ++tt) {
+      unsigned long long pending = __ballot(slow[tt] && h == 0);
+      n_slow += __popcll(pending);
+      while (pending) {
+        const int src = __ffsll((long long)pending) - 1;
+        pending &= pending - 1;
+        float rr32[32];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          rr32[j] = __shfl(r[tt][j], src, 64);
+          rr32[16 + j] = __shfl(r[tt][j], src + 32, 64);
+        }
+        float bd = INFINITY;
+        int bk = 0x7fffffff;
+        for (int k = lane; k < a.K; k += 64) {
+          const f32x4 *crow = reinterpret_cast<const f32x4 *>(a.C32 + ((int64_t)stage * a.K + k) * 32);
+          float dist = 0.f;
+#pragma unroll
+          for (int c4 = 0; c4 < 8; ++c4) {
+            const f32x4 cw = crow[c4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float dlt = rr32[c4 * 4 + e] - cw[e];
+              dist = fmaf(dlt, dlt, dist);
+            }
+          }
+          if (dist < bd) { bd = dist; bk = k; }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+          const float od = __shfl_xor(bd, o, 64);
+          const int ok = __shfl_xor(bk, o, 64);
+          if (od < bd || (od == bd && ok < bk)) { bd = od; bk = ok; }
+        }
+        if (lane == src || lane == src + 32) {
+          bestd[tt] = bd;
+          bestk[tt] = bk == 0x7fffffff ? 0 : bk;
+        }
+      }
+    }
+
+    if (lane == 0) {
+      atomicAdd(&a.counters[0], (unsigned long long)n_slow);
+      atomicAdd(&a.counters[1], (unsigned long long)n_exact);
+      atomicAdd(&a.counters[2], (unsigned long long)n_groups);
+      atomicAdd(&a.counters[3], (unsigned long long)(SCR_TT * 32));
+    }
+
+    // ---- emit the code and update the residual with the fp32 codeword (Algorithm 1)
+#pragma unroll
+    for (int tt = 0; tt < SCR_TT; ++tt) {
+      const int64_t v = vbase + tt * 32 + p;
+      int k = bestk[tt];
+      k = k < 0 ? 0 : (k >= a.K ? a.K - 1 : k);
+      if (v < a.V && h == 0) a.codes[v * a.depth + stage] = (int16_t)k;
+      const f32x4 *crow =
+          reinterpret_cast<const f32x4 *>(a.C32 + ((int64_t)stage * a.K + k) * 32 + 16 * h);
+#pragma unroll
+      for (int c4 = 0; c4 < 4; ++c4) {
+        const f32x4 cw = crow[c4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) r[tt][c4 * 4 + e] -= cw[e];
+      }
+    }
+  }
+
+  if (a.residual) {
+#pragma unroll
+    for (int tt = 0; tt < SCR_TT; ++tt) {
+      const int64_t v = vbase + tt * 32 + p;
+      if (v < a.V) {
+        f32x4 *dst = reinterpret_cast<f32x4 *>(a.residual + v * 32 + 16 * h);
+#pragma unroll
+        for (int c4 = 0; c4 < 4; ++c4) {
+          f32x4 w = {r[tt][c4 * 4 + 0], r[tt][c4 * 4 + 1], r[tt][c4 * 4 + 2], r[tt][c4 * 4 + 3]};
+          dst[c4] = w;
+        }
+      }
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t rvq_launch_encode_screen(const rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx,
+                                    int stage_begin, int stage_end, int16_t *dCodes,
+                                    float *dResidual, hipStream_t s) {
+  const rvq_config &c = ctx->cfg;
+  ScreenArgs a;
+  a.X = dX;
+  a.std32 = c.scale ? ctx->ws_std : nullptr;
+  a.C32 = ctx->C;
+  a.C16 = reinterpret_cast<const uint4 *>(ctx->C16);
+  a.normp = ctx->normp;
+  a.groupA = ctx->groupA;
+  a.perm = ctx->perm;
+  a.stats = ctx->stats;
+  a.kappa = ctx->kappa;
+  a.codes = dCodes;
+  a.residual = dResidual;
+  a.counters = ctx->counters;
+  a.N = N;
+  a.ldx = ldx;
+  a.V = N * ctx->G;
+  a.in_dtype = c.in_dtype;
+  a.G = ctx->G;
+  a.grouping = c.grouping;
+  a.K = c.K;
+  a.Kpad = ctx->Kpad;
+  a.depth = c.depth;
+  a.stage_begin = stage_begin;
+  a.stage_end = stage_end;
+  a.tag_bits = ctx->tag_bits;
+  const int64_t grid64 = (a.V + SCR_TOKENS - 1) / SCR_TOKENS;
+  if (grid64 > 0x7fffffffLL) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)grid64), block(64 * SCR_WAVES);
+  hipError_t e;
+#define RVQ_LAUNCH_SCREEN(DT)                                                                   \
+  e = hipFuncSetAttribute(reinterpret_cast<const void *>(&encode_screen_kernel<DT>),            \
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)SCR_LDS_BYTES);      \
+  if (e != hipSuccess) return e;                                                                \
+  hipLaunchKernelGGL(encode_screen_kernel<DT>, grid, block, SCR_LDS_BYTES, s, a)
+  switch (c.in_dtype) {
+    case RVQ_F32: RVQ_LAUNCH_SCREEN(RVQ_F32); break;
+    case RVQ_BF16: RVQ_LAUNCH_SCREEN(RVQ_BF16); break;
+    default: RVQ_LAUNCH_SCREEN(RVQ_F16); break;
+  }
+#undef RVQ_LAUNCH_SCREEN
+  return hipGetLastError();
+}

@@ -17,6 +17,23 @@ struct rvq_ctx {
   float *C;            // [depth][K][dhat] fp32 codebooks (the values Algorithm 1 uses)
   float *norms;        // [depth][K] squared norms, computed in fp64 and rounded once
 
+  // matrix-core screen operands (dhat == 32 only), K padded to Kpad = 32 * ceil(K / 32)
+  // Within a stage the codewords are ordered by norm ("position"), so that the 16 codewords a
+  // lane reduces together have similar norms and share a tight error bound.
+  uint16_t *C16;       // [depth][Kpad/32][2][64][8] fp16(-2 c), matrix-core A-operand order
+  float *normp;        // [depth][Kpad/32][2][16] ||c||^2 minus the group's second-order error
+                       //   term, in accumulator-register order
+  float *groupA;       // [depth][Kpad/16] largest ||2c|| of each (tile, half) group
+  int32_t *perm;       // [depth][Kpad] position -> codeword index (-1 for padding)
+  float *stats;        // [depth][8]: rounding-error bounds and scales of the fp16 operands
+  int32_t *dup;        // [depth][K] 1 if the codeword repeats an earlier one exactly
+  float *prep_tmp;     // [depth][Kpad][2] scratch of the preparation kernels
+  int32_t Kpad;
+  int32_t tag_bits;    // low mantissa bits that carry the tile number
+  float kappa;         // relative bound on accumulation + tagging error of a screened score
+
+  unsigned long long *counters;  // [4] statistics of the screen path since rvq_create
+
   float *ws_std;       // per-row fp32 std of the rows being encoded
   int64_t ws_rows;
   float *ws_ema;       // moving-average scratch: counts [K] + sums [K][dhat] (+ partials)
@@ -64,6 +81,9 @@ hipError_t rvq_launch_row_std(const rvq_ctx *ctx, const void *dX, int64_t N, int
 hipError_t rvq_launch_encode_exact(const rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx,
                                    int stage_begin, int stage_end, int16_t *dCodes,
                                    float *dResidual, hipStream_t s);
+hipError_t rvq_launch_encode_screen(const rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx,
+                                    int stage_begin, int stage_end, int16_t *dCodes,
+                                    float *dResidual, hipStream_t s);
 hipError_t rvq_launch_decode(const rvq_ctx *ctx, const int16_t *dCodes, const void *dStd,
                              int64_t N, int depth_used, void *dOut, int64_t ldo, hipStream_t s);
 hipError_t rvq_launch_ema(rvq_ctx *ctx, int stage, const float *dR, const int16_t *dCodes,
