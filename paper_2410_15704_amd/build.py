@@ -56,7 +56,8 @@ def build(force: bool = False, verbose: bool = True) -> str:
         if (not force and os.path.exists(obj)
                 and os.path.getmtime(obj) > max(os.path.getmtime(src), hdr_t)):
             continue
-        cmd = ["hipcc", *FLAGS, *EXTRA.get(name, []), *inc, "-c", src, "-o", obj]
+        cmd = ["hipcc", *FLAGS, *EXTRA.get(name, []), *os.environ.get("RVQ_EXTRA_FLAGS", "").split(),
+               *inc, "-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((cmd, subprocess.Popen(cmd, stderr=subprocess.PIPE, text=True)))

@@ -68,6 +68,7 @@ int rvq_create(rvq_ctx **out, const rvq_config *cfg) {
   ctx->perm = nullptr;
   ctx->prep_tmp = nullptr;
   ctx->dup = nullptr;
+  ctx->perm16 = nullptr;
   ctx->counters = nullptr;
   ctx->Kpad = (cfg->K + 31) / 32 * 32;
   ctx->tag_bits = 1;
@@ -89,9 +90,10 @@ int rvq_create(rvq_ctx **out, const rvq_config *cfg) {
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->dup, (size_t)cfg->depth * cfg->K * sizeof(int32_t));
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->groupA, (size_t)cfg->depth * (ctx->Kpad / 16) * sizeof(float));
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->perm, (size_t)cfg->depth * ctx->Kpad * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->perm16, (size_t)cfg->depth * ctx->Kpad * sizeof(uint16_t));
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->prep_tmp, (size_t)cfg->depth * ctx->Kpad * 2 * sizeof(float));
-    if (e == hipSuccess) e = hipMalloc((void **)&ctx->counters, 4 * sizeof(unsigned long long));
-    if (e == hipSuccess) e = hipMemset(ctx->counters, 0, 4 * sizeof(unsigned long long));
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->counters, 16 * sizeof(unsigned long long));
+    if (e == hipSuccess) e = hipMemset(ctx->counters, 0, 16 * sizeof(unsigned long long));
   }
   if (e == hipSuccess) {
     ctx->ws_ema_bytes = rvq_ema_workspace_bytes(ctx);
@@ -107,6 +109,7 @@ int rvq_create(rvq_ctx **out, const rvq_config *cfg) {
     if (ctx->perm) (void)hipFree(ctx->perm);
     if (ctx->prep_tmp) (void)hipFree(ctx->prep_tmp);
     if (ctx->dup) (void)hipFree(ctx->dup);
+    if (ctx->perm16) (void)hipFree(ctx->perm16);
     if (ctx->counters) (void)hipFree(ctx->counters);
     if (ctx->ws_ema) (void)hipFree(ctx->ws_ema);
     delete ctx;
@@ -128,6 +131,7 @@ int rvq_destroy(rvq_ctx *ctx) {
   if (ctx->perm) (void)hipFree(ctx->perm);
   if (ctx->prep_tmp) (void)hipFree(ctx->prep_tmp);
   if (ctx->dup) (void)hipFree(ctx->dup);
+  if (ctx->perm16) (void)hipFree(ctx->perm16);
   if (ctx->counters) (void)hipFree(ctx->counters);
   if (ctx->ws_std) (void)hipFree(ctx->ws_std);
   if (ctx->ws_ema) (void)hipFree(ctx->ws_ema);
@@ -157,9 +161,12 @@ int rvq_get_counters(rvq_ctx *ctx, int64_t *host_out) {
   if (!ctx || !host_out) return RVQ_EINVAL;
   for (int i = 0; i < 4; ++i) host_out[i] = 0;
   if (!ctx->counters) return RVQ_OK;
-  unsigned long long tmp[4];
+  unsigned long long tmp[16];
   RVQ_HIP(ctx, hipMemcpy(tmp, ctx->counters, sizeof(tmp), hipMemcpyDeviceToHost));
   for (int i = 0; i < 4; ++i) host_out[i] = (int64_t)tmp[i];
+#ifdef RVQ_PHASE_CLOCKS
+  for (int i = 4; i < 10; ++i) host_out[i] = (int64_t)tmp[i];  // debug builds: caller passes 16
+#endif
   return RVQ_OK;
 }
 

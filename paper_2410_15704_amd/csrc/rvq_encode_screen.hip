@@ -45,7 +45,8 @@ constexpr int SCR_WAVES = 8;
 constexpr int SCR_TT = 4;                              // token tiles per wavefront
 constexpr int SCR_TOKENS = SCR_WAVES * SCR_TT * 32;    // group vectors per workgroup
 constexpr int SCR_KC = 2048;                           // codewords resident in LDS
-constexpr size_t SCR_LDS_BYTES = (size_t)SCR_KC * 64 + (size_t)SCR_KC * 4 + (size_t)(SCR_KC / 16) * 4;
+constexpr size_t SCR_LDS_BYTES =
+    (size_t)SCR_KC * 64 + (size_t)SCR_KC * 4 + (size_t)(SCR_KC / 16) * 4 + (size_t)SCR_KC * 2;
 constexpr float BIG = 3.0e38f;
 
 struct ScreenArgs {
@@ -55,7 +56,7 @@ struct ScreenArgs {
   const uint4 *C16;
   const float *normp;
   const float *groupA;
-  const int32_t *perm;
+  const uint16_t *perm16;
   const float *stats;
   int16_t *codes;
   float *residual;
@@ -87,12 +88,40 @@ __device__ __forceinline__ float dot8(const uint4 w, const half8 b, float acc) {
   return acc;
 }
 
+#ifdef RVQ_PHASE_CLOCKS
+#define PHASE_MARK(i)                                            \
+  do {                                                           \
+    const long long now_ = wall_clock64();                       \
+    phase_acc[i] += now_ - phase_t;                              \
+    phase_t = now_;                                              \
+  } while (0)
+#else
+#define PHASE_MARK(i) do { } while (0)
+#endif
+
+// rotate a 4-entry per-token-tile array by one: lets a compact, non-unrolled loop work on entry
+// 0 four times instead of unrolling its body four times (the unrolled resolve code did not fit
+// the instruction cache)
+#define ROT4(x)         \
+  do {                  \
+    auto t_ = x[0];     \
+    x[0] = x[1];        \
+    x[1] = x[2];        \
+    x[2] = x[3];        \
+    x[3] = t_;          \
+  } while (0)
+
 template <int DT>
 __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const ScreenArgs a) {
+#ifdef RVQ_PHASE_CLOCKS
+  long long phase_acc[6] = {0, 0, 0, 0, 0, 0};
+  long long phase_t = wall_clock64();
+#endif
   extern __shared__ uint4 smem[];
   uint4 *lds_A = smem;                                              // SCR_KC * 4 chunks of 16 B
   float *lds_n = reinterpret_cast<float *>(smem + SCR_KC * 4);      // SCR_KC shifted norms
   float *lds_g = lds_n + SCR_KC;                                    // SCR_KC / 16 group bounds
+  uint16_t *lds_p = reinterpret_cast<uint16_t *>(lds_g + SCR_KC / 16);  // position -> codeword
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -103,6 +132,13 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
 
   // ---- load this lane's 16 channels of its 4 tokens, scaled by the row std (Section 2.2)
   float r[SCR_TT][16];
+#ifdef RVQ_DEBUG_DUMP
+  float dbg[SCR_TT][16];
+#pragma unroll
+  for (int tt = 0; tt < SCR_TT; ++tt)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) dbg[tt][j] = 0.f;
+#endif
 #pragma unroll
   for (int tt = 0; tt < SCR_TT; ++tt) {
     const int64_t v = vbase + tt * 32 + p;
@@ -120,6 +156,8 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
     }
   }
 
+  PHASE_MARK(0);  // input load
+  unsigned n_slow = 0, n_exact = 0, n_groups = 0, n_search = 0;  // wave-uniform statistics
   const unsigned tag_mask = ~((1u << a.tag_bits) - 1u);
   const float k4 = 0.125f * a.kappa;  // kappa * (S T ||c||^2) = k4 * ||S 2c||^2 with T = S / 2
 
@@ -130,20 +168,24 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
     const float Tscale = a.stats[stage * 8 + 4];  // power of two applied to the residuals
 
     // ---- fp16 B operands and the per-token error bound
-    half8 B[SCR_TT][2];
+    half8 B0[SCR_TT], B1[SCR_TT];
     float g1[SCR_TT];     // token part of the error bound: e_k = g1 ||2c|| + k4 ||2c||^2 + g0
     float g0[SCR_TT];     // ||fp16(r)|| * (largest norm of codeword elements dropped to zero)
-    bool slow[SCR_TT];    // token goes to the exact wavefront search
-    float bestd[SCR_TT];
-    int bestk[SCR_TT];
+    int slow[SCR_TT];     // token goes to the exact wavefront search
+    int nc[SCR_TT];                                       // candidates found for the token
+    unsigned cA[SCR_TT], cB[SCR_TT], cC[SCR_TT];          // up to twelve of them, 16 bits each
+    unsigned cD[SCR_TT], cE[SCR_TT], cF[SCR_TT];
 #pragma unroll
     for (int tt = 0; tt < SCR_TT; ++tt) {
+      nc[tt] = 0;
+      cA[tt] = cB[tt] = cC[tt] = cD[tt] = cE[tt] = cF[tt] = 0u;
       float s_r = 0.f, s_q = 0.f, s_d = 0.f;
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
         const float x = r[tt][j] * Tscale;  // exact
         const _Float16 hx = fabsf(x) < 6.103515625e-5f ? (_Float16)0.f : (_Float16)x;
-        B[tt][j >> 3][j & 7] = hx;
+        if (j < 8) B0[tt][j] = hx;
+        else B1[tt][j - 8] = hx;
         const float xr = (float)hx;
         const float dx = x - xr;  // exact
         s_r = fmaf(x, x, s_r);
@@ -157,33 +199,49 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
       const float nd = sqrtf(s_d) * 1.000001f;
       g1[tt] = (nd + (rho + a.kappa * (1.0f + rho)) * nq) * 1.000001f;
       g0[tt] = nq * Fdrop * 1.000001f;
-      slow[tt] = !usable || !(s_r < 3.6e9f);
-      bestd[tt] = INFINITY;
-      bestk[tt] = 0;
+#ifdef RVQ_FORCE_SLOW
+      slow[tt] = 1;
+#else
+      slow[tt] = (!usable || !(s_r < 3.6e9f)) ? 1 : 0;
+#endif
     }
 
-    unsigned n_slow = 0, n_exact = 0, n_groups = 0;  // wave-uniform statistics
+    PHASE_MARK(1);  // operand conversion
     for (int cbase = 0; cbase < a.Kpad; cbase += SCR_KC) {
       const int kc = min(SCR_KC, a.Kpad - cbase);
       const int ntiles = kc >> 5;
-      // ---- stage the chunk's operands in LDS (linear copy, already in operand order)
+      // ---- stage the chunk's operands in LDS: a linear copy (the global layout is already the
+      // operand order), moved by direct global->LDS loads so no registers are tied up
       __syncthreads();
       {
-        const uint4 *src = a.C16 + ((int64_t)stage * a.Kpad + cbase) * 4;
-        for (int i = tid; i < kc * 4; i += 64 * SCR_WAVES) lds_A[i] = src[i];
+        const char *src = reinterpret_cast<const char *>(a.C16 + ((int64_t)stage * a.Kpad + cbase) * 4);
+        char *dstb = reinterpret_cast<char *>(lds_A);
+        const int bytes = kc * 64;  // a multiple of 2048
+        for (int off = wave * 1024; off < bytes; off += SCR_WAVES * 1024)
+          __builtin_amdgcn_global_load_lds(
+              (const __attribute__((address_space(1))) void *)(src + off + lane * 16),
+              (__attribute__((address_space(3))) void *)(dstb + off), 16, 0, 0);
         const float *nsrc = a.normp + (int64_t)stage * a.Kpad + cbase;
         for (int i = tid; i < kc; i += 64 * SCR_WAVES) lds_n[i] = nsrc[i];
         const float *gsrc = a.groupA + ((int64_t)stage * a.Kpad + cbase) / 16;
         for (int i = tid; i < kc / 16; i += 64 * SCR_WAVES) lds_g[i] = gsrc[i];
+        const uint16_t *psrc = a.perm16 + (int64_t)stage * a.Kpad + cbase;
+        for (int i = tid; i < kc; i += 64 * SCR_WAVES) lds_p[i] = psrc[i];
+        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the direct loads have landed
       }
       __syncthreads();
+      PHASE_MARK(2);  // staging + barriers
 
       // ---- sweep: three smallest tagged group lower bounds per lane and token tile
       float m1[SCR_TT], m2[SCR_TT], m3[SCR_TT];
 #pragma unroll
       for (int tt = 0; tt < SCR_TT; ++tt) m1[tt] = m2[tt] = m3[tt] = BIG;
       const int tile0 = cbase >> 5;
+#ifdef RVQ_SKIP_SWEEP
+      for (int t = 0; t < 2; ++t) {
+#else
       for (int t = 0; t < ntiles; ++t) {
+#endif
         const half8 a0 = __builtin_bit_cast(half8, lds_A[(t * 2 + 0) * 64 + lane]);
         const half8 a1 = __builtin_bit_cast(half8, lds_A[(t * 2 + 1) * 64 + lane]);
         f32x16 cn;
@@ -197,8 +255,8 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
         const float Ag = lds_g[t * 2 + h];
 #pragma unroll
         for (int tt = 0; tt < SCR_TT; ++tt) {
-          f32x16 acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, B[tt][0], cn, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, B[tt][1], acc, 0, 0, 0);
+          f32x16 acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, B0[tt], cn, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, B1[tt], acc, 0, 0, 0);
           float tau = min3f(acc[0], acc[1], acc[2]);
           tau = min3f(tau, acc[3], acc[4]);
           tau = min3f(tau, acc[5], acc[6]);
@@ -215,155 +273,266 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
         }
       }
 
-      // ---- resolve the chunk: groups within the window -> candidates -> exact scores
-#pragma unroll
-      for (int tt = 0; tt < SCR_TT; ++tt) {
-        const float o1 = xor32(m1[tt]), o2 = xor32(m2[tt]), o3 = xor32(m3[tt]);
+      PHASE_MARK(3);  // sweep
+      // ---- resolve, step 1 (LDS only): the candidate codewords of every token of the chunk.
+      // The loop body always works on entry 0 of the per-tile arrays, which are rotated.
+#ifdef RVQ_SKIP_RESOLVE
+      for (int tt = 0; tt < SCR_TT; ++tt) { nc[tt] = 1; cA[tt] = __float_as_uint(m1[tt]) & 1023u; }
+      if (false)
+#endif
+#pragma unroll 1
+      for (int rot = 0; rot < SCR_TT; ++rot) {
+        const float o1 = xor32(m1[0]), o2 = xor32(m2[0]), o3 = xor32(m3[0]);
         // upper bound on the exact minimum from my best group (LB + 2 e_g, 25 % spare), then
         // the smaller of the two lanes' bounds
         float thr;
         {
-          int t1 = (int)(__float_as_uint(m1[tt]) & ~tag_mask) - tile0;
+          int t1 = (int)(__float_as_uint(m1[0]) & ~tag_mask) - tile0;
           t1 = t1 < 0 ? 0 : (t1 >= ntiles ? ntiles - 1 : t1);
           const float A1 = lds_g[t1 * 2 + h];
-          const float mine = m1[tt] + 2.5f * (g1[tt] * A1 + k4 * A1 * A1 + g0[tt]);
+          const float mine = m1[0] + 2.5f * (g1[0] * A1 + k4 * A1 * A1 + g0[0]);
           thr = fminf(mine, xor32(mine));
         }
-        if (m3[tt] <= thr || o3 <= thr) slow[tt] = true;
-        const float ent[4] = {h ? o1 : m1[tt], h ? o2 : m2[tt], h ? m1[tt] : o1, h ? m2[tt] : o2};
-#pragma unroll
+#ifdef RVQ_DEBUG_DUMP
+        if (stage == a.stage_begin) {
+          dbg[rot][0] = m1[0]; dbg[rot][1] = m2[0]; dbg[rot][2] = m3[0]; dbg[rot][3] = thr;
+          dbg[rot][4] = o1; dbg[rot][5] = g1[0]; dbg[rot][6] = g0[0]; dbg[rot][7] = (float)slow[0];
+        }
+#endif
+        if (m3[0] <= thr || o3 <= thr) slow[0] = 1;
+        // the token's four tracked groups, the best one first so that one pass settles almost
+        // every token; both lanes of the pair build the same list (half-0 entries a, half-1 b)
+        const float a1 = h ? o1 : m1[0], a2 = h ? o2 : m2[0];
+        const float b1 = h ? m1[0] : o1, b2 = h ? m2[0] : o2;
+        const bool afirst = a1 <= b1;
+#pragma unroll 1
         for (int it = 0; it < 4; ++it) {
-          const int hh = it >> 1;  // which half of the lanes owned the group
-          const float val = ent[it];
-          const bool act = !slow[tt] && val <= thr && val < 1e37f;
+          const int hh = (afirst ? it : it + 1) & 1;  // lane half that owned the group
+          const float va = it < 2 ? a1 : a2, vb = it < 2 ? b1 : b2;
+          const float val = hh ? vb : va;
+          const bool act = !slow[0] && val <= thr && val < 1e37f;
           if (!__any(act)) continue;
           n_groups += __popcll(__ballot(act && h == 0));
           int tl = (int)(__float_as_uint(val) & ~tag_mask) - tile0;
           tl = tl < 0 ? 0 : (tl >= ntiles ? ntiles - 1 : tl);
-          // partial fp16 dot products of my 16 channels with the 16 rows of (tl, hh)
-          float part[16];
-#pragma unroll
-          for (int rr = 0; rr < 16; ++rr) {
-            const int m = 8 * (rr >> 2) + 4 * hh + (rr & 3);
-            const uint4 x0 = lds_A[(tl * 2 + 0) * 64 + h * 32 + m];
-            const uint4 x1 = lds_A[(tl * 2 + 1) * 64 + h * 32 + m];
-            part[rr] = dot8(x1, B[tt][1], dot8(x0, B[tt][0], 0.f));
-          }
-          // lane half h finishes rows 8 h .. 8 h + 7 of the group
-          unsigned mask = 0;
-          const f32x4 *np = reinterpret_cast<const f32x4 *>(lds_n + (tl * 2 + hh) * 16 + 8 * h);
-          const f32x4 n0 = np[0], n1 = np[1];
+          // fp16 re-score of the 16 rows of group (tl, hh): every lane forms the partial dot
+          // product of its 16 channels with two rows per step, one that it finishes itself
+          // (rows 8 h .. 8 h + 7 of the group) and one that its partner lane finishes
+          const uint4 *rows0 = lds_A + (tl * 2 + 0) * 64 + h * 32 + 4 * hh;
+          const uint4 *rows1 = lds_A + (tl * 2 + 1) * 64 + h * 32 + 4 * hh;
+          const float *nrow = lds_n + (tl * 2 + hh) * 16 + 8 * h;
           const float Agrp = lds_g[tl * 2 + hh];
           const float shift = k4 * Agrp * Agrp;
-#pragma unroll
+          unsigned mask = 0;
+#pragma unroll 2
           for (int u = 0; u < 8; ++u) {
-            const float mine = h ? part[8 + u] : part[u];
-            const float send = h ? part[u] : part[8 + u];
-            const float nk = (u < 4 ? n0[u & 3] : n1[u & 3]) + shift;  // S T ||c||^2
+            const int mo = 8 * (u >> 2) + (u & 3);  // tile row of group row u, within 16 rows
+            const int mine_o = 16 * h + mo, send_o = 16 * (1 - h) + mo;
+            const float mine = dot8(rows1[mine_o], B1[0], dot8(rows0[mine_o], B0[0], 0.f));
+            const float send = dot8(rows1[send_o], B1[0], dot8(rows0[send_o], B0[0], 0.f));
+            const float nk = nrow[u] + shift;                           // S T ||c||^2
             const float al = 2.000002f * sqrtf(fmaxf(2.0f * nk, 0.f));  // ||S 2c|| (S / T = 2)
-            const float lb = mine + xor32(send) + nk - (g1[tt] * al + k4 * al * al);
+            const float lb = mine + xor32(send) + nk - (g1[0] * al + k4 * al * al);
             if (act && lb <= thr) mask |= 1u << (8 * h + u);
           }
           unsigned todo = mask | (unsigned)xor32i((int)mask);
-          // exact fp32 score of every surviving codeword
+          // append the survivors (as codeword indices) to the token's candidate list
           while (__any(todo != 0)) {
             const bool has = todo != 0;
-            n_exact += __popcll(__ballot(has && h == 0));
             const int rr = has ? __ffs(todo) - 1 : 0;
             todo &= todo - 1;
             const int m = 8 * (rr >> 2) + 4 * hh + (rr & 3);
-            const int k = has ? a.perm[(int64_t)stage * a.Kpad + (tile0 + tl) * 32 + m] : -1;
-            const bool real = k >= 0 && k < a.K;
-            const f32x4 *crow = reinterpret_cast<const f32x4 *>(
-                a.C32 + ((int64_t)stage * a.K + (real ? k : 0)) * 32 + 16 * h);
-            float dist = 0.f;
+            const unsigned kk = lds_p[tl * 32 + m];
+            // branch-free append: slot nc of the packed list, or the slow flag when it is full
+            const bool ok = has && kk < (unsigned)a.K;
+            const int n0 = nc[0];
+            const unsigned packed = kk << ((n0 & 1) * 16);
+            cA[0] |= (ok && (n0 >> 1) == 0) ? packed : 0u;
+            cB[0] |= (ok && (n0 >> 1) == 1) ? packed : 0u;
+            cC[0] |= (ok && (n0 >> 1) == 2) ? packed : 0u;
+            cD[0] |= (ok && (n0 >> 1) == 3) ? packed : 0u;
+            cE[0] |= (ok && (n0 >> 1) == 4) ? packed : 0u;
+            cF[0] |= (ok && (n0 >> 1) == 5) ? packed : 0u;
+            slow[0] |= (ok && n0 >= 12) ? 1 : 0;
+            nc[0] = n0 + (ok ? 1 : 0);
+          }
+        }
+        ROT4(m1); ROT4(m2); ROT4(m3); ROT4(g1); ROT4(g0); ROT4(slow); ROT4(nc);
+        ROT4(cA); ROT4(cB); ROT4(cC); ROT4(cD); ROT4(cE); ROT4(cF); ROT4(B0); ROT4(B1);
+      }
+    }
+
+    PHASE_MARK(4);  // resolve, LDS part
+    // ---- exact search by the whole wavefront for the tokens the screen could not settle
+    {
+      bool any_slow = false;
 #pragma unroll
-            for (int c4 = 0; c4 < 4; ++c4) {
-              const f32x4 cw = crow[c4];
+      for (int tt = 0; tt < SCR_TT; ++tt) {
+        if (nc[tt] == 0) slow[tt] = 1;
+        any_slow = any_slow || slow[tt];
+      }
+#ifdef RVQ_SKIP_SLOW
+      if (false) {
+#else
+      if (__any(any_slow)) {
+#endif
+#pragma unroll 1
+        for (int rot = 0; rot < SCR_TT; ++rot) {
+          unsigned long long pending = __ballot(slow[0] && h == 0);
+          n_slow += __popcll(pending);
+          while (pending) {
+            const int src = __ffsll((long long)pending) - 1;
+            pending &= pending - 1;
+            float rr32[32];
 #pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                const float dlt = r[tt][c4 * 4 + e] - cw[e];
-                dist = fmaf(dlt, dlt, dist);
+            for (int j = 0; j < 16; ++j) {
+              rr32[j] = __shfl(r[0][j], src, 64);
+              rr32[16 + j] = __shfl(r[0][j], src + 32, 64);
+            }
+            float bd = INFINITY;
+            int bk = 0x7fffffff;
+            for (int k0 = lane; k0 < a.K; k0 += 128) {  // two codewords per lane in flight
+              f32x4 cw[2][8];
+#pragma unroll
+              for (int q = 0; q < 2; ++q) {
+                const int k = min(k0 + 64 * q, a.K - 1);
+                const f32x4 *crow = reinterpret_cast<const f32x4 *>(a.C32 + ((int64_t)stage * a.K + k) * 32);
+#pragma unroll
+                for (int c4 = 0; c4 < 8; ++c4) cw[q][c4] = crow[c4];
+              }
+#pragma unroll
+              for (int q = 0; q < 2; ++q) {
+                const int k = k0 + 64 * q;
+                float dist = 0.f;
+#pragma unroll
+                for (int j = 0; j < 32; ++j) {
+                  const float dlt = rr32[j] - cw[q][j >> 2][j & 3];
+                  dist = fmaf(dlt, dlt, dist);
+                }
+                if (k < a.K && dist < bd) { bd = dist; bk = k; }
               }
             }
-            dist += xor32(dist);
-            if (real && (dist < bestd[tt] || (dist == bestd[tt] && k < bestk[tt]))) {
-              bestd[tt] = dist;
-              bestk[tt] = k;
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+              const float od = __shfl_xor(bd, o, 64);
+              const int ok = __shfl_xor(bk, o, 64);
+              if (od < bd || (od == bd && ok < bk)) { bd = od; bk = ok; }
             }
+            if (lane == src || lane == src + 32) {
+              // the single candidate of this token; step 2 below scores it like any other
+              cA[0] = bk == 0x7fffffff ? 0u : (unsigned)bk;
+              nc[0] = 1;
+            }
+          }
+          ROT4(slow); ROT4(nc); ROT4(cA);
+#pragma unroll
+          for (int j = 0; j < 16; ++j) {
+            const float t0 = r[0][j];
+            r[0][j] = r[1][j]; r[1][j] = r[2][j]; r[2][j] = r[3][j]; r[3][j] = t0;
           }
         }
       }
     }
 
-    // ---- exact search by the whole wavefront for the tokens the screen could not settle
+    float bestd[SCR_TT];
+    int bestk[SCR_TT];
+    // ---- resolve, step 2 (global): exact fp32 score of every candidate, sum (r - c)^2 with the
+    // fp32 codeword; slot s of all four tokens is loaded in one batch, and slots beyond the
+    // first only when some token of the wavefront has them
 #pragma unroll
     for (int tt = 0; tt < SCR_TT; ++tt) {
-      unsigned long long pending = __ballot(slow[tt] && h == 0);
-      n_slow += __popcll(pending);
-      while (pending) {
-        const int src = __ffsll((long long)pending) - 1;
-        pending &= pending - 1;
-        float rr32[32];
+      bestd[tt] = INFINITY;
+      bestk[tt] = 0;
+    }
+#pragma unroll 1
+    for (int slot = 0; slot < 12; ++slot) {
+      bool need = false;
+#pragma unroll
+      for (int tt = 0; tt < SCR_TT; ++tt) need = need || nc[tt] > slot;
+      if (!__any(need)) break;
+      f32x4 cw[SCR_TT][4];
+      int kk[SCR_TT];
+#pragma unroll
+      for (int tt = 0; tt < SCR_TT; ++tt) {
+        const unsigned w = slot < 2 ? cA[tt] : slot < 4 ? cB[tt] : slot < 6 ? cC[tt] : slot < 8 ? cD[tt] : slot < 10 ? cE[tt] : cF[tt];
+        const int cand = (int)((w >> ((slot & 1) * 16)) & 0xffffu);
+        kk[tt] = (nc[tt] > slot && cand < a.K) ? cand : 0;
+        const f32x4 *crow = reinterpret_cast<const f32x4 *>(
+            a.C32 + ((int64_t)stage * a.K + kk[tt]) * 32 + 16 * h);
+#pragma unroll
+        for (int c4 = 0; c4 < 4; ++c4) cw[tt][c4] = crow[c4];
+      }
+#pragma unroll
+      for (int tt = 0; tt < SCR_TT; ++tt) {
+        float dist = 0.f;
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-          rr32[j] = __shfl(r[tt][j], src, 64);
-          rr32[16 + j] = __shfl(r[tt][j], src + 32, 64);
+          const float dlt = r[tt][j] - cw[tt][j >> 2][j & 3];
+          dist = fmaf(dlt, dlt, dist);
         }
-        float bd = INFINITY;
-        int bk = 0x7fffffff;
-        for (int k = lane; k < a.K; k += 64) {
-          const f32x4 *crow = reinterpret_cast<const f32x4 *>(a.C32 + ((int64_t)stage * a.K + k) * 32);
-          float dist = 0.f;
-#pragma unroll
-          for (int c4 = 0; c4 < 8; ++c4) {
-            const f32x4 cw = crow[c4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const float dlt = rr32[c4 * 4 + e] - cw[e];
-              dist = fmaf(dlt, dlt, dist);
-            }
-          }
-          if (dist < bd) { bd = dist; bk = k; }
-        }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-          const float od = __shfl_xor(bd, o, 64);
-          const int ok = __shfl_xor(bk, o, 64);
-          if (od < bd || (od == bd && ok < bk)) { bd = od; bk = ok; }
-        }
-        if (lane == src || lane == src + 32) {
-          bestd[tt] = bd;
-          bestk[tt] = bk == 0x7fffffff ? 0 : bk;
+        dist += xor32(dist);
+        const bool valid = nc[tt] > slot;
+        n_exact += __popcll(__ballot(valid && h == 0));
+        if (valid && (dist < bestd[tt] || (dist == bestd[tt] && kk[tt] < bestk[tt]))) {
+          bestd[tt] = dist;
+          bestk[tt] = kk[tt];
         }
       }
     }
 
-    if (lane == 0) {
-      atomicAdd(&a.counters[0], (unsigned long long)n_slow);
-      atomicAdd(&a.counters[1], (unsigned long long)n_exact);
-      atomicAdd(&a.counters[2], (unsigned long long)n_groups);
-      atomicAdd(&a.counters[3], (unsigned long long)(SCR_TT * 32));
-    }
-
-    // ---- emit the code and update the residual with the fp32 codeword (Algorithm 1)
+#ifdef RVQ_DEBUG_DUMP
+    if (stage == a.stage_begin) {
 #pragma unroll
-    for (int tt = 0; tt < SCR_TT; ++tt) {
-      const int64_t v = vbase + tt * 32 + p;
-      int k = bestk[tt];
-      k = k < 0 ? 0 : (k >= a.K ? a.K - 1 : k);
-      if (v < a.V && h == 0) a.codes[v * a.depth + stage] = (int16_t)k;
-      const f32x4 *crow =
-          reinterpret_cast<const f32x4 *>(a.C32 + ((int64_t)stage * a.K + k) * 32 + 16 * h);
-#pragma unroll
-      for (int c4 = 0; c4 < 4; ++c4) {
-        const f32x4 cw = crow[c4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) r[tt][c4 * 4 + e] -= cw[e];
+      for (int tt = 0; tt < SCR_TT; ++tt) {
+        dbg[tt][8] = (float)nc[tt]; dbg[tt][9] = (float)(cA[tt] & 0xffff); dbg[tt][10] = (float)(cA[tt] >> 16);
+        dbg[tt][11] = (float)slow[tt]; dbg[tt][12] = bestd[tt]; dbg[tt][13] = (float)bestk[tt];
       }
     }
+#endif
+    n_search += SCR_TT * 32;
+
+    // ---- emit the code and subtract the fp32 codeword from the residual (Algorithm 1); the
+    // four rows are fetched in one batch
+    {
+      f32x4 cw[SCR_TT][4];
+#pragma unroll
+      for (int tt = 0; tt < SCR_TT; ++tt) {
+        const int64_t v = vbase + tt * 32 + p;
+        int k = bestk[tt];
+        k = k < 0 ? 0 : (k >= a.K ? a.K - 1 : k);
+        if (v < a.V && h == 0) a.codes[v * a.depth + stage] = (int16_t)k;
+        const f32x4 *crow =
+            reinterpret_cast<const f32x4 *>(a.C32 + ((int64_t)stage * a.K + k) * 32 + 16 * h);
+#pragma unroll
+        for (int c4 = 0; c4 < 4; ++c4) cw[tt][c4] = crow[c4];
+      }
+#pragma unroll
+      for (int tt = 0; tt < SCR_TT; ++tt)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) r[tt][j] -= cw[tt][j >> 2][j & 3];
+    }
+    PHASE_MARK(5);  // exact scores + code emit
   }
 
+  // statistics: one update per workgroup (the counters are shared by the whole grid)
+  {
+    __syncthreads();
+    unsigned *lds_c = reinterpret_cast<unsigned *>(smem);
+    if (tid < 4) lds_c[tid] = 0u;
+    __syncthreads();
+    if (lane == 0) {
+      atomicAdd(&lds_c[0], n_slow);
+      atomicAdd(&lds_c[1], n_exact);
+      atomicAdd(&lds_c[2], n_groups);
+      atomicAdd(&lds_c[3], n_search);
+    }
+    __syncthreads();
+    if (tid < 4) atomicAdd(&a.counters[tid], (unsigned long long)lds_c[tid]);
+  }
+#ifdef RVQ_PHASE_CLOCKS
+  if (lane == 0)
+    for (int i = 0; i < 6; ++i) atomicAdd(&a.counters[4 + i], (unsigned long long)phase_acc[i]);
+#endif
   if (a.residual) {
 #pragma unroll
     for (int tt = 0; tt < SCR_TT; ++tt) {
@@ -372,7 +541,11 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
         f32x4 *dst = reinterpret_cast<f32x4 *>(a.residual + v * 32 + 16 * h);
 #pragma unroll
         for (int c4 = 0; c4 < 4; ++c4) {
+#ifdef RVQ_DEBUG_DUMP
+          f32x4 w = {dbg[tt][c4 * 4 + 0], dbg[tt][c4 * 4 + 1], dbg[tt][c4 * 4 + 2], dbg[tt][c4 * 4 + 3]};
+#else
           f32x4 w = {r[tt][c4 * 4 + 0], r[tt][c4 * 4 + 1], r[tt][c4 * 4 + 2], r[tt][c4 * 4 + 3]};
+#endif
           dst[c4] = w;
         }
       }
@@ -393,7 +566,7 @@ hipError_t rvq_launch_encode_screen(const rvq_ctx *ctx, const void *dX, int64_t 
   a.C16 = reinterpret_cast<const uint4 *>(ctx->C16);
   a.normp = ctx->normp;
   a.groupA = ctx->groupA;
-  a.perm = ctx->perm;
+  a.perm16 = ctx->perm16;
   a.stats = ctx->stats;
   a.kappa = ctx->kappa;
   a.codes = dCodes;

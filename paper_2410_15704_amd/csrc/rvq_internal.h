@@ -25,6 +25,7 @@ struct rvq_ctx {
                        //   term, in accumulator-register order
   float *groupA;       // [depth][Kpad/16] largest ||2c|| of each (tile, half) group
   int32_t *perm;       // [depth][Kpad] position -> codeword index (-1 for padding)
+  uint16_t *perm16;    // the same, 0xffff for padding
   float *stats;        // [depth][8]: rounding-error bounds and scales of the fp16 operands
   int32_t *dup;        // [depth][K] 1 if the codeword repeats an earlier one exactly
   float *prep_tmp;     // [depth][Kpad][2] scratch of the preparation kernels

@@ -1,7 +1,8 @@
 // Derived codebook data.
 //   norms  : squared norms of the codewords, the constant term of ||c||^2 - 2 r.c
 // and, for the matrix-core screen (dhat == 32), per stage:
-//   perm   : the codewords ordered by norm (ties by index); position pos = tile * 32 + row
+//   perm   : the codewords ordered by norm (ties by index); position pos = tile * 32 + row;
+//            perm16 is the same as uint16 with 0xffff for padding (what the kernel keeps in LDS)
 //   C16    : fp16(-2 c) of the codeword at each position, laid out exactly as the A operand of
 //            v_mfma_f32_32x32x16_f16 is read, so the kernel copies it into LDS linearly and a
 //            lane's operand is one 16-byte LDS read
@@ -102,14 +103,15 @@ __global__ void rank_kernel(const float *__restrict__ norms, const int32_t *__re
 // ((t * 2 + q) * 64 + h * 32 + m).
 __global__ void screen_operands_kernel(const float *__restrict__ C, const int32_t *__restrict__ perm,
                                        int K, int Kpad, int stage_begin, int stage_end,
-                                       uint16_t *__restrict__ C16, float *__restrict__ tmp,
-                                       float *__restrict__ stats) {
+                                       uint16_t *__restrict__ C16, uint16_t *__restrict__ perm16,
+                                       float *__restrict__ tmp, float *__restrict__ stats) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t count = (int64_t)(stage_end - stage_begin) * Kpad;
   if (i >= count) return;
   const int stage = stage_begin + (int)(i / Kpad);
   const int pos = (int)(i % Kpad);
   const int k = perm[(int64_t)stage * Kpad + pos];
+  perm16[(int64_t)stage * Kpad + pos] = k < 0 ? (uint16_t)0xffff : (uint16_t)k;
   const int t = pos >> 5, m = pos & 31;
   uint16_t *dst = C16 + ((int64_t)stage * Kpad + (int64_t)t * 32) * 32;
   // S: power of two that brings the stage's largest |2c| into [2^13, 2^14); T = S / 2
@@ -195,8 +197,8 @@ hipError_t rvq_launch_prepare_codebook(const rvq_ctx *ctx, int stage_begin, int 
     hipLaunchKernelGGL(rank_kernel, blocks(ns * K), dim3(block), 0, s, ctx->norms, ctx->dup, (int)K,
                        ctx->Kpad, stage_begin, stage_end, ctx->perm);
     hipLaunchKernelGGL(screen_operands_kernel, blocks(np), dim3(block), 0, s, ctx->C, ctx->perm,
-                       (int)K, ctx->Kpad, stage_begin, stage_end, ctx->C16, ctx->prep_tmp,
-                       ctx->stats);
+                       (int)K, ctx->Kpad, stage_begin, stage_end, ctx->C16, ctx->perm16,
+                       ctx->prep_tmp, ctx->stats);
     hipLaunchKernelGGL(screen_groups_kernel, blocks(np / 16), dim3(block), 0, s, ctx->prep_tmp,
                        ctx->Kpad, stage_begin, stage_end, ctx->kappa, ctx->normp, ctx->groupA);
   }
