@@ -45,8 +45,10 @@ constexpr int SCR_WAVES = 8;
 constexpr int SCR_TT = 4;                              // token tiles per wavefront
 constexpr int SCR_TOKENS = SCR_WAVES * SCR_TT * 32;    // group vectors per workgroup
 constexpr int SCR_KC = 2048;                           // codewords resident in LDS
-constexpr size_t SCR_LDS_BYTES =
-    (size_t)SCR_KC * 64 + (size_t)SCR_KC * 4 + (size_t)(SCR_KC / 16) * 4 + (size_t)SCR_KC * 2;
+constexpr int SCR_CAND = 8;                            // candidate codewords kept per token
+constexpr size_t SCR_LDS_BYTES = (size_t)SCR_KC * 64 + (size_t)SCR_KC * 4 +
+                                 (size_t)(SCR_KC / 16) * 4 + (size_t)SCR_KC * 2 +
+                                 (size_t)SCR_TOKENS * SCR_CAND * 2;
 constexpr float BIG = 3.0e38f;
 
 struct ScreenArgs {
@@ -122,6 +124,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
   float *lds_n = reinterpret_cast<float *>(smem + SCR_KC * 4);      // SCR_KC shifted norms
   float *lds_g = lds_n + SCR_KC;                                    // SCR_KC / 16 group bounds
   uint16_t *lds_p = reinterpret_cast<uint16_t *>(lds_g + SCR_KC / 16);  // position -> codeword
+  uint16_t *lds_c = lds_p + SCR_KC;  // [token of the workgroup][SCR_CAND] candidate codewords
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -159,6 +162,8 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
   PHASE_MARK(0);  // input load
   unsigned n_slow = 0, n_exact = 0, n_groups = 0, n_search = 0;  // wave-uniform statistics
   const unsigned tag_mask = ~((1u << a.tag_bits) - 1u);
+  unsigned tag_mask_v = tag_mask;  // kept in a vector register: v_and_or_b32 takes one scalar only
+  asm volatile("" : "+v"(tag_mask_v));
   const float k4 = 0.125f * a.kappa;  // kappa * (S T ||c||^2) = k4 * ||S 2c||^2 with T = S / 2
 
   for (int stage = a.stage_begin; stage < a.stage_end; ++stage) {
@@ -172,13 +177,10 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
     float g1[SCR_TT];     // token part of the error bound: e_k = g1 ||2c|| + k4 ||2c||^2 + g0
     float g0[SCR_TT];     // ||fp16(r)|| * (largest norm of codeword elements dropped to zero)
     int slow[SCR_TT];     // token goes to the exact wavefront search
-    int nc[SCR_TT];                                       // candidates found for the token
-    unsigned cA[SCR_TT], cB[SCR_TT], cC[SCR_TT];          // up to twelve of them, 16 bits each
-    unsigned cD[SCR_TT], cE[SCR_TT], cF[SCR_TT];
+    int nc[SCR_TT];       // candidates found for the token (the list itself is in LDS)
 #pragma unroll
     for (int tt = 0; tt < SCR_TT; ++tt) {
       nc[tt] = 0;
-      cA[tt] = cB[tt] = cC[tt] = cD[tt] = cE[tt] = cF[tt] = 0u;
       float s_r = 0.f, s_q = 0.f, s_d = 0.f;
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
@@ -242,8 +244,11 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
 #else
       for (int t = 0; t < ntiles; ++t) {
 #endif
-        const half8 a0 = __builtin_bit_cast(half8, lds_A[(t * 2 + 0) * 64 + lane]);
-        const half8 a1 = __builtin_bit_cast(half8, lds_A[(t * 2 + 1) * 64 + lane]);
+        // the A operands: two 8-byte LDS reads each (16-byte reads run at half rate)
+        const uint2 *ap = reinterpret_cast<const uint2 *>(lds_A) + t * 256 + (lane ^ (t & 31));
+        const uint2 p00 = ap[0], p01 = ap[64], p10 = ap[128], p11 = ap[192];
+        const half8 a0 = __builtin_bit_cast(half8, make_uint4(p00.x, p00.y, p01.x, p01.y));
+        const half8 a1 = __builtin_bit_cast(half8, make_uint4(p10.x, p10.y, p11.x, p11.y));
         f32x16 cn;
         const f32x4 *np = reinterpret_cast<const f32x4 *>(lds_n + (t * 2 + h) * 16);
 #pragma unroll
@@ -266,7 +271,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
           tau = min3f(tau, acc[13], acc[14]);
           tau = fminf(tau, acc[15]);
           tau = fmaf(-g1[tt], Ag, tau);  // lower bound on the exact scores of the group
-          tau = __uint_as_float((__float_as_uint(tau) & tag_mask) | tile_id);
+          tau = __uint_as_float((__float_as_uint(tau) & tag_mask_v) | tile_id);
           m3[tt] = med3f(m2[tt], m3[tt], tau);
           m2[tt] = med3f(m1[tt], m2[tt], tau);
           m1[tt] = fminf(m1[tt], tau);
@@ -277,11 +282,12 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
       // ---- resolve, step 1 (LDS only): the candidate codewords of every token of the chunk.
       // The loop body always works on entry 0 of the per-tile arrays, which are rotated.
 #ifdef RVQ_SKIP_RESOLVE
-      for (int tt = 0; tt < SCR_TT; ++tt) { nc[tt] = 1; cA[tt] = __float_as_uint(m1[tt]) & 1023u; }
+      for (int tt = 0; tt < SCR_TT; ++tt) { nc[tt] = 1; lds_c[(wave * (SCR_TT * 32) + tt * 32 + p) * SCR_CAND] = __float_as_uint(m1[tt]) & 1023u; }
       if (false)
 #endif
 #pragma unroll 1
       for (int rot = 0; rot < SCR_TT; ++rot) {
+        uint16_t *cand_row = lds_c + (wave * (SCR_TT * 32) + rot * 32 + p) * SCR_CAND;
         const float o1 = xor32(m1[0]), o2 = xor32(m2[0]), o3 = xor32(m3[0]);
         // upper bound on the exact minimum from my best group (LB + 2 e_g, 25 % spare), then
         // the smaller of the two lanes' bounds
@@ -318,21 +324,45 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
           // fp16 re-score of the 16 rows of group (tl, hh): every lane forms the partial dot
           // product of its 16 channels with two rows per step, one that it finishes itself
           // (rows 8 h .. 8 h + 7 of the group) and one that its partner lane finishes
-          const uint4 *rows0 = lds_A + (tl * 2 + 0) * 64 + h * 32 + 4 * hh;
-          const uint4 *rows1 = lds_A + (tl * 2 + 1) * 64 + h * 32 + 4 * hh;
+          const uint2 *rows = reinterpret_cast<const uint2 *>(lds_A) + tl * 256 + h * 32;
+          const int swz = tl & 31;  // row m of tile tl is stored in slot m ^ swz
           const float *nrow = lds_n + (tl * 2 + hh) * 16 + 8 * h;
           const float Agrp = lds_g[tl * 2 + hh];
           const float shift = k4 * Agrp * Agrp;
+          // all reads of one half of the rows are issued before their dot products, and the
+          // eight partner partials are exchanged together: few dependent LDS round trips
+          float pm[8], ps[8];
+#pragma unroll
+          for (int qt = 0; qt < 4; ++qt) {  // two group rows per lane role and step
+            uint4 xm0[2], xm1[2], xs0[2], xs1[2];
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+              const int u = 2 * qt + q;
+              const int mo = 8 * (u >> 2) + (u & 3);  // tile row of group row u, within 16 rows
+              const uint2 *rm = rows + ((16 * h + 4 * hh + mo) ^ swz);
+              const uint2 *rs = rows + ((16 * (1 - h) + 4 * hh + mo) ^ swz);
+              xm0[q] = make_uint4(rm[0].x, rm[0].y, rm[64].x, rm[64].y);
+              xm1[q] = make_uint4(rm[128].x, rm[128].y, rm[192].x, rm[192].y);
+              xs0[q] = make_uint4(rs[0].x, rs[0].y, rs[64].x, rs[64].y);
+              xs1[q] = make_uint4(rs[128].x, rs[128].y, rs[192].x, rs[192].y);
+            }
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+              pm[2 * qt + q] = dot8(xm1[q], B1[0], dot8(xm0[q], B0[0], 0.f));
+              ps[2 * qt + q] = dot8(xs1[q], B1[0], dot8(xs0[q], B0[0], 0.f));
+            }
+          }
+          float po[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) po[u] = xor32(ps[u]);
+          const f32x4 nlo = *reinterpret_cast<const f32x4 *>(nrow);
+          const f32x4 nhi = *reinterpret_cast<const f32x4 *>(nrow + 4);
           unsigned mask = 0;
-#pragma unroll 2
+#pragma unroll
           for (int u = 0; u < 8; ++u) {
-            const int mo = 8 * (u >> 2) + (u & 3);  // tile row of group row u, within 16 rows
-            const int mine_o = 16 * h + mo, send_o = 16 * (1 - h) + mo;
-            const float mine = dot8(rows1[mine_o], B1[0], dot8(rows0[mine_o], B0[0], 0.f));
-            const float send = dot8(rows1[send_o], B1[0], dot8(rows0[send_o], B0[0], 0.f));
-            const float nk = nrow[u] + shift;                           // S T ||c||^2
-            const float al = 2.000002f * sqrtf(fmaxf(2.0f * nk, 0.f));  // ||S 2c|| (S / T = 2)
-            const float lb = mine + xor32(send) + nk - (g1[0] * al + k4 * al * al);
+            const float nk = (u < 4 ? nlo[u & 3] : nhi[u & 3]) + shift;   // S T ||c||^2
+            const float al = 2.000002f * sqrtf(fmaxf(2.0f * nk, 0.f));    // ||S 2c|| (S / T = 2)
+            const float lb = pm[u] + po[u] + nk - (g1[0] * al + k4 * al * al);
             if (act && lb <= thr) mask |= 1u << (8 * h + u);
           }
           unsigned todo = mask | (unsigned)xor32i((int)mask);
@@ -343,22 +373,16 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
             todo &= todo - 1;
             const int m = 8 * (rr >> 2) + 4 * hh + (rr & 3);
             const unsigned kk = lds_p[tl * 32 + m];
-            // branch-free append: slot nc of the packed list, or the slow flag when it is full
+            // append to the token's list in LDS, or raise the slow flag when it is full
             const bool ok = has && kk < (unsigned)a.K;
             const int n0 = nc[0];
-            const unsigned packed = kk << ((n0 & 1) * 16);
-            cA[0] |= (ok && (n0 >> 1) == 0) ? packed : 0u;
-            cB[0] |= (ok && (n0 >> 1) == 1) ? packed : 0u;
-            cC[0] |= (ok && (n0 >> 1) == 2) ? packed : 0u;
-            cD[0] |= (ok && (n0 >> 1) == 3) ? packed : 0u;
-            cE[0] |= (ok && (n0 >> 1) == 4) ? packed : 0u;
-            cF[0] |= (ok && (n0 >> 1) == 5) ? packed : 0u;
-            slow[0] |= (ok && n0 >= 12) ? 1 : 0;
+            if (ok && n0 < SCR_CAND && h == 0) cand_row[n0] = (uint16_t)kk;
+            slow[0] |= (ok && n0 >= SCR_CAND) ? 1 : 0;
             nc[0] = n0 + (ok ? 1 : 0);
           }
         }
         ROT4(m1); ROT4(m2); ROT4(m3); ROT4(g1); ROT4(g0); ROT4(slow); ROT4(nc);
-        ROT4(cA); ROT4(cB); ROT4(cC); ROT4(cD); ROT4(cE); ROT4(cF); ROT4(B0); ROT4(B1);
+        ROT4(B0); ROT4(B1);
       }
     }
 
@@ -420,11 +444,12 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
             }
             if (lane == src || lane == src + 32) {
               // the single candidate of this token; step 2 below scores it like any other
-              cA[0] = bk == 0x7fffffff ? 0u : (unsigned)bk;
+              if (lane == src)
+                lds_c[(wave * (SCR_TT * 32) + rot * 32 + src) * SCR_CAND] = (uint16_t)(bk == 0x7fffffff ? 0 : bk);
               nc[0] = 1;
             }
           }
-          ROT4(slow); ROT4(nc); ROT4(cA);
+          ROT4(slow); ROT4(nc);
 #pragma unroll
           for (int j = 0; j < 16; ++j) {
             const float t0 = r[0][j];
@@ -445,7 +470,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
       bestk[tt] = 0;
     }
 #pragma unroll 1
-    for (int slot = 0; slot < 12; ++slot) {
+    for (int slot = 0; slot < SCR_CAND; ++slot) {
       bool need = false;
 #pragma unroll
       for (int tt = 0; tt < SCR_TT; ++tt) need = need || nc[tt] > slot;
@@ -454,8 +479,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
       int kk[SCR_TT];
 #pragma unroll
       for (int tt = 0; tt < SCR_TT; ++tt) {
-        const unsigned w = slot < 2 ? cA[tt] : slot < 4 ? cB[tt] : slot < 6 ? cC[tt] : slot < 8 ? cD[tt] : slot < 10 ? cE[tt] : cF[tt];
-        const int cand = (int)((w >> ((slot & 1) * 16)) & 0xffffu);
+        const int cand = lds_c[(wave * (SCR_TT * 32) + tt * 32 + p) * SCR_CAND + slot];
         kk[tt] = (nc[tt] > slot && cand < a.K) ? cand : 0;
         const f32x4 *crow = reinterpret_cast<const f32x4 *>(
             a.C32 + ((int64_t)stage * a.K + kk[tt]) * 32 + 16 * h);
@@ -484,7 +508,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
     if (stage == a.stage_begin) {
 #pragma unroll
       for (int tt = 0; tt < SCR_TT; ++tt) {
-        dbg[tt][8] = (float)nc[tt]; dbg[tt][9] = (float)(cA[tt] & 0xffff); dbg[tt][10] = (float)(cA[tt] >> 16);
+        dbg[tt][8] = (float)nc[tt];
         dbg[tt][11] = (float)slow[tt]; dbg[tt][12] = bestd[tt]; dbg[tt][13] = (float)bestk[tt];
       }
     }

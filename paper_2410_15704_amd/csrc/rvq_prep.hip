@@ -99,8 +99,8 @@ __global__ void rank_kernel(const float *__restrict__ norms, const int32_t *__re
 }
 
 // One thread per (stage, position).  Operand order: tile t = pos / 32, row m = pos % 32; the
-// lane (m, h) of matrix-core instruction q holds dims 16 h + 8 q .. + 7 of row m, 16 bytes at
-// ((t * 2 + q) * 64 + h * 32 + m).
+// lane (m, h) of matrix-core instruction q holds dims 16 h + 8 q .. + 7 of row m, as two
+// 8-byte pieces at (((t * 2 + q) * 2 + piece) * 64 + h * 32 + m) * 8.
 __global__ void screen_operands_kernel(const float *__restrict__ C, const int32_t *__restrict__ perm,
                                        int K, int Kpad, int stage_begin, int stage_end,
                                        uint16_t *__restrict__ C16, uint16_t *__restrict__ perm16,
@@ -137,8 +137,13 @@ __global__ void screen_operands_kernel(const float *__restrict__ C, const int32_
     a2 += (double)a * a;
     if (flushed) f2 += (double)a * a;                             // absolute part of the error
     else e2 += ((double)back - a) * ((double)back - a);           // relative part
+    // the 16-byte operand of a lane is stored as two 8-byte pieces 512 bytes apart, so that the
+    // kernel fetches it with two conflict-free 8-byte LDS reads
     const int h = j >> 4, q = (j >> 3) & 1, e = j & 7;
-    dst[(((q * 64) + h * 32 + m) * 8) + e] = __half_as_ushort(hv);
+    // row m of tile t sits in slot m ^ (t & 31): the sweep still reads a permutation of all
+    // slots (no conflict), and lanes that fetch the same row of different tiles while re-scoring
+    // no longer collide on one LDS bank
+    dst[((((q * 2 + (e >> 2)) * 64) + h * 32 + (m ^ (t & 31))) * 4) + (e & 3)] = __half_as_ushort(hv);
   }
   float *o = tmp + ((int64_t)stage * Kpad + pos) * 2;
   if (k >= 0) {
