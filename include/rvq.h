@@ -130,7 +130,9 @@ int rvq_decode(rvq_ctx *ctx, const int16_t *dCodes, const void *dStd, int64_t N,
  *   dClusterSize device, float [K], in/out (N_k)
  *   dEmbedSum    device, float [K][dhat], in/out (M_k)
  * The new codebook replaces codebook `stage` inside the context (and its derived copies);
- * read it back with rvq_get_codebooks.
+ * read it back with rvq_get_codebooks.  The first call on a context allocates its scratch
+ * (per-code counts and sums plus the per-workgroup partial histograms, about
+ * 129 * K * (dhat + 1) * 4 bytes) with hipMalloc.
  */
 int rvq_ema_update(rvq_ctx *ctx, int32_t stage, const float *dR, const int16_t *dCodes,
                    int64_t code_stride, int64_t M, float decay, float eps, float *dClusterSize,

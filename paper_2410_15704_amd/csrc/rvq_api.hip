@@ -95,10 +95,6 @@ int rvq_create(rvq_ctx **out, const rvq_config *cfg) {
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->counters, 16 * sizeof(unsigned long long));
     if (e == hipSuccess) e = hipMemset(ctx->counters, 0, 16 * sizeof(unsigned long long));
   }
-  if (e == hipSuccess) {
-    ctx->ws_ema_bytes = rvq_ema_workspace_bytes(ctx);
-    e = hipMalloc((void **)&ctx->ws_ema, ctx->ws_ema_bytes);
-  }
   if (e != hipSuccess) {
     if (ctx->C) (void)hipFree(ctx->C);
     if (ctx->norms) (void)hipFree(ctx->norms);
@@ -232,6 +228,10 @@ int rvq_ema_update(rvq_ctx *ctx, int32_t stage, const float *dR, const int16_t *
   if (!ctx->have_codebooks) return RVQ_ENOCODEBOOK;
   if (M == 0) return RVQ_OK;
   hipStream_t s = (hipStream_t)stream;
+  if (!ctx->ws_ema) {  // scratch of the scatter step, allocated on first use
+    ctx->ws_ema_bytes = rvq_ema_workspace_bytes(ctx);
+    RVQ_HIP(ctx, hipMalloc((void **)&ctx->ws_ema, ctx->ws_ema_bytes));
+  }
   RVQ_HIP(ctx, rvq_launch_ema(ctx, stage, dR, dCodes, code_stride, M, decay, eps, dClusterSize,
                               dEmbedSum, s));
   RVQ_HIP(ctx, rvq_launch_prepare_codebook(ctx, stage, stage + 1, s));

@@ -13,6 +13,10 @@
 
 namespace {
 
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
 __device__ __forceinline__ int clamp_code(int k, int K) { return k < 0 ? 0 : (k >= K ? K - 1 : k); }
 
 __device__ __forceinline__ float load_std(const void *std_in, int std_dtype, int64_t n) {
@@ -77,7 +81,9 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
       if (g < G) {
         const int16_t *cg = codes + (n * G + g) * depth;
         if (DEPTH8) {
-          const int4 w = *reinterpret_cast<const int4 *>(cg);
+          // codes and outputs are streamed once: non-temporal accesses keep them from evicting
+          // the codebook rows, which every wavefront gathers again and again, from L2
+          const i32x4 w = __builtin_nontemporal_load(reinterpret_cast<const i32x4 *>(cg));
           const int kk[8] = {(int16_t)(w.x & 0xffff), (int16_t)(w.x >> 16),
                              (int16_t)(w.y & 0xffff), (int16_t)(w.y >> 16),
                              (int16_t)(w.z & 0xffff), (int16_t)(w.z >> 16),
@@ -108,9 +114,11 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
                    ((uint32_t)__half_as_ushort(__float2half_rn(acc.y)) << 16);
             pk.y = (uint32_t)__half_as_ushort(__float2half_rn(acc.z)) |
                    ((uint32_t)__half_as_ushort(__float2half_rn(acc.w)) << 16);
-            *reinterpret_cast<uint2 *>(o) = pk;
+            const u32x2 pkv = {pk.x, pk.y};
+            __builtin_nontemporal_store(pkv, reinterpret_cast<u32x2 *>(o));
           } else {
-            *reinterpret_cast<float4 *>(o) = acc;
+            const f32x4 av = {acc.x, acc.y, acc.z, acc.w};
+            __builtin_nontemporal_store(av, reinterpret_cast<f32x4 *>(o));
           }
         } else {
           // element j = 4q + t of group g goes to channel j * G + g: LDS row j, column g
@@ -133,18 +141,19 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
         for (int c = lane * 2; c < d; c += 128) {
           const int j = c / G, g = c - j * G;
           const uint32_t v = *reinterpret_cast<const uint32_t *>(&stage[j * lds_row + g]);
-          *reinterpret_cast<uint32_t *>(o + c) = v;
+          __builtin_nontemporal_store(v, reinterpret_cast<uint32_t *>(o + c));
         }
       } else {
         for (int c = lane; c < d; c += 64) {
           const int j = c / G, g = c - j * G;
-          o[c] = stage[j * lds_row + g];
+          __builtin_nontemporal_store(stage[j * lds_row + g], o + c);
         }
       }
       __builtin_amdgcn_s_waitcnt(0xc07f);
     }
   }
 }
+
 
 }  // namespace
 

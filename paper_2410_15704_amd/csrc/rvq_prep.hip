@@ -46,56 +46,63 @@ __global__ void prep_init_kernel(float *stats, int32_t *perm, int Kpad, int stag
   if (i < (stage_end - stage_begin) * 8) stats[stage_begin * 8 + i] = (i & 7) == 1 ? 1.0f : 0.0f;
 }
 
-// One thread per codeword: is it an exact repeat of an earlier codeword of its stage (flag in
+// One workgroup per codeword: is it an exact repeat of an earlier codeword of its stage (flag in
 // dup), and the stage's largest |2 c| (stats[5]); a non-finite element clears the usable flag.
-__global__ void dup_maxabs_kernel(const float *__restrict__ C, const float *__restrict__ norms,
-                                  int K, int stage_begin, int stage_end, int32_t *__restrict__ dup,
-                                  float *__restrict__ stats) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= (int64_t)(stage_end - stage_begin) * K) return;
-  const int stage = stage_begin + (int)(i / K);
-  const int k = (int)(i % K);
+__global__ __launch_bounds__(256) void dup_maxabs_kernel(const float *__restrict__ C,
+                                                         const float *__restrict__ norms, int K,
+                                                         int stage_begin, int32_t *__restrict__ dup,
+                                                         float *__restrict__ stats) {
+  __shared__ int found;
+  const int stage = stage_begin + blockIdx.x / K;
+  const int k = blockIdx.x % K;
   const float *n = norms + (int64_t)stage * K;
   const float *Cs = C + (int64_t)stage * K * 32;
-  float mx = 0.f;
-  bool finite = true;
-  for (int j = 0; j < 32; ++j) {
-    const float a = fabsf(2.0f * Cs[(int64_t)k * 32 + j]);
-    if (!(a <= 3.0e38f)) finite = false;
-    else mx = fmaxf(mx, a);
+  if (threadIdx.x == 0) found = 0;
+  if (threadIdx.x < 32) {  // one lane per channel of codeword k
+    const float a = fabsf(2.0f * Cs[(int64_t)k * 32 + threadIdx.x]);
+    const bool finite = a <= 3.0e38f;
+    float mx = finite ? a : 0.f;
+    for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+    if (!finite) stats[stage * 8 + 1] = 0.0f;
+    if (threadIdx.x == 0) atomic_max_pos(&stats[stage * 8 + 5], mx);
   }
-  if (!finite) stats[stage * 8 + 1] = 0.0f;
-  atomic_max_pos(&stats[stage * 8 + 5], mx);
+  __syncthreads();
   const float nk = n[k];
-  int d = 0;
-  for (int j = 0; j < k && !d; ++j) {
+  for (int j = threadIdx.x; j < k; j += blockDim.x) {
     if (n[j] != nk) continue;
     bool same = true;
     for (int e = 0; e < 32; ++e) same = same && Cs[(int64_t)j * 32 + e] == Cs[(int64_t)k * 32 + e];
-    if (same) d = 1;
+    if (same) found = 1;
   }
-  dup[(int64_t)stage * K + k] = d;
+  __syncthreads();
+  if (threadIdx.x == 0) dup[(int64_t)stage * K + k] = found;
 }
 
 // position of codeword k in the order (norm, index) among the codewords that are no repeats:
-// one thread per codeword counts the ones in front of it (K^2 comparisons per stage; runs once
-// per codebook upload)
-__global__ void rank_kernel(const float *__restrict__ norms, const int32_t *__restrict__ dup, int K,
-                            int Kpad, int stage_begin, int stage_end, int32_t *__restrict__ perm) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= (int64_t)(stage_end - stage_begin) * K) return;
-  const int stage = stage_begin + (int)(i / K);
-  const int k = (int)(i % K);
+// one workgroup per codeword counts the ones in front of it (K^2 comparisons per stage, spread
+// over K workgroups; runs once per codebook upload or update)
+__global__ __launch_bounds__(256) void rank_kernel(const float *__restrict__ norms,
+                                                   const int32_t *__restrict__ dup, int K, int Kpad,
+                                                   int stage_begin, int32_t *__restrict__ perm) {
+  __shared__ int part[256];
+  const int stage = stage_begin + blockIdx.x / K;
+  const int k = blockIdx.x % K;
   const float *n = norms + (int64_t)stage * K;
   const int32_t *dp = dup + (int64_t)stage * K;
-  if (dp[k]) return;
+  if (dp[k]) return;  // uniform over the workgroup
   const float nk = n[k];
-  int rank = 0;
-  for (int j = 0; j < K; ++j) {
+  int cnt = 0;
+  for (int j = threadIdx.x; j < K; j += blockDim.x) {
     const float nj = n[j];
-    rank += (!dp[j] && (nj < nk || (nj == nk && j < k))) ? 1 : 0;
+    cnt += (!dp[j] && (nj < nk || (nj == nk && j < k))) ? 1 : 0;
   }
-  perm[(int64_t)stage * Kpad + rank] = k;
+  part[threadIdx.x] = cnt;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) part[threadIdx.x] += part[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) perm[(int64_t)stage * Kpad + part[0]] = k;
 }
 
 // One thread per (stage, position).  Operand order: tile t = pos / 32, row m = pos % 32; the
@@ -197,10 +204,10 @@ hipError_t rvq_launch_prepare_codebook(const rvq_ctx *ctx, int stage_begin, int 
     const int64_t np = (int64_t)ns * ctx->Kpad;
     hipLaunchKernelGGL(prep_init_kernel, blocks(np), dim3(block), 0, s, ctx->stats, ctx->perm,
                        ctx->Kpad, stage_begin, stage_end);
-    hipLaunchKernelGGL(dup_maxabs_kernel, blocks(ns * K), dim3(block), 0, s, ctx->C, ctx->norms,
-                       (int)K, stage_begin, stage_end, ctx->dup, ctx->stats);
-    hipLaunchKernelGGL(rank_kernel, blocks(ns * K), dim3(block), 0, s, ctx->norms, ctx->dup, (int)K,
-                       ctx->Kpad, stage_begin, stage_end, ctx->perm);
+    hipLaunchKernelGGL(dup_maxabs_kernel, dim3((unsigned)(ns * K)), dim3(256), 0, s, ctx->C,
+                       ctx->norms, (int)K, stage_begin, ctx->dup, ctx->stats);
+    hipLaunchKernelGGL(rank_kernel, dim3((unsigned)(ns * K)), dim3(256), 0, s, ctx->norms, ctx->dup,
+                       (int)K, ctx->Kpad, stage_begin, ctx->perm);
     hipLaunchKernelGGL(screen_operands_kernel, blocks(np), dim3(block), 0, s, ctx->C, ctx->perm,
                        (int)K, ctx->Kpad, stage_begin, stage_end, ctx->C16, ctx->perm16,
                        ctx->prep_tmp, ctx->stats);
