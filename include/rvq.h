@@ -140,11 +140,12 @@ int rvq_ema_update(rvq_ctx *ctx, int32_t stage, const float *dR, const int16_t *
 
 /*
  * Statistics of the matrix-core encode path, accumulated since rvq_create (diagnostics; this
- * call synchronizes the device).  host_out is HOST memory, 4 values:
+ * call synchronizes the device).  host_out is HOST memory, 5 values:
  *   [0] (token, stage) searches the fp16 screen could not settle and the whole wavefront redid
  *       exactly in fp32, [1] codewords re-scored exactly in fp32, [2] 16-codeword groups
  *       re-scored from LDS, [3] all (token, stage) searches (padding lanes of the last
- *       workgroup included).
+ *       workgroup included), [4] searches with more candidates than the kernel's list holds,
+ *       settled by scoring every codeword of their candidate groups exactly.
  */
 int rvq_get_counters(rvq_ctx *ctx, int64_t *host_out);
 

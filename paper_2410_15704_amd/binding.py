@@ -144,7 +144,8 @@ def rvq_ema_update(ctx, stage, dR, dCodes, code_stride, M, decay, eps, dClusterS
 def rvq_get_counters(ctx):
     out = (ctypes.c_int64 * 16)()  # debug builds report more
     _chk(lib.rvq_get_counters(ctx, out), ctx)
-    return dict(zip(("slow_searches", "exact_rescored", "groups_rescored", "searches"), list(out)))
+    return dict(zip(("slow_searches", "exact_rescored", "groups_rescored", "searches",
+                     "group_exact_passes"), list(out)))
 
 
 class Quantizer:

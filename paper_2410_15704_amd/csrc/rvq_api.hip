@@ -88,7 +88,7 @@ int rvq_create(rvq_ctx **out, const rvq_config *cfg) {
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->normp, (size_t)cfg->depth * ctx->Kpad * sizeof(float));
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->stats, (size_t)cfg->depth * 8 * sizeof(float));
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->dup, (size_t)cfg->depth * cfg->K * sizeof(int32_t));
-    if (e == hipSuccess) e = hipMalloc((void **)&ctx->groupA, (size_t)cfg->depth * (ctx->Kpad / 16) * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->groupA, (size_t)cfg->depth * (ctx->Kpad / 16) * sizeof(float) + 64);  // + slack: read in 16-byte pieces
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->perm, (size_t)cfg->depth * ctx->Kpad * sizeof(int32_t));
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->perm16, (size_t)cfg->depth * ctx->Kpad * sizeof(uint16_t));
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->prep_tmp, (size_t)cfg->depth * ctx->Kpad * 2 * sizeof(float));
@@ -155,13 +155,14 @@ int rvq_get_codebooks(rvq_ctx *ctx, float *dC, void *stream) {
 
 int rvq_get_counters(rvq_ctx *ctx, int64_t *host_out) {
   if (!ctx || !host_out) return RVQ_EINVAL;
-  for (int i = 0; i < 4; ++i) host_out[i] = 0;
+  for (int i = 0; i < 5; ++i) host_out[i] = 0;
   if (!ctx->counters) return RVQ_OK;
   unsigned long long tmp[16];
   RVQ_HIP(ctx, hipMemcpy(tmp, ctx->counters, sizeof(tmp), hipMemcpyDeviceToHost));
   for (int i = 0; i < 4; ++i) host_out[i] = (int64_t)tmp[i];
+  host_out[4] = (int64_t)tmp[10];
 #ifdef RVQ_PHASE_CLOCKS
-  for (int i = 4; i < 10; ++i) host_out[i] = (int64_t)tmp[i];  // debug builds: caller passes 16
+  for (int i = 4; i < 10; ++i) host_out[i + 1] = (int64_t)tmp[i];  // debug builds: caller passes 16
 #endif
   return RVQ_OK;
 }

@@ -166,6 +166,26 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
   asm volatile("" : "+v"(tag_mask_v));
   const float k4 = 0.125f * a.kappa;  // kappa * (S T ||c||^2) = k4 * ||S 2c||^2 with T = S / 2
 
+  // asynchronous copy of one chunk of a stage's operands into LDS; every piece is a whole number
+  // of 16-byte lanes, a wavefront moves 1 KiB per instruction (lane i lands at base + 16 i)
+  auto stage_to_lds = [&](int st, int cb, int kcc) {
+    auto dma = [&](const void *gsrc, void *ldst, int bytes) {
+      const char *src = reinterpret_cast<const char *>(gsrc);
+      char *dstb = reinterpret_cast<char *>(ldst);
+      for (int off = wave * 1024; off < bytes; off += SCR_WAVES * 1024)
+        if (off + lane * 16 < bytes)
+          __builtin_amdgcn_global_load_lds(
+              (const __attribute__((address_space(1))) void *)(src + off + lane * 16),
+              (__attribute__((address_space(3))) void *)(dstb + off), 16, 0, 0);
+    };
+    dma(a.C16 + ((int64_t)st * a.Kpad + cb) * 4, lds_A, kcc * 64);
+    dma(a.normp + (int64_t)st * a.Kpad + cb, lds_n, kcc * 4);
+    dma(a.groupA + ((int64_t)st * a.Kpad + cb) / 16, lds_g, kcc / 4);
+    dma(a.perm16 + (int64_t)st * a.Kpad + cb, lds_p, kcc * 2);
+  };
+  const bool single_chunk = a.Kpad <= SCR_KC;
+  bool prefetched = false;
+
   for (int stage = a.stage_begin; stage < a.stage_end; ++stage) {
     const float rho = a.stats[stage * 8 + 0];
     const bool usable = a.stats[stage * 8 + 1] != 0.0f;
@@ -212,25 +232,15 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
     for (int cbase = 0; cbase < a.Kpad; cbase += SCR_KC) {
       const int kc = min(SCR_KC, a.Kpad - cbase);
       const int ntiles = kc >> 5;
-      // ---- stage the chunk's operands in LDS: a linear copy (the global layout is already the
-      // operand order), moved by direct global->LDS loads so no registers are tied up
-      __syncthreads();
-      {
-        const char *src = reinterpret_cast<const char *>(a.C16 + ((int64_t)stage * a.Kpad + cbase) * 4);
-        char *dstb = reinterpret_cast<char *>(lds_A);
-        const int bytes = kc * 64;  // a multiple of 2048
-        for (int off = wave * 1024; off < bytes; off += SCR_WAVES * 1024)
-          __builtin_amdgcn_global_load_lds(
-              (const __attribute__((address_space(1))) void *)(src + off + lane * 16),
-              (__attribute__((address_space(3))) void *)(dstb + off), 16, 0, 0);
-        const float *nsrc = a.normp + (int64_t)stage * a.Kpad + cbase;
-        for (int i = tid; i < kc; i += 64 * SCR_WAVES) lds_n[i] = nsrc[i];
-        const float *gsrc = a.groupA + ((int64_t)stage * a.Kpad + cbase) / 16;
-        for (int i = tid; i < kc / 16; i += 64 * SCR_WAVES) lds_g[i] = gsrc[i];
-        const uint16_t *psrc = a.perm16 + (int64_t)stage * a.Kpad + cbase;
-        for (int i = tid; i < kc; i += 64 * SCR_WAVES) lds_p[i] = psrc[i];
-        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the direct loads have landed
+      // ---- stage the chunk's operands in LDS: linear copies (the global layouts are already
+      // what the kernel reads), moved by direct global->LDS loads so no registers are tied up.
+      // With a single chunk per stage the copy for this stage was already started right after
+      // the previous stage stopped reading LDS and has been running behind its exact scoring.
+      if (!(prefetched && cbase == 0)) {
+        __syncthreads();
+        stage_to_lds(stage, cbase, kc);
       }
+      __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's direct loads have landed
       __syncthreads();
       PHASE_MARK(2);  // staging + barriers
 
@@ -311,13 +321,24 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
         const float a1 = h ? o1 : m1[0], a2 = h ? o2 : m2[0];
         const float b1 = h ? m1[0] : o1, b2 = h ? m2[0] : o2;
         const bool afirst = a1 <= b1;
-#pragma unroll 1
-        for (int it = 0; it < 4; ++it) {
+        // entries within the window, as a per-lane bit mask; every pass lets each token work
+        // on its next pending entry, so the number of passes is the largest number of pending
+        // groups of any token of the tile (almost always 1 or 2), not the number of entries
+        const float e0 = afirst ? a1 : b1, e1 = afirst ? b1 : a1;
+        const float e2 = afirst ? a2 : b2, e3 = afirst ? b2 : a2;
+        unsigned pend = 0;
+        bool over = false;  // more candidates than the list in LDS holds
+        if (!slow[0]) {
+          pend = (e0 <= thr && e0 < 1e37f ? 1u : 0u) | (e1 <= thr && e1 < 1e37f ? 2u : 0u) |
+                 (e2 <= thr && e2 < 1e37f ? 4u : 0u) | (e3 <= thr && e3 < 1e37f ? 8u : 0u);
+        }
+        const unsigned pend0 = pend;
+        while (__any(pend != 0)) {
+          const bool act = pend != 0 && !slow[0];
+          const int it = act ? __ffs(pend) - 1 : 0;
+          pend &= pend - 1;
           const int hh = (afirst ? it : it + 1) & 1;  // lane half that owned the group
-          const float va = it < 2 ? a1 : a2, vb = it < 2 ? b1 : b2;
-          const float val = hh ? vb : va;
-          const bool act = !slow[0] && val <= thr && val < 1e37f;
-          if (!__any(act)) continue;
+          const float val = it == 0 ? e0 : (it == 1 ? e1 : (it == 2 ? e2 : e3));
           n_groups += __popcll(__ballot(act && h == 0));
           int tl = (int)(__float_as_uint(val) & ~tag_mask) - tile0;
           tl = tl < 0 ? 0 : (tl >= ntiles ? ntiles - 1 : tl);
@@ -361,7 +382,8 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
 #pragma unroll
           for (int u = 0; u < 8; ++u) {
             const float nk = (u < 4 ? nlo[u & 3] : nhi[u & 3]) + shift;   // S T ||c||^2
-            const float al = 2.000002f * sqrtf(fmaxf(2.0f * nk, 0.f));    // ||S 2c|| (S / T = 2)
+            // ||S 2c|| = 2 sqrt(2 nk) (S / T = 2); hardware sqrt (1 ulp) with upward slack
+            const float al = 2.00001f * __builtin_amdgcn_sqrtf(fmaxf(2.0f * nk, 0.f));
             const float lb = pm[u] + po[u] + nk - (g1[0] * al + k4 * al * al);
             if (act && lb <= thr) mask |= 1u << (8 * h + u);
           }
@@ -373,16 +395,73 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
             todo &= todo - 1;
             const int m = 8 * (rr >> 2) + 4 * hh + (rr & 3);
             const unsigned kk = lds_p[tl * 32 + m];
-            // append to the token's list in LDS, or raise the slow flag when it is full
+            // append to the token's list in LDS; a full list marks the token for the
+            // group-wide exact pass below
             const bool ok = has && kk < (unsigned)a.K;
             const int n0 = nc[0];
             if (ok && n0 < SCR_CAND && h == 0) cand_row[n0] = (uint16_t)kk;
-            slow[0] |= (ok && n0 >= SCR_CAND) ? 1 : 0;
+            over = over || (ok && n0 >= SCR_CAND);
             nc[0] = n0 + (ok ? 1 : 0);
           }
         }
+        // ---- a token with more candidates than the list holds: the wavefront scores ALL rows
+        // of its (at most four) groups in the window exactly, one lane per row, and the token
+        // keeps the single winner.  Exact, because the true winner lies in one of these groups.
+        unsigned long long ovm = __ballot(over && !slow[0] && h == 0);
+        while (ovm) {
+          const int src = __ffsll((long long)ovm) - 1;
+          ovm &= ovm - 1;
+          n_slow += 1u << 16;  // counted apart from the full searches (upper half of the counter)
+          float rr32[32];
+#pragma unroll
+          for (int j = 0; j < 16; ++j) {
+            const float rj = rot == 0 ? r[0][j] : (rot == 1 ? r[1][j] : (rot == 2 ? r[2][j] : r[3][j]));
+            rr32[j] = __shfl(rj, src, 64);
+            rr32[16 + j] = __shfl(rj, src + 32, 64);
+          }
+          const int gi = lane >> 4, rw = lane & 15;  // lane -> (group of the window, row)
+          const float ge0 = __shfl(e0, src, 64), ge1 = __shfl(e1, src, 64);
+          const float ge2 = __shfl(e2, src, 64), ge3 = __shfl(e3, src, 64);
+          const unsigned gpend = (unsigned)__shfl((int)pend0, src, 64);
+          const int gaf = __shfl((int)afirst, src, 64);
+          const float gval = gi == 0 ? ge0 : (gi == 1 ? ge1 : (gi == 2 ? ge2 : ge3));
+          const int ghh = (gaf ? gi : gi + 1) & 1;
+          int gtl = (int)(__float_as_uint(gval) & ~tag_mask) - tile0;
+          gtl = gtl < 0 ? 0 : (gtl >= ntiles ? ntiles - 1 : gtl);
+          const int gm = 8 * (rw >> 2) + 4 * ghh + (rw & 3);
+          const unsigned gk = ((gpend >> gi) & 1u) ? (unsigned)lds_p[gtl * 32 + gm] : 0xffffu;
+          const bool gvalid = gk < (unsigned)a.K;
+          const f32x4 *crow = reinterpret_cast<const f32x4 *>(
+              a.C32 + ((int64_t)stage * a.K + (gvalid ? gk : 0u)) * 32);
+          float dist = 0.f;
+#pragma unroll
+          for (int c4 = 0; c4 < 8; ++c4) {
+            const f32x4 cw = crow[c4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float dlt = rr32[c4 * 4 + e] - cw[e];
+              dist = fmaf(dlt, dlt, dist);
+            }
+          }
+          float bd = gvalid ? dist : INFINITY;
+          int bk = gvalid ? (int)gk : 0x7fffffff;
+#pragma unroll
+          for (int o = 32; o > 0; o >>= 1) {
+            const float od = __shfl_xor(bd, o, 64);
+            const int ok2 = __shfl_xor(bk, o, 64);
+            if (od < bd || (od == bd && ok2 < bk)) { bd = od; bk = ok2; }
+          }
+          if (lane == src) cand_row[0] = (uint16_t)(bk == 0x7fffffff ? 0 : bk);
+          if (lane == src || lane == src + 32) nc[0] = 1;
+        }
         ROT4(m1); ROT4(m2); ROT4(m3); ROT4(g1); ROT4(g0); ROT4(slow); ROT4(nc);
         ROT4(B0); ROT4(B1);
+      }
+      prefetched = false;
+      if (single_chunk && stage + 1 < a.stage_end) {
+        __syncthreads();  // every wavefront has finished reading this stage's operands
+        stage_to_lds(stage + 1, 0, kc);
+        prefetched = true;
       }
     }
 
@@ -542,16 +621,18 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
   {
     __syncthreads();
     unsigned *lds_c = reinterpret_cast<unsigned *>(smem);
-    if (tid < 4) lds_c[tid] = 0u;
+    if (tid < 5) lds_c[tid] = 0u;
     __syncthreads();
     if (lane == 0) {
-      atomicAdd(&lds_c[0], n_slow);
+      atomicAdd(&lds_c[0], n_slow & 0xffffu);
+      atomicAdd(&lds_c[4], n_slow >> 16);
       atomicAdd(&lds_c[1], n_exact);
       atomicAdd(&lds_c[2], n_groups);
       atomicAdd(&lds_c[3], n_search);
     }
     __syncthreads();
     if (tid < 4) atomicAdd(&a.counters[tid], (unsigned long long)lds_c[tid]);
+    if (tid == 4) atomicAdd(&a.counters[10], (unsigned long long)lds_c[4]);
   }
 #ifdef RVQ_PHASE_CLOCKS
   if (lane == 0)
