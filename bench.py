@@ -41,8 +41,10 @@ def parse():
     ap.add_argument("--no-decode-stream", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--decode-slices", type=int, default=64)
-    ap.add_argument("--cpu-rows", type=int, default=8192)
+    ap.add_argument("--cpu-rows", type=int, default=32768)
     ap.add_argument("--encode-path", type=int, default=0)
+    ap.add_argument("--profile", choices=["encode", "decode", "ema", "copy"], default=None,
+                    help="run only one kernel a few times (for rocprofv3 runs; prints no JSON)")
     return ap.parse_args()
 
 
@@ -220,6 +222,62 @@ def run_cpu_baseline(args):
                 encode_Mvec_s=V / (t1 - t0) / 1e6)
 
 
+def run_profile(args):
+    """A few launches of one kernel, for `rocprofv3 --kernel-trace --stats` / `--pmc` runs.
+    `copy` is a plain 1 GiB device copy whose FETCH_SIZE / WRITE_SIZE readings calibrate the
+    counters' units."""
+    import numpy as np
+    import torch
+
+    from paper_2410_15704_amd import binding as b
+    from paper_2410_15704_amd import synth, train
+
+    if args.profile == "copy":
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        return
+    if args.profile == "decode":
+        T, d, G, depth, K = 16 * 32768, 1024, 32, 8, 2048
+        Cs = torch.from_numpy(synth.decode_codebooks(2)).cuda()
+        std = torch.from_numpy(synth.decode_std_fp16(T)).cuda()
+        out = torch.empty((T, d), dtype=torch.float16, device="cuda")
+        for s_, grp in enumerate((b.STRIDED, b.CONTIGUOUS)):
+            q = b.Quantizer(d=d, dhat=32, depth=depth, K=K, out_dtype=b.F16, std_dtype=b.F16, grouping=grp)
+            q.set_codebooks(Cs[s_])
+            codes = synth.uniform_codes_device(T, G, depth, K, "cuda", extra=100 + s_)
+            for _ in range(3):
+                b.rvq_decode(q.ctx, codes, std, T, depth, out, d)
+            torch.cuda.synchronize()
+            q.close()
+        return
+    N, d, dhat, depth, K = (W2[k] for k in ("N", "d", "dhat", "depth", "K"))
+    Xb, _ = synth.llama_key(N, d)
+    dX = torch.from_numpy(Xb.view(np.int16)).cuda().view(torch.bfloat16)
+    Zhead = train.scaled_groups(dX[:2048], d=d, dhat=dhat, grouping=b.STRIDED, in_dtype=b.BF16)
+    C = train.sample_init_codebooks(Zhead, depth, K, seed=synth.BASE_SEED + 2)
+    q = b.Quantizer(d=d, dhat=dhat, depth=depth, K=K, grouping=b.STRIDED, in_dtype=b.BF16,
+                    out_dtype=b.F16, std_dtype=b.F16, encode_path=args.encode_path)
+    q.set_codebooks(C)
+    codes = torch.empty((N, d // dhat, depth), dtype=torch.int16, device="cuda")
+    std = torch.empty((N,), dtype=torch.float16, device="cuda")
+    if args.profile == "encode":
+        for _ in range(5):
+            b.rvq_encode(q.ctx, dX, N, d, 0, depth, codes, std, None)
+    else:
+        Z = train.scaled_groups(dX, d=d, dhat=dhat, grouping=b.STRIDED, in_dtype=b.BF16)
+        b.rvq_encode(q.ctx, dX, N, d, 0, depth, codes, std, None)
+        cs = torch.ones(K, dtype=torch.float32, device="cuda")
+        es = C[0].clone()
+        for _ in range(5):
+            b.rvq_ema_update(q.ctx, 0, Z, codes, depth, N * (d // dhat), 0.99, 1e-5, cs, es)
+    torch.cuda.synchronize()
+    print(b.rvq_get_counters(q.ctx))
+    q.close()
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -230,6 +288,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.profile:
+        run_profile(args)
+        return
     r = run_steps(args)
     line = {
         "metric": "RVQ encode+decode+EMA step throughput, dhat=32, depth 8, K=2048 "
@@ -239,7 +300,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": r["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32 (distances screened on fp16 matrix cores where that path is active)",
+        "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": "workload 2: Llama-3-8B-like key projection, N=32768 x 1024 ch "
                                "bf16, strided groups of 32, depth 8, K=2048; encode + decode + "

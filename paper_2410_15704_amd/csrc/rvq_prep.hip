@@ -52,7 +52,7 @@ __global__ __launch_bounds__(256) void dup_maxabs_kernel(const float *__restrict
                                                          const float *__restrict__ norms, int K,
                                                          int stage_begin, int32_t *__restrict__ dup,
                                                          float *__restrict__ stats) {
-  __shared__ int found;
+  __shared__ volatile int found;
   const int stage = stage_begin + blockIdx.x / K;
   const int k = blockIdx.x % K;
   const float *n = norms + (int64_t)stage * K;
@@ -68,7 +68,7 @@ __global__ __launch_bounds__(256) void dup_maxabs_kernel(const float *__restrict
   }
   __syncthreads();
   const float nk = n[k];
-  for (int j = threadIdx.x; j < k; j += blockDim.x) {
+  for (int j = threadIdx.x; j < k && !found; j += blockDim.x) {  // one earlier repeat is enough
     if (n[j] != nk) continue;
     bool same = true;
     for (int e = 0; e < 32; ++e) same = same && Cs[(int64_t)j * 32 + e] == Cs[(int64_t)k * 32 + e];
