@@ -163,6 +163,7 @@ int rvq_get_counters(rvq_ctx *ctx, int64_t *host_out) {
   host_out[4] = (int64_t)tmp[10];
 #ifdef RVQ_PHASE_CLOCKS
   for (int i = 4; i < 10; ++i) host_out[i + 1] = (int64_t)tmp[i];  // debug builds: caller passes 16
+  for (int i = 11; i < 14; ++i) host_out[i] = (int64_t)tmp[i];
 #endif
   return RVQ_OK;
 }

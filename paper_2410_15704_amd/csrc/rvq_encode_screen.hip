@@ -41,14 +41,22 @@ typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int SCR_WAVES = 8;
-constexpr int SCR_TT = 4;                              // token tiles per wavefront
+#ifndef RVQ_SCR_WAVES
+#define RVQ_SCR_WAVES 8
+#define RVQ_SCR_TT 4
+#define RVQ_SCR_QCAP 16
+#endif
+constexpr int SCR_WAVES = RVQ_SCR_WAVES;
+constexpr int SCR_TT = RVQ_SCR_TT;                     // token tiles per wavefront
 constexpr int SCR_TOKENS = SCR_WAVES * SCR_TT * 32;    // group vectors per workgroup
 constexpr int SCR_KC = 2048;                           // codewords resident in LDS
-constexpr int SCR_CAND = 8;                            // candidate codewords kept per token
+constexpr int SCR_CAND = 4;                            // candidate codewords kept per token
+constexpr int SCR_QCAP = RVQ_SCR_QCAP;                         // queued (token, group) pairs per wavefront
 constexpr size_t SCR_LDS_BYTES = (size_t)SCR_KC * 64 + (size_t)SCR_KC * 4 +
                                  (size_t)(SCR_KC / 16) * 4 + (size_t)SCR_KC * 2 +
-                                 (size_t)SCR_TOKENS * SCR_CAND * 2;
+                                 (size_t)SCR_TOKENS * SCR_CAND * 2 + (size_t)SCR_TOKENS * 2 +
+                                 (size_t)SCR_WAVES * SCR_QCAP * 72;
+static_assert(SCR_LDS_BYTES <= 160 * 1024, "one workgroup must fit the 160 KiB of LDS");
 constexpr float BIG = 3.0e38f;
 
 struct ScreenArgs {
@@ -101,22 +109,20 @@ __device__ __forceinline__ float dot8(const uint4 w, const half8 b, float acc) {
 #define PHASE_MARK(i) do { } while (0)
 #endif
 
-// rotate a 4-entry per-token-tile array by one: lets a compact, non-unrolled loop work on entry
-// 0 four times instead of unrolling its body four times (the unrolled resolve code did not fit
-// the instruction cache)
-#define ROT4(x)         \
-  do {                  \
-    auto t_ = x[0];     \
-    x[0] = x[1];        \
-    x[1] = x[2];        \
-    x[2] = x[3];        \
-    x[3] = t_;          \
+// rotate a per-token-tile array by one entry: lets a compact, non-unrolled loop work on entry 0
+// SCR_TT times instead of unrolling its body (the unrolled resolve code did not fit the
+// instruction cache)
+#define ROT4(x)                                                   \
+  do {                                                            \
+    auto t_ = x[0];                                               \
+    _Pragma("unroll") for (int i_ = 0; i_ + 1 < SCR_TT; ++i_) x[i_] = x[i_ + 1]; \
+    x[SCR_TT - 1] = t_;                                           \
   } while (0)
 
 template <int DT>
 __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const ScreenArgs a) {
 #ifdef RVQ_PHASE_CLOCKS
-  long long phase_acc[6] = {0, 0, 0, 0, 0, 0};
+  long long phase_acc[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
   long long phase_t = wall_clock64();
 #endif
   extern __shared__ uint4 smem[];
@@ -125,6 +131,12 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
   float *lds_g = lds_n + SCR_KC;                                    // SCR_KC / 16 group bounds
   uint16_t *lds_p = reinterpret_cast<uint16_t *>(lds_g + SCR_KC / 16);  // position -> codeword
   uint16_t *lds_c = lds_p + SCR_KC;  // [token of the workgroup][SCR_CAND] candidate codewords
+  // candidates found per token: two 16-bit counts per word, bumped with LDS atomics
+  unsigned *lds_cnt = reinterpret_cast<unsigned *>(lds_c + SCR_TOKENS * SCR_CAND);
+  // per-wavefront queue of (token, group) pairs waiting for a re-score: 64 bytes of fp16
+  // residual (two lanes x 32 bytes) and 8 bytes of bookkeeping per entry
+  uint4 *lds_qB = reinterpret_cast<uint4 *>(lds_cnt + SCR_TOKENS / 2);
+  uint2 *lds_qM = reinterpret_cast<uint2 *>(lds_qB + SCR_WAVES * SCR_QCAP * 4);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -132,16 +144,12 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
   const int p = lane & 31;
   const int h = lane >> 5;
   const int64_t vbase = (int64_t)blockIdx.x * SCR_TOKENS + wave * (SCR_TT * 32);
+  const int wtok = wave * (SCR_TT * 32);  // first token slot of this wavefront in the workgroup
+  uint4 *qB = lds_qB + wave * SCR_QCAP * 4;
+  uint2 *qM = lds_qM + wave * SCR_QCAP;
 
   // ---- load this lane's 16 channels of its 4 tokens, scaled by the row std (Section 2.2)
   float r[SCR_TT][16];
-#ifdef RVQ_DEBUG_DUMP
-  float dbg[SCR_TT][16];
-#pragma unroll
-  for (int tt = 0; tt < SCR_TT; ++tt)
-#pragma unroll
-    for (int j = 0; j < 16; ++j) dbg[tt][j] = 0.f;
-#endif
 #pragma unroll
   for (int tt = 0; tt < SCR_TT; ++tt) {
     const int64_t v = vbase + tt * 32 + p;
@@ -160,7 +168,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
   }
 
   PHASE_MARK(0);  // input load
-  unsigned n_slow = 0, n_exact = 0, n_groups = 0, n_search = 0;  // wave-uniform statistics
+  unsigned n_slow = 0, n_over = 0, n_exact = 0, n_groups = 0, n_search = 0;  // wave-uniform
   const unsigned tag_mask = ~((1u << a.tag_bits) - 1u);
   unsigned tag_mask_v = tag_mask;  // kept in a vector register: v_and_or_b32 takes one scalar only
   asm volatile("" : "+v"(tag_mask_v));
@@ -191,42 +199,47 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
     const bool usable = a.stats[stage * 8 + 1] != 0.0f;
     const float Fdrop = a.stats[stage * 8 + 2];
     const float Tscale = a.stats[stage * 8 + 4];  // power of two applied to the residuals
+    const float tiny = 6.103515625e-5f / Tscale;  // below this the scaled value is no normal half
 
     // ---- fp16 B operands and the per-token error bound
     half8 B0[SCR_TT], B1[SCR_TT];
     float g1[SCR_TT];     // token part of the error bound: e_k = g1 ||2c|| + k4 ||2c||^2 + g0
     float g0[SCR_TT];     // ||fp16(r)|| * (largest norm of codeword elements dropped to zero)
     int slow[SCR_TT];     // token goes to the exact wavefront search
-    int nc[SCR_TT];       // candidates found for the token (the list itself is in LDS)
+    float bestd[SCR_TT];  // exact distance and index of the best candidate scored so far
+    int bestk[SCR_TT];
+    int done[SCR_TT];     // the codeword has already been subtracted from the residual
 #pragma unroll
     for (int tt = 0; tt < SCR_TT; ++tt) {
-      nc[tt] = 0;
-      float s_r = 0.f, s_q = 0.f, s_d = 0.f;
+      bestd[tt] = INFINITY;
+      bestk[tt] = 0;
+      done[tt] = 0;
+      float s_q = 0.f, s_d = 0.f;
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
         const float x = r[tt][j] * Tscale;  // exact
-        const _Float16 hx = fabsf(x) < 6.103515625e-5f ? (_Float16)0.f : (_Float16)x;
+        const _Float16 hx = fabsf(r[tt][j]) < tiny ? (_Float16)0.f : (_Float16)x;
         if (j < 8) B0[tt][j] = hx;
         else B1[tt][j - 8] = hx;
         const float xr = (float)hx;
         const float dx = x - xr;  // exact
-        s_r = fmaf(x, x, s_r);
         s_q = fmaf(xr, xr, s_q);
         s_d = fmaf(dx, dx, s_d);
       }
-      s_r += xor32(s_r);
       s_q += xor32(s_q);
       s_d += xor32(s_d);
       const float nq = sqrtf(s_q) * 1.000001f;
       const float nd = sqrtf(s_d) * 1.000001f;
       g1[tt] = (nd + (rho + a.kappa * (1.0f + rho)) * nq) * 1.000001f;
       g0[tt] = nq * Fdrop * 1.000001f;
+      // an element beyond the half range turns s_q into infinity
 #ifdef RVQ_FORCE_SLOW
       slow[tt] = 1;
 #else
-      slow[tt] = (!usable || !(s_r < 3.6e9f)) ? 1 : 0;
+      slow[tt] = (!usable || !(s_q < 3.6e9f)) ? 1 : 0;
 #endif
     }
+    if (lane < SCR_TT * 16) lds_cnt[(wtok >> 1) + lane] = 0u;  // this wavefront's candidate counts
 
     PHASE_MARK(1);  // operand conversion
     for (int cbase = 0; cbase < a.Kpad; cbase += SCR_KC) {
@@ -290,188 +303,304 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
 
       PHASE_MARK(3);  // sweep
       // ---- resolve, step 1 (LDS only): the candidate codewords of every token of the chunk.
+      //
+      // fp16 re-score of the 16 rows of group (tl, hh) for the token whose fp16 residual halves
+      // the lane pair holds in (Bx0, Bx1): every lane forms the partial dot product of its 16
+      // channels with two rows per step, one that it finishes itself (rows 8 h .. 8 h + 7 of
+      // the group) and one that its partner lane finishes.  A row survives when its score minus
+      // the group's error bound is within the token's window: score <= tadj = thr + g1 A_g
+      // (the second-order part of the bound is already inside the stored norms).  Returns the
+      // survivors of the pair as a 16-bit row mask, the same in both lanes.
+      auto rescore = [&](int tl, int hh, const half8 &Bx0, const half8 &Bx1, float tadj,
+                         bool act) -> unsigned {
+        const uint2 *rows = reinterpret_cast<const uint2 *>(lds_A) + tl * 256 + h * 32;
+        const int swz = tl & 31;  // row m of tile tl is stored in slot m ^ swz
+        const float *nrow = lds_n + (tl * 2 + hh) * 16 + 8 * h;
+        // all reads of one quarter of the rows are issued before their dot products, and the
+        // eight partner partials are exchanged together: few dependent LDS round trips
+        float pm[8], ps[8];
+#pragma unroll
+        for (int qt = 0; qt < 4; ++qt) {  // two group rows per lane role and step
+          uint4 xm0[2], xm1[2], xs0[2], xs1[2];
+#pragma unroll
+          for (int q = 0; q < 2; ++q) {
+            const int u = 2 * qt + q;
+            const int mo = 8 * (u >> 2) + (u & 3);  // tile row of group row u, within 16 rows
+            const uint2 *rm = rows + ((16 * h + 4 * hh + mo) ^ swz);
+            const uint2 *rs = rows + ((16 * (1 - h) + 4 * hh + mo) ^ swz);
+            xm0[q] = make_uint4(rm[0].x, rm[0].y, rm[64].x, rm[64].y);
+            xm1[q] = make_uint4(rm[128].x, rm[128].y, rm[192].x, rm[192].y);
+            xs0[q] = make_uint4(rs[0].x, rs[0].y, rs[64].x, rs[64].y);
+            xs1[q] = make_uint4(rs[128].x, rs[128].y, rs[192].x, rs[192].y);
+          }
+#pragma unroll
+          for (int q = 0; q < 2; ++q) {
+            pm[2 * qt + q] = dot8(xm1[q], Bx1, dot8(xm0[q], Bx0, 0.f));
+            ps[2 * qt + q] = dot8(xs1[q], Bx1, dot8(xs0[q], Bx0, 0.f));
+          }
+        }
+        const f32x4 nlo = *reinterpret_cast<const f32x4 *>(nrow);
+        const f32x4 nhi = *reinterpret_cast<const f32x4 *>(nrow + 4);
+        unsigned mask = 0;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const float sc = (pm[u] + xor32(ps[u])) + (u < 4 ? nlo[u & 3] : nhi[u & 3]);
+          mask |= (sc <= tadj ? 1u : 0u) << u;
+        }
+        mask = act ? mask << (8 * h) : 0u;
+        n_groups += __popcll(__ballot(act && h == 0));
+        return mask | (unsigned)xor32i((int)mask);
+      };
+      // append the surviving rows of group (tl, hh), as codeword indices, to the candidate list
+      // of token slot `tok` of this wavefront; a count beyond the list marks the token for the
+      // group-wide exact pass below
+      auto append = [&](unsigned todo, int tl, int hh, int tok) {
+        const int sh = 16 * (tok & 1);
+        while (__any(todo != 0)) {
+          const bool has = todo != 0;
+          const int rr = has ? __ffs(todo) - 1 : 0;
+          todo &= todo - 1;
+          const int m = 8 * (rr >> 2) + 4 * hh + (rr & 3);
+          const unsigned kk = lds_p[tl * 32 + m];
+          if (has && h == 0 && kk < (unsigned)a.K) {
+            const unsigned pos = (atomicAdd(&lds_cnt[(wtok + tok) >> 1], 1u << sh) >> sh) & 0xffffu;
+            if (pos < (unsigned)SCR_CAND) lds_c[(wtok + tok) * SCR_CAND + pos] = (uint16_t)kk;
+          }
+        }
+      };
+      // group (tile, lane half) of a tagged lower bound, tile relative to the chunk
+      auto tile_of = [&](float val) -> int {
+        int tl = (int)(__float_as_uint(val) & ~tag_mask) - tile0;
+        return tl < 0 ? 0 : (tl >= ntiles ? ntiles - 1 : tl);
+      };
+      // the window of entry 0 of the (rotated) per-tile arrays: thr = upper bound on the exact
+      // minimum, from the best group of either lane (LB + 2 e_g, 25 % spare); e0..e3 = the
+      // token's four tracked groups, the best one first (both lanes of the pair build the same
+      // list: the two best of half 0 and of half 1); pend = which of them lie within the window
+      struct Window { float thr, e0, e1, e2, e3; unsigned pend; bool afirst; };
+      auto window = [&]() -> Window {
+        Window w;
+        const float o1 = xor32(m1[0]), o2 = xor32(m2[0]), o3 = xor32(m3[0]);
+        {
+          const float A1 = lds_g[tile_of(m1[0]) * 2 + h];
+          const float mine = m1[0] + 2.5f * (g1[0] * A1 + k4 * A1 * A1 + g0[0]);
+          w.thr = fminf(mine, xor32(mine));
+        }
+        // a third group of one lane inside the window: more groups than are tracked
+        if (m3[0] <= w.thr || o3 <= w.thr) slow[0] = 1;
+        const float a1 = h ? o1 : m1[0], a2 = h ? o2 : m2[0];
+        const float b1 = h ? m1[0] : o1, b2 = h ? m2[0] : o2;
+        w.afirst = a1 <= b1;
+        w.e0 = w.afirst ? a1 : b1; w.e1 = w.afirst ? b1 : a1;
+        w.e2 = w.afirst ? a2 : b2; w.e3 = w.afirst ? b2 : a2;
+        w.pend = 0;
+        if (!slow[0])
+          w.pend = (w.e0 <= w.thr && w.e0 < 1e37f ? 1u : 0u) | (w.e1 <= w.thr && w.e1 < 1e37f ? 2u : 0u) |
+                   (w.e2 <= w.thr && w.e2 < 1e37f ? 4u : 0u) | (w.e3 <= w.thr && w.e3 < 1e37f ? 8u : 0u);
+        return w;
+      };
+
+      // Pass A, per token tile: the best group of every token is re-scored in place; its other
+      // groups inside the window (3 % of the tokens have one) are queued, so that they are
+      // re-scored 32 at a time afterwards instead of one extra pass per token tile.
       // The loop body always works on entry 0 of the per-tile arrays, which are rotated.
+      int qn = 0;  // queue entries of this wavefront (wave-uniform)
 #ifdef RVQ_SKIP_RESOLVE
-      for (int tt = 0; tt < SCR_TT; ++tt) { nc[tt] = 1; lds_c[(wave * (SCR_TT * 32) + tt * 32 + p) * SCR_CAND] = __float_as_uint(m1[tt]) & 1023u; }
+      for (int tt = 0; tt < SCR_TT; ++tt) {
+        lds_c[(wtok + tt * 32 + p) * SCR_CAND] = __float_as_uint(m1[tt]) & 1023u;
+        if (h == 0) atomicAdd(&lds_cnt[(wtok + tt * 32 + p) >> 1], 1u << (16 * (p & 1)));
+      }
       if (false)
 #endif
 #pragma unroll 1
       for (int rot = 0; rot < SCR_TT; ++rot) {
-        uint16_t *cand_row = lds_c + (wave * (SCR_TT * 32) + rot * 32 + p) * SCR_CAND;
-        const float o1 = xor32(m1[0]), o2 = xor32(m2[0]), o3 = xor32(m3[0]);
-        // upper bound on the exact minimum from my best group (LB + 2 e_g, 25 % spare), then
-        // the smaller of the two lanes' bounds
-        float thr;
+        const int tok = rot * 32 + p;
+        const Window w = window();
         {
-          int t1 = (int)(__float_as_uint(m1[0]) & ~tag_mask) - tile0;
-          t1 = t1 < 0 ? 0 : (t1 >= ntiles ? ntiles - 1 : t1);
-          const float A1 = lds_g[t1 * 2 + h];
-          const float mine = m1[0] + 2.5f * (g1[0] * A1 + k4 * A1 * A1 + g0[0]);
-          thr = fminf(mine, xor32(mine));
+          const int tl = tile_of(w.e0);
+          const int hh = (w.afirst ? 0 : 1);
+          const float tadj = w.thr + g1[0] * lds_g[tl * 2 + hh];
+          const unsigned todo = rescore(tl, hh, B0[0], B1[0], tadj, (w.pend & 1u) != 0);
+          append(todo, tl, hh, tok);
         }
-#ifdef RVQ_DEBUG_DUMP
-        if (stage == a.stage_begin) {
-          dbg[rot][0] = m1[0]; dbg[rot][1] = m2[0]; dbg[rot][2] = m3[0]; dbg[rot][3] = thr;
-          dbg[rot][4] = o1; dbg[rot][5] = g1[0]; dbg[rot][6] = g0[0]; dbg[rot][7] = (float)slow[0];
-        }
-#endif
-        if (m3[0] <= thr || o3 <= thr) slow[0] = 1;
-        // the token's four tracked groups, the best one first so that one pass settles almost
-        // every token; both lanes of the pair build the same list (half-0 entries a, half-1 b)
-        const float a1 = h ? o1 : m1[0], a2 = h ? o2 : m2[0];
-        const float b1 = h ? m1[0] : o1, b2 = h ? m2[0] : o2;
-        const bool afirst = a1 <= b1;
-        // entries within the window, as a per-lane bit mask; every pass lets each token work
-        // on its next pending entry, so the number of passes is the largest number of pending
-        // groups of any token of the tile (almost always 1 or 2), not the number of entries
-        const float e0 = afirst ? a1 : b1, e1 = afirst ? b1 : a1;
-        const float e2 = afirst ? a2 : b2, e3 = afirst ? b2 : a2;
-        unsigned pend = 0;
-        bool over = false;  // more candidates than the list in LDS holds
-        if (!slow[0]) {
-          pend = (e0 <= thr && e0 < 1e37f ? 1u : 0u) | (e1 <= thr && e1 < 1e37f ? 2u : 0u) |
-                 (e2 <= thr && e2 < 1e37f ? 4u : 0u) | (e3 <= thr && e3 < 1e37f ? 8u : 0u);
-        }
-        const unsigned pend0 = pend;
-        while (__any(pend != 0)) {
-          const bool act = pend != 0 && !slow[0];
-          const int it = act ? __ffs(pend) - 1 : 0;
-          pend &= pend - 1;
-          const int hh = (afirst ? it : it + 1) & 1;  // lane half that owned the group
-          const float val = it == 0 ? e0 : (it == 1 ? e1 : (it == 2 ? e2 : e3));
-          n_groups += __popcll(__ballot(act && h == 0));
-          int tl = (int)(__float_as_uint(val) & ~tag_mask) - tile0;
-          tl = tl < 0 ? 0 : (tl >= ntiles ? ntiles - 1 : tl);
-          // fp16 re-score of the 16 rows of group (tl, hh): every lane forms the partial dot
-          // product of its 16 channels with two rows per step, one that it finishes itself
-          // (rows 8 h .. 8 h + 7 of the group) and one that its partner lane finishes
-          const uint2 *rows = reinterpret_cast<const uint2 *>(lds_A) + tl * 256 + h * 32;
-          const int swz = tl & 31;  // row m of tile tl is stored in slot m ^ swz
-          const float *nrow = lds_n + (tl * 2 + hh) * 16 + 8 * h;
-          const float Agrp = lds_g[tl * 2 + hh];
-          const float shift = k4 * Agrp * Agrp;
-          // all reads of one half of the rows are issued before their dot products, and the
-          // eight partner partials are exchanged together: few dependent LDS round trips
-          float pm[8], ps[8];
+        bool over = false;
 #pragma unroll
-          for (int qt = 0; qt < 4; ++qt) {  // two group rows per lane role and step
-            uint4 xm0[2], xm1[2], xs0[2], xs1[2];
-#pragma unroll
-            for (int q = 0; q < 2; ++q) {
-              const int u = 2 * qt + q;
-              const int mo = 8 * (u >> 2) + (u & 3);  // tile row of group row u, within 16 rows
-              const uint2 *rm = rows + ((16 * h + 4 * hh + mo) ^ swz);
-              const uint2 *rs = rows + ((16 * (1 - h) + 4 * hh + mo) ^ swz);
-              xm0[q] = make_uint4(rm[0].x, rm[0].y, rm[64].x, rm[64].y);
-              xm1[q] = make_uint4(rm[128].x, rm[128].y, rm[192].x, rm[192].y);
-              xs0[q] = make_uint4(rs[0].x, rs[0].y, rs[64].x, rs[64].y);
-              xs1[q] = make_uint4(rs[128].x, rs[128].y, rs[192].x, rs[192].y);
+        for (int it = 1; it < 4; ++it) {
+          const bool has = ((w.pend >> it) & 1u) != 0;
+          const unsigned long long bal = __ballot(has && h == 0);
+          if (bal) {  // wave-uniform, seldom taken
+            const int idx = qn + __popcll(bal & ((1ull << p) - 1ull));
+            const float val = it == 1 ? w.e1 : (it == 2 ? w.e2 : w.e3);
+            const int tl = tile_of(val);
+            const int hh = (w.afirst ? it : it + 1) & 1;
+            if (has) {
+              if (idx < SCR_QCAP) {
+                qB[(idx * 2 + h) * 2 + 0] = __builtin_bit_cast(uint4, B0[0]);
+                qB[(idx * 2 + h) * 2 + 1] = __builtin_bit_cast(uint4, B1[0]);
+                if (h == 0)
+                  qM[idx] = make_uint2(__float_as_uint(w.thr + g1[0] * lds_g[tl * 2 + hh]),
+                                       (unsigned)tok | ((unsigned)tl << 8) | ((unsigned)hh << 16));
+              } else {
+                over = true;  // queue full: the group-wide exact pass takes the token
+              }
             }
-#pragma unroll
-            for (int q = 0; q < 2; ++q) {
-              pm[2 * qt + q] = dot8(xm1[q], B1[0], dot8(xm0[q], B0[0], 0.f));
-              ps[2 * qt + q] = dot8(xs1[q], B1[0], dot8(xs0[q], B0[0], 0.f));
-            }
-          }
-          float po[8];
-#pragma unroll
-          for (int u = 0; u < 8; ++u) po[u] = xor32(ps[u]);
-          const f32x4 nlo = *reinterpret_cast<const f32x4 *>(nrow);
-          const f32x4 nhi = *reinterpret_cast<const f32x4 *>(nrow + 4);
-          unsigned mask = 0;
-#pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            const float nk = (u < 4 ? nlo[u & 3] : nhi[u & 3]) + shift;   // S T ||c||^2
-            // ||S 2c|| = 2 sqrt(2 nk) (S / T = 2); hardware sqrt (1 ulp) with upward slack
-            const float al = 2.00001f * __builtin_amdgcn_sqrtf(fmaxf(2.0f * nk, 0.f));
-            const float lb = pm[u] + po[u] + nk - (g1[0] * al + k4 * al * al);
-            if (act && lb <= thr) mask |= 1u << (8 * h + u);
-          }
-          unsigned todo = mask | (unsigned)xor32i((int)mask);
-          // append the survivors (as codeword indices) to the token's candidate list
-          while (__any(todo != 0)) {
-            const bool has = todo != 0;
-            const int rr = has ? __ffs(todo) - 1 : 0;
-            todo &= todo - 1;
-            const int m = 8 * (rr >> 2) + 4 * hh + (rr & 3);
-            const unsigned kk = lds_p[tl * 32 + m];
-            // append to the token's list in LDS; a full list marks the token for the
-            // group-wide exact pass below
-            const bool ok = has && kk < (unsigned)a.K;
-            const int n0 = nc[0];
-            if (ok && n0 < SCR_CAND && h == 0) cand_row[n0] = (uint16_t)kk;
-            over = over || (ok && n0 >= SCR_CAND);
-            nc[0] = n0 + (ok ? 1 : 0);
+            qn = min(SCR_QCAP, qn + (int)__popcll(bal));
           }
         }
-        // ---- a token with more candidates than the list holds: the wavefront scores ALL rows
-        // of its (at most four) groups in the window exactly, one lane per row, and the token
-        // keeps the single winner.  Exact, because the true winner lies in one of these groups.
-        unsigned long long ovm = __ballot(over && !slow[0] && h == 0);
-        while (ovm) {
-          const int src = __ffsll((long long)ovm) - 1;
-          ovm &= ovm - 1;
-          n_slow += 1u << 16;  // counted apart from the full searches (upper half of the counter)
-          float rr32[32];
-#pragma unroll
-          for (int j = 0; j < 16; ++j) {
-            const float rj = rot == 0 ? r[0][j] : (rot == 1 ? r[1][j] : (rot == 2 ? r[2][j] : r[3][j]));
-            rr32[j] = __shfl(rj, src, 64);
-            rr32[16 + j] = __shfl(rj, src + 32, 64);
-          }
-          const int gi = lane >> 4, rw = lane & 15;  // lane -> (group of the window, row)
-          const float ge0 = __shfl(e0, src, 64), ge1 = __shfl(e1, src, 64);
-          const float ge2 = __shfl(e2, src, 64), ge3 = __shfl(e3, src, 64);
-          const unsigned gpend = (unsigned)__shfl((int)pend0, src, 64);
-          const int gaf = __shfl((int)afirst, src, 64);
-          const float gval = gi == 0 ? ge0 : (gi == 1 ? ge1 : (gi == 2 ? ge2 : ge3));
-          const int ghh = (gaf ? gi : gi + 1) & 1;
-          int gtl = (int)(__float_as_uint(gval) & ~tag_mask) - tile0;
-          gtl = gtl < 0 ? 0 : (gtl >= ntiles ? ntiles - 1 : gtl);
-          const int gm = 8 * (rw >> 2) + 4 * ghh + (rw & 3);
-          const unsigned gk = ((gpend >> gi) & 1u) ? (unsigned)lds_p[gtl * 32 + gm] : 0xffffu;
-          const bool gvalid = gk < (unsigned)a.K;
-          const f32x4 *crow = reinterpret_cast<const f32x4 *>(
-              a.C32 + ((int64_t)stage * a.K + (gvalid ? gk : 0u)) * 32);
-          float dist = 0.f;
-#pragma unroll
-          for (int c4 = 0; c4 < 8; ++c4) {
-            const f32x4 cw = crow[c4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const float dlt = rr32[c4 * 4 + e] - cw[e];
-              dist = fmaf(dlt, dlt, dist);
-            }
-          }
-          float bd = gvalid ? dist : INFINITY;
-          int bk = gvalid ? (int)gk : 0x7fffffff;
-#pragma unroll
-          for (int o = 32; o > 0; o >>= 1) {
-            const float od = __shfl_xor(bd, o, 64);
-            const int ok2 = __shfl_xor(bk, o, 64);
-            if (od < bd || (od == bd && ok2 < bk)) { bd = od; bk = ok2; }
-          }
-          if (lane == src) cand_row[0] = (uint16_t)(bk == 0x7fffffff ? 0 : bk);
-          if (lane == src || lane == src + 32) nc[0] = 1;
-        }
-        ROT4(m1); ROT4(m2); ROT4(m3); ROT4(g1); ROT4(g0); ROT4(slow); ROT4(nc);
+        if (over && h == 0) atomicOr(&lds_cnt[(wtok + tok) >> 1], 0x100u << (16 * (tok & 1)));
+        ROT4(m1); ROT4(m2); ROT4(m3); ROT4(g1); ROT4(g0); ROT4(slow);
         ROT4(B0); ROT4(B1);
       }
+      PHASE_MARK(4);  // resolve: best groups in place
+      // Pass B: the queued (token, group) pairs, one per lane pair
+      for (int base = 0; base < qn; base += 32) {
+        const bool valid = base + p < qn;
+        const int qi = valid ? base + p : 0;
+        const uint2 meta = qM[qi];
+        const half8 Bq0 = __builtin_bit_cast(half8, qB[(qi * 2 + h) * 2 + 0]);
+        const half8 Bq1 = __builtin_bit_cast(half8, qB[(qi * 2 + h) * 2 + 1]);
+        const int tok = (int)(meta.y & 0xffu) & (SCR_TT * 32 - 1);
+        int tl = (int)((meta.y >> 8) & 0xffu);
+        tl = tl >= ntiles ? ntiles - 1 : tl;
+        const int hh = (int)((meta.y >> 16) & 1u);
+        const unsigned todo = rescore(tl, hh, Bq0, Bq1, __uint_as_float(meta.x), valid);
+        append(todo, tl, hh, tok);
+      }
+
+      PHASE_MARK(6);  // resolve: queued groups
+      // candidates per token, as counted in LDS
+      int nc[SCR_TT];
+      bool any_over = false;
+#pragma unroll
+      for (int tt = 0; tt < SCR_TT; ++tt) {
+        nc[tt] = (int)((lds_cnt[(wtok + tt * 32 + p) >> 1] >> (16 * (p & 1))) & 0xffffu);
+        any_over = any_over || nc[tt] > SCR_CAND;
+      }
+      // ---- a token with more candidates than the list holds (or whose groups did not fit the
+      // queue): the wavefront scores ALL rows of its (at most four) groups in the window
+      // exactly, one lane per row, and the token keeps the single winner.  Exact, because the
+      // true winner of the chunk lies in one of these groups.
+      if (__any(any_over)) {
+#pragma unroll 1
+        for (int rot = 0; rot < SCR_TT; ++rot) {
+          unsigned long long ovm = __ballot(nc[0] > SCR_CAND && !slow[0] && h == 0);
+          if (ovm) {
+            const Window w = window();
+            while (ovm) {
+              const int src = __ffsll((long long)ovm) - 1;
+              ovm &= ovm - 1;
+              n_over += 1;
+              float rr32[32];
+#pragma unroll
+              for (int j = 0; j < 16; ++j) {
+                float rj = r[0][j];
+#pragma unroll
+                for (int t2 = 1; t2 < SCR_TT; ++t2) rj = rot == t2 ? r[t2][j] : rj;
+                rr32[j] = __shfl(rj, src, 64);
+                rr32[16 + j] = __shfl(rj, src + 32, 64);
+              }
+              const int gi = lane >> 4, rw = lane & 15;  // lane -> (group of the window, row)
+              const float ge0 = __shfl(w.e0, src, 64), ge1 = __shfl(w.e1, src, 64);
+              const float ge2 = __shfl(w.e2, src, 64), ge3 = __shfl(w.e3, src, 64);
+              const unsigned gpend = (unsigned)__shfl((int)w.pend, src, 64);
+              const int gaf = __shfl((int)w.afirst, src, 64);
+              const float gval = gi == 0 ? ge0 : (gi == 1 ? ge1 : (gi == 2 ? ge2 : ge3));
+              const int ghh = (gaf ? gi : gi + 1) & 1;
+              const int gtl = tile_of(gval);
+              const int gm = 8 * (rw >> 2) + 4 * ghh + (rw & 3);
+              const unsigned gk = ((gpend >> gi) & 1u) ? (unsigned)lds_p[gtl * 32 + gm] : 0xffffu;
+              const bool gvalid = gk < (unsigned)a.K;
+              const f32x4 *crow = reinterpret_cast<const f32x4 *>(
+                  a.C32 + ((int64_t)stage * a.K + (gvalid ? gk : 0u)) * 32);
+              float dist = 0.f;
+#pragma unroll
+              for (int c4 = 0; c4 < 8; ++c4) {
+                const f32x4 cw = crow[c4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  const float dlt = rr32[c4 * 4 + e] - cw[e];
+                  dist = fmaf(dlt, dlt, dist);
+                }
+              }
+              float bd = gvalid ? dist : INFINITY;
+              int bk = gvalid ? (int)gk : 0x7fffffff;
+#pragma unroll
+              for (int o = 32; o > 0; o >>= 1) {
+                const float od = __shfl_xor(bd, o, 64);
+                const int ok2 = __shfl_xor(bk, o, 64);
+                if (od < bd || (od == bd && ok2 < bk)) { bd = od; bk = ok2; }
+              }
+              if (lane == src) lds_c[(wtok + rot * 32 + src) * SCR_CAND] = (uint16_t)(bk == 0x7fffffff ? 0 : bk);
+              // bk == 0x7fffffff cannot happen for a token with candidates; it would leave the
+              // token without one and send it to the wavefront search below
+              if (lane == src || lane == src + 32) nc[0] = bk == 0x7fffffff ? 0 : 1;
+            }
+          }
+          ROT4(m1); ROT4(m2); ROT4(m3); ROT4(g1); ROT4(g0); ROT4(slow); ROT4(nc);
+        }
+      }
+      PHASE_MARK(7);  // resolve: group-wide exact passes
       prefetched = false;
       if (single_chunk && stage + 1 < a.stage_end) {
         __syncthreads();  // every wavefront has finished reading this stage's operands
         stage_to_lds(stage + 1, 0, kc);
         prefetched = true;
       }
+      PHASE_MARK(8);  // barrier + start of the next stage's copy
+
+      // ---- resolve, step 2 (global): exact fp32 score of every candidate of the chunk,
+      // sum (r - c)^2 with the fp32 codeword; slot s of all four tokens is loaded in one batch,
+      // and slots beyond the first only when some token of the wavefront has them.  A token
+      // whose only candidate this is (97 % of them) has found its codeword: the row is
+      // subtracted from the residual right away, so it is fetched once, not twice.
+#pragma unroll 1
+      for (int slot = 0; slot < SCR_CAND; ++slot) {
+        bool need = false;
+#pragma unroll
+        for (int tt = 0; tt < SCR_TT; ++tt) need = need || (nc[tt] > slot && !slow[tt]);
+        if (!__any(need)) break;
+        f32x4 cw[SCR_TT][4];
+        int kk[SCR_TT];
+#pragma unroll
+        for (int tt = 0; tt < SCR_TT; ++tt) {
+          const int cand = lds_c[(wtok + tt * 32 + p) * SCR_CAND + slot];
+          kk[tt] = (nc[tt] > slot && cand < a.K) ? cand : 0;
+          const f32x4 *crow = reinterpret_cast<const f32x4 *>(
+              a.C32 + ((int64_t)stage * a.K + kk[tt]) * 32 + 16 * h);
+#pragma unroll
+          for (int c4 = 0; c4 < 4; ++c4) cw[tt][c4] = crow[c4];
+        }
+#pragma unroll
+        for (int tt = 0; tt < SCR_TT; ++tt) {
+          const bool valid = nc[tt] > slot && !slow[tt];
+          const bool commit = single_chunk && slot == 0 && valid && nc[tt] == 1;
+          const float sel = commit ? 1.0f : 0.0f;
+          float dist = 0.f;
+#pragma unroll
+          for (int j = 0; j < 16; ++j) {
+            const float c = cw[tt][j >> 2][j & 3];
+            const float dlt = r[tt][j] - c;
+            dist = fmaf(dlt, dlt, dist);
+            r[tt][j] = fmaf(-sel, c, r[tt][j]);  // exact: sel is 0 or 1
+          }
+          dist += xor32(dist);
+          n_exact += __popcll(__ballot(valid && h == 0));
+          if (valid && (dist < bestd[tt] || (dist == bestd[tt] && kk[tt] < bestk[tt]))) {
+            bestd[tt] = dist;
+            bestk[tt] = kk[tt];
+          }
+          if (commit) done[tt] = 1;
+        }
+      }
+      if (!single_chunk && lane < SCR_TT * 16) lds_cnt[(wtok >> 1) + lane] = 0u;  // new lists per chunk
     }
 
-    PHASE_MARK(4);  // resolve, LDS part
     // ---- exact search by the whole wavefront for the tokens the screen could not settle
     {
       bool any_slow = false;
 #pragma unroll
       for (int tt = 0; tt < SCR_TT; ++tt) {
-        if (nc[tt] == 0) slow[tt] = 1;
+        if (!(bestd[tt] < INFINITY)) slow[tt] = 1;  // no candidate in any chunk
         any_slow = any_slow || slow[tt];
       }
 #ifdef RVQ_SKIP_SLOW
@@ -521,81 +650,24 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
               const int ok = __shfl_xor(bk, o, 64);
               if (od < bd || (od == bd && ok < bk)) { bd = od; bk = ok; }
             }
-            if (lane == src || lane == src + 32) {
-              // the single candidate of this token; step 2 below scores it like any other
-              if (lane == src)
-                lds_c[(wave * (SCR_TT * 32) + rot * 32 + src) * SCR_CAND] = (uint16_t)(bk == 0x7fffffff ? 0 : bk);
-              nc[0] = 1;
-            }
+            if (lane == src || lane == src + 32) bestk[0] = bk == 0x7fffffff ? 0 : bk;
           }
-          ROT4(slow); ROT4(nc);
+          ROT4(slow); ROT4(bestk);
 #pragma unroll
           for (int j = 0; j < 16; ++j) {
             const float t0 = r[0][j];
-            r[0][j] = r[1][j]; r[1][j] = r[2][j]; r[2][j] = r[3][j]; r[3][j] = t0;
+#pragma unroll
+            for (int t2 = 0; t2 + 1 < SCR_TT; ++t2) r[t2][j] = r[t2 + 1][j];
+            r[SCR_TT - 1][j] = t0;
           }
         }
       }
     }
-
-    float bestd[SCR_TT];
-    int bestk[SCR_TT];
-    // ---- resolve, step 2 (global): exact fp32 score of every candidate, sum (r - c)^2 with the
-    // fp32 codeword; slot s of all four tokens is loaded in one batch, and slots beyond the
-    // first only when some token of the wavefront has them
-#pragma unroll
-    for (int tt = 0; tt < SCR_TT; ++tt) {
-      bestd[tt] = INFINITY;
-      bestk[tt] = 0;
-    }
-#pragma unroll 1
-    for (int slot = 0; slot < SCR_CAND; ++slot) {
-      bool need = false;
-#pragma unroll
-      for (int tt = 0; tt < SCR_TT; ++tt) need = need || nc[tt] > slot;
-      if (!__any(need)) break;
-      f32x4 cw[SCR_TT][4];
-      int kk[SCR_TT];
-#pragma unroll
-      for (int tt = 0; tt < SCR_TT; ++tt) {
-        const int cand = lds_c[(wave * (SCR_TT * 32) + tt * 32 + p) * SCR_CAND + slot];
-        kk[tt] = (nc[tt] > slot && cand < a.K) ? cand : 0;
-        const f32x4 *crow = reinterpret_cast<const f32x4 *>(
-            a.C32 + ((int64_t)stage * a.K + kk[tt]) * 32 + 16 * h);
-#pragma unroll
-        for (int c4 = 0; c4 < 4; ++c4) cw[tt][c4] = crow[c4];
-      }
-#pragma unroll
-      for (int tt = 0; tt < SCR_TT; ++tt) {
-        float dist = 0.f;
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          const float dlt = r[tt][j] - cw[tt][j >> 2][j & 3];
-          dist = fmaf(dlt, dlt, dist);
-        }
-        dist += xor32(dist);
-        const bool valid = nc[tt] > slot;
-        n_exact += __popcll(__ballot(valid && h == 0));
-        if (valid && (dist < bestd[tt] || (dist == bestd[tt] && kk[tt] < bestk[tt]))) {
-          bestd[tt] = dist;
-          bestk[tt] = kk[tt];
-        }
-      }
-    }
-
-#ifdef RVQ_DEBUG_DUMP
-    if (stage == a.stage_begin) {
-#pragma unroll
-      for (int tt = 0; tt < SCR_TT; ++tt) {
-        dbg[tt][8] = (float)nc[tt];
-        dbg[tt][11] = (float)slow[tt]; dbg[tt][12] = bestd[tt]; dbg[tt][13] = (float)bestk[tt];
-      }
-    }
-#endif
     n_search += SCR_TT * 32;
 
-    // ---- emit the code and subtract the fp32 codeword from the residual (Algorithm 1); the
-    // four rows are fetched in one batch
+    // ---- emit the code and subtract the fp32 codeword from the residual (Algorithm 1) where
+    // that has not happened yet; the four rows are fetched in one batch (row 0 stands in for
+    // the tokens that are done, so their lanes cost no memory traffic)
     {
       f32x4 cw[SCR_TT][4];
 #pragma unroll
@@ -604,15 +676,17 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
         int k = bestk[tt];
         k = k < 0 ? 0 : (k >= a.K ? a.K - 1 : k);
         if (v < a.V && h == 0) a.codes[v * a.depth + stage] = (int16_t)k;
-        const f32x4 *crow =
-            reinterpret_cast<const f32x4 *>(a.C32 + ((int64_t)stage * a.K + k) * 32 + 16 * h);
+        const f32x4 *crow = reinterpret_cast<const f32x4 *>(
+            a.C32 + ((int64_t)stage * a.K + (done[tt] ? 0 : k)) * 32 + 16 * h);
 #pragma unroll
         for (int c4 = 0; c4 < 4; ++c4) cw[tt][c4] = crow[c4];
       }
 #pragma unroll
-      for (int tt = 0; tt < SCR_TT; ++tt)
+      for (int tt = 0; tt < SCR_TT; ++tt) {
+        const float sel = done[tt] ? 0.0f : 1.0f;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) r[tt][j] -= cw[tt][j >> 2][j & 3];
+        for (int j = 0; j < 16; ++j) r[tt][j] = fmaf(-sel, cw[tt][j >> 2][j & 3], r[tt][j]);
+      }
     }
     PHASE_MARK(5);  // exact scores + code emit
   }
@@ -620,23 +694,23 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
   // statistics: one update per workgroup (the counters are shared by the whole grid)
   {
     __syncthreads();
-    unsigned *lds_c = reinterpret_cast<unsigned *>(smem);
-    if (tid < 5) lds_c[tid] = 0u;
+    unsigned *lds_s = reinterpret_cast<unsigned *>(smem);
+    if (tid < 5) lds_s[tid] = 0u;
     __syncthreads();
     if (lane == 0) {
-      atomicAdd(&lds_c[0], n_slow & 0xffffu);
-      atomicAdd(&lds_c[4], n_slow >> 16);
-      atomicAdd(&lds_c[1], n_exact);
-      atomicAdd(&lds_c[2], n_groups);
-      atomicAdd(&lds_c[3], n_search);
+      atomicAdd(&lds_s[0], n_slow);
+      atomicAdd(&lds_s[1], n_exact);
+      atomicAdd(&lds_s[2], n_groups);
+      atomicAdd(&lds_s[3], n_search);
+      atomicAdd(&lds_s[4], n_over);
     }
     __syncthreads();
-    if (tid < 4) atomicAdd(&a.counters[tid], (unsigned long long)lds_c[tid]);
-    if (tid == 4) atomicAdd(&a.counters[10], (unsigned long long)lds_c[4]);
+    if (tid < 4) atomicAdd(&a.counters[tid], (unsigned long long)lds_s[tid]);
+    if (tid == 4) atomicAdd(&a.counters[10], (unsigned long long)lds_s[4]);
   }
 #ifdef RVQ_PHASE_CLOCKS
   if (lane == 0)
-    for (int i = 0; i < 6; ++i) atomicAdd(&a.counters[4 + i], (unsigned long long)phase_acc[i]);
+    for (int i = 0; i < 9; ++i) atomicAdd(&a.counters[(i < 6 ? 4 : 5) + i], (unsigned long long)phase_acc[i]);
 #endif
   if (a.residual) {
 #pragma unroll
@@ -646,11 +720,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
         f32x4 *dst = reinterpret_cast<f32x4 *>(a.residual + v * 32 + 16 * h);
 #pragma unroll
         for (int c4 = 0; c4 < 4; ++c4) {
-#ifdef RVQ_DEBUG_DUMP
-          f32x4 w = {dbg[tt][c4 * 4 + 0], dbg[tt][c4 * 4 + 1], dbg[tt][c4 * 4 + 2], dbg[tt][c4 * 4 + 3]};
-#else
-          f32x4 w = {r[tt][c4 * 4 + 0], r[tt][c4 * 4 + 1], r[tt][c4 * 4 + 2], r[tt][c4 * 4 + 3]};
-#endif
+          const f32x4 w = {r[tt][c4 * 4 + 0], r[tt][c4 * 4 + 1], r[tt][c4 * 4 + 2], r[tt][c4 * 4 + 3]};
           dst[c4] = w;
         }
       }
