@@ -70,6 +70,7 @@ int rvq_create(rvq_ctx **out, const rvq_config *cfg) {
   ctx->dup = nullptr;
   ctx->perm16 = nullptr;
   ctx->counters = nullptr;
+  ctx->Csplit = nullptr;
   ctx->Kpad = (cfg->K + 31) / 32 * 32;
   ctx->tag_bits = 1;
   while ((1 << ctx->tag_bits) < ctx->Kpad / 32) ++ctx->tag_bits;
@@ -94,6 +95,9 @@ int rvq_create(rvq_ctx **out, const rvq_config *cfg) {
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->prep_tmp, (size_t)cfg->depth * ctx->Kpad * 2 * sizeof(float));
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->counters, 16 * sizeof(unsigned long long));
     if (e == hipSuccess) e = hipMemset(ctx->counters, 0, 16 * sizeof(unsigned long long));
+    // channel-split copy for the LDS decode path, when one channel pair of all stages fits LDS
+    if (e == hipSuccess && cb <= RVQ_SPLIT_MAX_LDS * 16)
+      e = hipMalloc((void **)&ctx->Csplit, cb);
   }
   if (e != hipSuccess) {
     if (ctx->C) (void)hipFree(ctx->C);
@@ -107,6 +111,7 @@ int rvq_create(rvq_ctx **out, const rvq_config *cfg) {
     if (ctx->dup) (void)hipFree(ctx->dup);
     if (ctx->perm16) (void)hipFree(ctx->perm16);
     if (ctx->counters) (void)hipFree(ctx->counters);
+    if (ctx->Csplit) (void)hipFree(ctx->Csplit);
     if (ctx->ws_ema) (void)hipFree(ctx->ws_ema);
     delete ctx;
     return e == hipErrorOutOfMemory ? RVQ_ENOMEM : RVQ_EHIP;
@@ -129,6 +134,7 @@ int rvq_destroy(rvq_ctx *ctx) {
   if (ctx->dup) (void)hipFree(ctx->dup);
   if (ctx->perm16) (void)hipFree(ctx->perm16);
   if (ctx->counters) (void)hipFree(ctx->counters);
+  if (ctx->Csplit) (void)hipFree(ctx->Csplit);
   if (ctx->ws_std) (void)hipFree(ctx->ws_std);
   if (ctx->ws_ema) (void)hipFree(ctx->ws_ema);
   delete ctx;

@@ -155,6 +155,144 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
 }
 
 
+// ---- channel-split kernel: strided grouping, dhat == 32, one channel pair per workgroup --------
+// The gather is what bounds decode: 32 KiB of fp32 codeword rows per token row against 2.5 KB
+// of HBM traffic, more than the L2 delivers.  Here a workgroup keeps channels (2a, 2a+1) of
+// ALL stages in LDS (depth * K * 8 bytes) and produces those two channels of every group, so
+// the gathers are 8-byte LDS reads.  With strided grouping the two channels of the G groups
+// are the contiguous output range [2a G, 2a G + 2 G) of the token row: full lines.
+// The codes are read once per channel pair (16 times in all); the 16 workgroups that share a
+// token range sit on the same XCD (block ids 8 apart) and walk it in step, so 15 of those
+// reads hit that XCD's L2.
+constexpr int SPL_THREADS = 1024;
+constexpr int SPL_UNROLL = 4;  // (token, group) pairs per thread and trip
+
+// KC: the codebook size when it is a power of two known at compile time (codes are then reduced
+// with a mask and the stage offsets become instruction immediates), 0 for any other size.
+// GS: log2 of the group count when that is a power of two, -1 otherwise.
+// DU: the number of stages summed when known at compile time (straight-line gathers), else 0.
+template <bool OUT_F16, int KC, int GS, int DU>
+__global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
+    const int16_t *__restrict__ codes, const void *__restrict__ std_in, int std_dtype, int64_t N,
+    int G, const float *__restrict__ Csplit, int Krt, int depth, int depth_used_rt,
+    void *__restrict__ out, int64_t ldo) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int depth_used = DU ? DU : depth_used_rt;
+  // the table [depth][K] starts at LDS address 0: this kernel has no other LDS, and a literal
+  // base keeps the stage offsets in the instructions' immediate fields
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  typedef __attribute__((address_space(3))) const f32x2 lds_f2;
+  lds_f2 *tab = reinterpret_cast<lds_f2 *>(0);
+  const int K = KC ? KC : Krt;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int b = blockIdx.x;
+  const int xcd = b & 7;
+  const int a = (b >> 3) & 15;           // channel pair of this workgroup
+  const int part = b >> 7;               // which share of the XCD's token range
+  const int parts = gridDim.x >> 7;
+
+  {  // table of this channel pair: a linear copy, straight from global memory into LDS
+    const int bytes = depth * K * 8;
+    const char *src = reinterpret_cast<const char *>(Csplit) + (size_t)a * bytes;
+    for (int off = wave * 1024; off < bytes; off += (SPL_THREADS / 64) * 1024)
+      if (off + lane * 16 < bytes)
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void *)(src + off + lane * 16),
+            (__attribute__((address_space(3))) void *)(smem + off), 16, 0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+    __syncthreads();
+  }
+
+  using out_t = typename std::conditional<OUT_F16, uint16_t, float>::type;
+  const int64_t V = N * G;  // (token, group) pairs; the codes of pair e start at codes + e * depth
+  constexpr int TRIP = SPL_THREADS * SPL_UNROLL;
+  const int64_t trips = (V + TRIP - 1) / TRIP;
+  const bool odd = lane & 1;
+  const int chan = (2 * a + (odd ? 1 : 0)) * G;  // first output channel of this lane's pair
+  // trips c = xcd (mod 8) belong to this XCD; its `parts` workgroups per channel pair take them
+  // in turn.  Everything inside a trip is addressed with 32-bit offsets from per-trip bases.
+  i32x4 cur[SPL_UNROLL], nxt[SPL_UNROLL];
+  auto load_trip = [&](int64_t c, i32x4 *dst) {
+    const i32x4 *src = reinterpret_cast<const i32x4 *>(codes) + c * TRIP;  // depth == 8: 16 bytes
+    const int64_t left = V - c * TRIP;
+#pragma unroll
+    for (int u = 0; u < SPL_UNROLL; ++u) {
+      const int q = u * SPL_THREADS + tid;
+      const i32x4 zero = {0, 0, 0, 0};
+      // plain loads: the other 15 channel-pair workgroups of this XCD find the line in its L2
+      dst[u] = (c < trips && q < left) ? src[q] : zero;
+    }
+  };
+  const int64_t step = 8 * (int64_t)parts;
+  int64_t c = xcd + 8 * (int64_t)part;
+  load_trip(c, cur);
+  for (; c < trips; c += step) {
+    load_trip(c + step, nxt);
+    const int64_t e0 = c * TRIP;
+    const int64_t left = V - e0;
+    int64_t n0 = 0;
+    if constexpr (GS >= 0) n0 = e0 >> GS;  // TRIP is a multiple of G: a trip starts at a token boundary
+    out_t *out0 = reinterpret_cast<out_t *>(out) + n0 * ldo;
+#pragma unroll
+    for (int u = 0; u < SPL_UNROLL; ++u) {
+      const int q = u * SPL_THREADS + tid;
+      const bool valid = q < left;
+      int nl, g;  // token relative to n0, group
+      if constexpr (GS >= 0) {
+        nl = q >> GS;
+        g = q & ((1 << GS) - 1);
+      } else {
+        const int64_t n = (e0 + q) / G;
+        g = (int)(e0 + q - n * G);
+        nl = (int)n;  // n0 == 0 here; rows beyond 2^31 are refused by the launcher
+      }
+      const unsigned wd[4] = {(unsigned)cur[u].x, (unsigned)cur[u].y, (unsigned)cur[u].z,
+                              (unsigned)cur[u].w};
+      float2 acc = make_float2(0.f, 0.f);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (i < depth_used) {
+          const unsigned half = (i & 1) ? (wd[i >> 1] >> 16) : (wd[i >> 1] & 0xffffu);
+          int k;
+          if (KC) k = (int)(half & (unsigned)(KC - 1));
+          else k = clamp_code((int)(int16_t)half, K);
+          const f32x2 t = tab[i * K + k];
+          if (DU && i == 0) {
+            acc = make_float2(t.x, t.y);  // 0 + t, without the addition
+          } else {
+            acc.x += t.x;
+            acc.y += t.y;
+          }
+        }
+      }
+      const float sd = valid ? load_std(std_in, std_dtype, n0 + nl) : 0.f;
+      acc.x *= sd;
+      acc.y *= sd;
+      // pair exchange: the even lane ends up with channel 2a of groups (g, g + 1), the odd lane
+      // with channel 2a + 1 of groups (g - 1, g): two adjacent outputs each
+      const float give = odd ? acc.x : acc.y;
+      const float got = __shfl_xor(give, 1, 64);
+      const float lo = odd ? got : acc.x;
+      const float hi = odd ? acc.y : got;
+      if (valid) {
+        out_t *o = out0 + ((int64_t)nl * ldo + chan + (g & ~1));
+        if (OUT_F16) {
+          const uint32_t pk = (uint32_t)__half_as_ushort(__float2half_rn(lo)) |
+                              ((uint32_t)__half_as_ushort(__float2half_rn(hi)) << 16);
+          __builtin_nontemporal_store(pk, reinterpret_cast<uint32_t *>(o));
+        } else {
+          const f32x2 v = {lo, hi};
+          __builtin_nontemporal_store(v, reinterpret_cast<f32x2 *>(o));
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < SPL_UNROLL; ++u) cur[u] = nxt[u];
+  }
+}
+
 }  // namespace
 
 hipError_t rvq_launch_decode(const rvq_ctx *ctx, const int16_t *dCodes, const void *dStd,
@@ -164,6 +302,30 @@ hipError_t rvq_launch_decode(const rvq_ctx *ctx, const int16_t *dCodes, const vo
   const int G = ctx->G;
   const size_t osz = f16 ? 2 : 4;
   const bool strided = c.grouping == RVQ_STRIDED && G > 1;
+  // LDS path: strided grouping, depth-8 codes in one 16-byte word, even G, a channel-pair table
+  // that fits LDS, and enough rows to pay for filling 256 tables
+  const size_t tab_bytes = (size_t)c.depth * c.K * 8;
+  if (ctx->Csplit && strided && c.dhat == 32 && c.depth == 8 && (G % 2) == 0 &&
+      tab_bytes <= RVQ_SPLIT_MAX_LDS && (ldo * osz) % 8 == 0 && N * (int64_t)G >= (1 << 19)) {
+    int g_shift = -1;
+    if ((G & (G - 1)) == 0 && G <= SPL_THREADS * SPL_UNROLL) { g_shift = 0; while ((1 << g_shift) < G) ++g_shift; }
+    if (g_shift < 0 && N > 0x7fffffffLL) return hipErrorInvalidValue;
+    const dim3 grid(256), block(SPL_THREADS);
+    hipError_t e;
+#define RVQ_LAUNCH_SPLIT(F16, KC, GS, DU)                                                           \
+  e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_split_kernel<F16, KC, GS, DU>),      \
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)tab_bytes);            \
+  if (e != hipSuccess) return e;                                                                  \
+  hipLaunchKernelGGL((decode_split_kernel<F16, KC, GS, DU>), grid, block, tab_bytes, s, dCodes, dStd, \
+                     c.std_dtype, N, G, ctx->Csplit, c.K, c.depth, depth_used, dOut, ldo)
+    if (c.K == 2048 && g_shift == 5 && depth_used == 8) {
+      if (f16) { RVQ_LAUNCH_SPLIT(true, 2048, 5, 8); } else { RVQ_LAUNCH_SPLIT(false, 2048, 5, 8); }
+    } else {
+      if (f16) { RVQ_LAUNCH_SPLIT(true, 0, -1, 0); } else { RVQ_LAUNCH_SPLIT(false, 0, -1, 0); }
+    }
+#undef RVQ_LAUNCH_SPLIT
+    return hipGetLastError();
+  }
   // padded LDS row: row stride of 4 rows must move by one 16-byte bank group (see header)
   int lds_row = 0;
   size_t lds_bytes = 0;

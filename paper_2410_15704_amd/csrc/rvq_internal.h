@@ -7,6 +7,9 @@
 
 #include "rvq.h"
 
+// largest channel-pair table (bytes) the LDS decode path keeps resident: depth * K * 8
+constexpr size_t RVQ_SPLIT_MAX_LDS = 144 * 1024;
+
 struct rvq_ctx {
   rvq_config cfg;
   int32_t G;           // d / dhat
@@ -32,6 +35,10 @@ struct rvq_ctx {
   int32_t Kpad;
   int32_t tag_bits;    // low mantissa bits that carry the tile number
   float kappa;         // relative bound on accumulation + tagging error of a screened score
+
+  // channel-split copy for the LDS decode path (dhat == 32 and depth * K * 8 bytes fit LDS):
+  // Csplit[a][i][k] = (C_i[k][2a], C_i[k][2a+1]), so the table of one channel pair is contiguous
+  float *Csplit;       // [16][depth][K][2]
 
   unsigned long long *counters;  // [4] statistics of the screen path since rvq_create
 

@@ -190,6 +190,19 @@ __global__ void screen_groups_kernel(const float *__restrict__ tmp, int Kpad, in
   }
 }
 
+// channel-split copy of the fp32 codebooks: Csplit[a][i][k] = (C_i[k][2a], C_i[k][2a+1]); one
+// thread per codeword moves the 128-byte row as 16 float2 pieces
+__global__ void split_kernel(const float *__restrict__ C, float *__restrict__ Csplit, int K,
+                             int depth, int stage_begin, int stage_end) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t count = (int64_t)(stage_end - stage_begin) * K * 16;
+  if (e >= count) return;
+  const int a = (int)(e & 15);
+  const int64_t ik = (int64_t)stage_begin * K + (e >> 4);  // i * K + k
+  const float2 v = *reinterpret_cast<const float2 *>(C + ik * 32 + 2 * a);
+  *reinterpret_cast<float2 *>(Csplit + (((int64_t)a * depth * K) + ik) * 2) = v;
+}
+
 }  // namespace
 
 hipError_t rvq_launch_prepare_codebook(const rvq_ctx *ctx, int stage_begin, int stage_end,
@@ -214,5 +227,8 @@ hipError_t rvq_launch_prepare_codebook(const rvq_ctx *ctx, int stage_begin, int 
     hipLaunchKernelGGL(screen_groups_kernel, blocks(np / 16), dim3(block), 0, s, ctx->prep_tmp,
                        ctx->Kpad, stage_begin, stage_end, ctx->kappa, ctx->normp, ctx->groupA);
   }
+  if (ctx->Csplit)
+    hipLaunchKernelGGL(split_kernel, blocks((int64_t)ns * K * 16), dim3(block), 0, s, ctx->C,
+                       ctx->Csplit, (int)K, ctx->cfg.depth, stage_begin, stage_end);
   return hipGetLastError();
 }
