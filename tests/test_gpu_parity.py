@@ -57,7 +57,7 @@ def _half_ulp_distance(a_bits, b_bits):
 
 
 def check_encode(Xs, in_dtype, d, dhat, depth, K, grouping, C32, *, path=0, sample_rows=None,
-                 std_dtype="fp32", min_equal=0.9999):
+                 std_dtype="fp32", min_equal=0.9999, mismatch_cap=None):
     """Run rvq_encode on the GPU for all rows, the oracle on `sample_rows` (all if None)."""
     torch, b = _torch(), _b()
     N = Xs.shape[0]
@@ -86,7 +86,9 @@ def check_encode(Xs, in_dtype, d, dhat, depth, K, grouping, C32, *, path=0, samp
     # (i) agreement with the free-running oracle codes
     neq = g_codes != ref["codes"]
     entries = neq.size
-    if entries >= 100000:
+    if mismatch_cap is not None:  # inputs built to be full of near-ties: (ii) and (iii) decide
+        assert neq.sum() <= mismatch_cap
+    elif entries >= 100000:
         assert 1.0 - neq.mean() >= min_equal, f"only {1 - neq.mean():.6f} of codes agree"
     else:
         assert neq.sum() <= max(2, int(entries * 1e-4))
@@ -240,6 +242,76 @@ def test_encode_degenerate_rows(gpu_device):
     assert std.cpu().numpy().tolist() == [1.0, 1.0]
     assert np.array_equal(codes.cpu().numpy(), ref["codes"])
     q.close()
+
+
+@pytest.mark.parametrize("path", [1, 2])  # RVQ_PATH_EXACT, RVQ_PATH_SCREEN
+def test_encode_both_paths_against_oracle(gpu_device, path):
+    """The fp32 scan and the matrix-core screen are held to the same bar, on the same input."""
+    X, _ = synth.llama_key(2048, 1024)
+    Xw = synth.widen(X, "bf16")
+    C = _codebooks_from_samples(Xw, 32, oracle.STRIDED, 4, 512, seed=21, rows=512)
+    rows = np.arange(0, 2048, 8)
+    r = check_encode(X, "bf16", 1024, 32, 4, 512, oracle.STRIDED, C, path=path, sample_rows=rows)
+    print("path", path, r)
+
+
+def test_encode_screen_crowded_codebook_takes_every_fallback(gpu_device):
+    """Codebooks made of tight clusters (32 near-copies of 64 centres, 1e-3 apart): the fp16
+    screen cannot tell the copies apart, so tokens have many candidates and many groups inside
+    their window.  That drives the candidate-list overflow pass, the queue of extra groups and
+    the exact wavefront search; the exact fp32 scoring must still pick the oracle's codeword."""
+    torch, b = _torch(), _b()
+    rng = np.random.Generator(np.random.PCG64(synth.BASE_SEED + 77))
+    depth, K, dhat, d, N = 2, 2048, 32, 1024, 192
+    C = np.empty((depth, K, dhat), dtype=np.float32)
+    for s in range(depth):
+        centres = rng.standard_normal((64, dhat)) * (0.8 ** s)
+        copies = centres[:, None, :] * (1.0 + 1e-3 * rng.standard_normal((64, 32, dhat)))
+        C[s] = copies.reshape(K, dhat)[rng.permutation(K)].astype(np.float32)
+    X = synth.gaussian_rows(N, d, seed=4242, dtype="fp32", outliers=4)
+    # 32 copies 1e-3 apart make real near-ties (fp32 against fp64 rounding) a few times in 12288
+    # searches: the count is capped loosely, every mismatch must still be a proven near-tie
+    r = check_encode(X, "fp32", d, dhat, depth, K, oracle.CONTIGUOUS, C, path=2, mismatch_cap=40)
+    r1 = check_encode(X, "fp32", d, dhat, depth, K, oracle.CONTIGUOUS, C, path=1, mismatch_cap=40)
+    print("exact path on the same input:", r1)
+    # the fallbacks really ran
+    q = b.Quantizer(d=d, dhat=dhat, depth=depth, K=K, grouping=b.CONTIGUOUS, in_dtype=b.F32,
+                    encode_path=b.PATH_SCREEN)
+    q.set_codebooks(torch.from_numpy(C).cuda())
+    q.encode(torch.from_numpy(X).cuda())
+    torch.cuda.synchronize()
+    cnt = b.rvq_get_counters(q.ctx)
+    q.close()
+    print("crowded codebook:", r, cnt)
+    assert cnt["searches"] == N * (d // dhat) * depth
+    assert cnt["group_exact_passes"] > cnt["searches"] // 2   # candidate lists overflowed
+    assert cnt["slow_searches"] > 0                            # more groups than are tracked
+    assert cnt["groups_rescored"] > cnt["searches"]            # extra groups went through the queue
+
+
+def test_encode_screen_duplicate_zero_and_dead_codewords(gpu_device):
+    """Exact duplicates (the smallest index must win), an all-zero stage and codewords far from
+    every input (dead codes) on the matrix-core path."""
+    X = synth.gaussian_rows(300, 256, seed=77, dtype="fp32", outliers=2)
+    Xw = X.astype(np.float64)
+    C = _codebooks_from_samples(Xw, 32, oracle.STRIDED, 3, 96, seed=5)
+    C[0, 40:60] = C[0, 10:30]          # duplicates of earlier rows
+    C[0, 90:] = 1.0e4                   # dead, huge
+    C[1, :] = 0.0                       # a stage of zeros: every code is 0
+    C[2, 5] = 0.0
+    C[2, 6] = 0.0
+    torch, b = _torch(), _b()
+    r = check_encode(X, "fp32", 256, 32, 3, 96, oracle.STRIDED, C, path=2)
+    q = b.Quantizer(d=256, dhat=32, depth=3, K=96, grouping=b.STRIDED, in_dtype=b.F32,
+                    encode_path=b.PATH_SCREEN)
+    q.set_codebooks(torch.from_numpy(C).cuda())
+    codes, _, _ = q.encode(torch.from_numpy(X).cuda())
+    cz = codes.cpu().numpy()
+    q.close()
+    assert (cz[:, :, 1] == 0).all()
+    assert not np.isin(cz[:, :, 0], np.arange(40, 60)).any()
+    print("duplicates / zeros:", r)
+
 
 
 def test_encode_stage_range_continues_from_residual(gpu_device):
