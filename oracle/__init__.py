@@ -206,5 +206,33 @@ def sample_init_codebooks(Z, depth: int, K: int, rng: np.random.Generator):
     return C
 
 
+def kmeans_init_codebooks(Z, depth: int, K: int, iters: int, picks):
+    """Section 3's initialisation, stage by stage: the codebook of stage s starts from K rows
+    `picks[s]` of the vectors entering stage s and is refined by `iters` Lloyd steps on those
+    vectors (assign every vector to its nearest codeword, replace each codeword by the mean of
+    its vectors); the vectors are then quantized with the result and their residuals enter stage
+    s + 1.  A Lloyd step is the moving-average update with decay 0 and no smoothing, so a
+    codeword that no vector chose becomes 0 (no revival).  Z [V][dhat] float64.
+    Returns (C [depth][K][dhat] float64, mse [depth][iters + 1]): mean squared quantization
+    error of each stage before the first step and after every step."""
+    Z = _f64(Z)
+    V, dhat = Z.shape
+    C = np.empty((depth, K, dhat), dtype=np.float64)
+    mse = np.empty((depth, iters + 1), dtype=np.float64)
+    R = Z
+    for s in range(depth):
+        Cs = R[np.asarray(picks[s])].copy()
+        for it in range(iters):
+            out = encode(R, Cs[None], dhat, CONTIGUOUS, scale=False, want_residual=True)
+            mse[s, it] = np.mean(out["residual"] ** 2)
+            _, _, Cs = ema_update(R, out["codes"].reshape(V), K, 0.0, 0.0,
+                                  np.zeros(K), np.zeros((K, dhat)))
+        out = encode(R, Cs[None], dhat, CONTIGUOUS, scale=False, want_residual=True)
+        mse[s, iters] = np.mean(out["residual"] ** 2)
+        C[s] = Cs
+        R = out["residual"].reshape(V, dhat)
+    return C, mse
+
+
 if __name__ == "__main__":
     print(build(force="--force" in sys.argv))

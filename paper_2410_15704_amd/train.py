@@ -84,3 +84,34 @@ def ema_train_sequential(R0: torch.Tensor, depth: int, K: int, iters: int, decay
     torch.cuda.synchronize()
     q.close()
     return C
+
+
+def kmeans_init_codebooks(Z: torch.Tensor, depth: int, K: int, iters: int, picks,
+                          encode_path: int = b.PATH_AUTO) -> torch.Tensor:
+    """The initialisation Section 3 describes, stage by stage: the codebook of stage s starts
+    from rows `picks[s]` (K indices) of the vectors entering stage s and is refined by `iters`
+    Lloyd steps on them; a Lloyd step is rvq_encode over that one stage (assignment) followed by
+    rvq_ema_update with decay 0 and no smoothing (each codeword becomes the mean of its vectors;
+    one that no vector chose becomes 0).  The vectors are then quantized with the result and
+    their residuals enter stage s + 1.  Z float32 [V][dhat] on the device.
+    Returns C [depth][K][dhat]."""
+    V, dhat = Z.shape
+    q = b.Quantizer(d=dhat, dhat=dhat, depth=depth, K=K, scale=0, encode_path=encode_path)
+    C = torch.zeros((depth, K, dhat), dtype=torch.float32, device=Z.device)
+    codes = torch.empty((V, 1, depth), dtype=torch.int16, device=Z.device)
+    R = Z.contiguous()
+    for s in range(depth):
+        pick = torch.as_tensor(picks[s], dtype=torch.int64, device=Z.device)
+        C[s] = R.index_select(0, pick)
+        q.set_codebooks(C)
+        for _ in range(iters):
+            q.encode(R, stages=(s, s + 1), codes=codes)
+            cs = torch.zeros(K, dtype=torch.float32, device=Z.device)
+            es = torch.zeros((K, dhat), dtype=torch.float32, device=Z.device)
+            b.rvq_ema_update(q.ctx, s, R, codes.data_ptr() + 2 * s, depth, V, 0.0, 0.0, cs, es)
+        _, _, res = q.encode(R, want_residual=True, stages=(s, s + 1), codes=codes)
+        R = res.view(V, dhat)
+        C = q.get_codebooks()
+    torch.cuda.synchronize()
+    q.close()
+    return C

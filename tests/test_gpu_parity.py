@@ -497,6 +497,23 @@ def test_ema_mixture_workload_one_pass(gpu_device):
     q.close()
 
 
+def test_kmeans_init_matches_oracle(gpu_device):
+    """Section 3's k-means initialisation driven through rvq_encode + rvq_ema_update (decay 0)
+    against the oracle's, from the same picked rows: codebooks within 1e-5 per stage."""
+    torch = _torch()
+    from paper_2410_15704_amd import train
+    R = synth.gaussian_mixture(M=30000)
+    depth, K, iters = 2, 96, 4
+    rng = np.random.Generator(np.random.PCG64(41))
+    picks = [np.sort(rng.choice(30000, K, replace=False)) for _ in range(depth)]
+    Cg = train.kmeans_init_codebooks(torch.from_numpy(R).cuda(), depth, K, iters, picks).cpu().numpy()
+    Co, mse = oracle.kmeans_init_codebooks(R.astype(np.float64), depth, K, iters, picks)
+    for s in range(depth):
+        rel = np.linalg.norm(Cg[s] - Co[s]) / np.linalg.norm(Co[s])
+        print(f"k-means stage {s}: rel {rel:.2e}, oracle mse per step {np.round(mse[s], 5).tolist()}")
+        assert rel <= 1e-5
+
+
 # ------------------------------------------------------------------------------------ boundary
 def test_error_codes_on_device(gpu_device):
     torch, b = _torch(), _b()

@@ -370,3 +370,40 @@ def test_sample_init_codebooks_are_rows_of_the_stage_inputs():
         dec = oracle.decode(full["codes"], full["std"], C, 4, CONTIGUOUS, depth_used=used)
         err.append(np.mean((Z - dec) ** 2))
     assert err[0] > err[1] > err[2]
+
+
+# ---- Section 3: k-means initialisation ----------------------------------------------------------
+def test_kmeans_init_matches_library_lloyd_and_never_raises_the_error():
+    """One stage of the oracle's k-means initialisation, started from given rows, equals SciPy's
+    Lloyd iteration started from the same rows (no cluster empties on this input), and the mean
+    squared quantization error never rises from one Lloyd step to the next (the textbook
+    invariant of Lloyd's algorithm)."""
+    from scipy.cluster.vq import kmeans2
+    rng = np.random.Generator(np.random.PCG64(31))
+    centres = rng.standard_normal((12, 8)) * 2.0
+    label = rng.integers(0, 12, 3000)
+    Z = centres[label] + 0.4 * rng.standard_normal((3000, 8))
+    # one starting row per component, moved well off its centre by the noise
+    picks = [np.sort(np.array([np.flatnonzero(label == c)[0] for c in range(12)]))]
+    for iters in (1, 3, 6):
+        C, mse = oracle.kmeans_init_codebooks(Z, 1, 12, iters, picks)
+        ref, _ = kmeans2(Z, Z[picks[0]].copy(), iter=iters, minit="matrix", missing="raise")
+        np.testing.assert_allclose(C[0], ref, rtol=1e-12, atol=1e-12)
+        assert np.all(np.diff(mse[0]) <= 1e-15)
+        assert mse[0, -1] < mse[0, 0]
+
+
+def test_kmeans_init_stages_chain_through_residuals():
+    """Stage 1 of a depth-2 initialisation is the one-stage procedure applied to the residuals
+    that stage 0 leaves; with zero Lloyd steps the codebooks are the picked rows themselves."""
+    rng = np.random.Generator(np.random.PCG64(32))
+    Z = rng.standard_normal((800, 4))
+    picks = [np.sort(rng.choice(800, 16, replace=False)) for _ in range(2)]
+    C, mse = oracle.kmeans_init_codebooks(Z, 2, 16, 2, picks)
+    out = oracle.encode(Z, C[:1], 4, oracle.CONTIGUOUS, scale=False, want_residual=True)
+    R1 = out["residual"].reshape(800, 4)
+    C1, mse1 = oracle.kmeans_init_codebooks(R1, 1, 16, 2, picks[1:])
+    np.testing.assert_array_equal(C[1], C1[0])
+    assert mse[1, 0] <= mse[0, -1] + 1e-15       # a picked residual row can only help
+    C0, _ = oracle.kmeans_init_codebooks(Z, 2, 16, 0, picks)
+    np.testing.assert_array_equal(C0[0], Z[picks[0]])
