@@ -71,7 +71,7 @@ int rvq_create(rvq_ctx **out, const rvq_config *cfg) {
   ctx->perm16 = nullptr;
   ctx->counters = nullptr;
   ctx->Csplit = nullptr;
-  ctx->Kpad = (cfg->K + 31) / 32 * 32;
+  ctx->Kpad = (cfg->K + 63) / 64 * 64;  // whole pairs of 32-codeword tiles
   ctx->tag_bits = 1;
   while ((1 << ctx->tag_bits) < ctx->Kpad / 32) ++ctx->tag_bits;
   // norm rounding 2^-24, fp32 accumulation of 33 terms <= 2^-17, tile tag 2^(bits-23), 25 % spare

@@ -18,11 +18,14 @@
 //     tight bound e_g; the quantity that is tracked per group is the lower bound
 //     LB_g = (smallest screened score of the group) - e_g.  The exact winner lies in a group
 //     with LB_g <= UB, UB = LB + 2 e of the group with the smallest LB.  Those few groups are
-//     re-scored from the same LDS copy with packed fp16 dot products, and every codeword whose
-//     own lower bound is <= UB is scored exactly (fp32, direct form sum (r - c)^2, fp32
-//     codebook), ties going to the smallest index.  A token with more candidate groups in one
-//     lane than the three tracked ones, or whose residual does not fit fp16, is searched
-//     exactly by the whole wavefront instead.
+//     re-scored from the same LDS copy with packed fp16 dot products (the best group of every
+//     token in place, the 3 % of further groups from a per-wavefront queue, 32 at a time), and
+//     every codeword whose lower bound is <= UB is scored exactly (fp32, direct form
+//     sum (r - c)^2, fp32 codebook), ties going to the smallest index.  A token with a single
+//     candidate (97 %) needs no score at all: the row is fetched once and subtracted.  A token
+//     with more candidates than its list holds has all rows of its window groups scored exactly
+//     by the wavefront; one with more groups in a lane than the three tracked ones, or whose
+//     residual does not fit fp16, is searched exactly over the whole codebook.
 //
 // The residual stays in registers (fp32) across all stages and is updated with the fp32
 // codeword, so stages never round-trip through memory (the fusion Section 3 of the paper
@@ -41,17 +44,12 @@ typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-#ifndef RVQ_SCR_WAVES
-#define RVQ_SCR_WAVES 8
-#define RVQ_SCR_TT 4
-#define RVQ_SCR_QCAP 16
-#endif
-constexpr int SCR_WAVES = RVQ_SCR_WAVES;
-constexpr int SCR_TT = RVQ_SCR_TT;                     // token tiles per wavefront
+constexpr int SCR_WAVES = 8;
+constexpr int SCR_TT = 4;                              // token tiles per wavefront
 constexpr int SCR_TOKENS = SCR_WAVES * SCR_TT * 32;    // group vectors per workgroup
 constexpr int SCR_KC = 2048;                           // codewords resident in LDS
 constexpr int SCR_CAND = 4;                            // candidate codewords kept per token
-constexpr int SCR_QCAP = RVQ_SCR_QCAP;                         // queued (token, group) pairs per wavefront
+constexpr int SCR_QCAP = 16;                           // queued (token, group) pairs per wavefront
 constexpr size_t SCR_LDS_BYTES = (size_t)SCR_KC * 64 + (size_t)SCR_KC * 4 +
                                  (size_t)(SCR_KC / 16) * 4 + (size_t)SCR_KC * 2 +
                                  (size_t)SCR_TOKENS * SCR_CAND * 2 + (size_t)SCR_TOKENS * 2 +
@@ -118,6 +116,97 @@ __device__ __forceinline__ float dot8(const uint4 w, const half8 b, float acc) {
     _Pragma("unroll") for (int i_ = 0; i_ + 1 < SCR_TT; ++i_) x[i_] = x[i_ + 1]; \
     x[SCR_TT - 1] = t_;                                           \
   } while (0)
+
+// pieces of the sweep's reduction of one accumulator set: R1 folds the 16 scores of a lane into two
+// partial minima (reads the accumulators), R2 finishes the group's tagged lower bound and merges
+// it into the three smallest of token tile TT
+#define SWEEP_FENCE() __builtin_amdgcn_sched_barrier(0)
+#define SWEEP_R1(acc, tau)                                   \
+  float tau = min3f(acc[0], acc[1], acc[2]);                 \
+  float tau##b = min3f(acc[3], acc[4], acc[5]);              \
+  float tau##c = min3f(acc[6], acc[7], acc[8]);              \
+  float tau##d = min3f(acc[9], acc[10], acc[11]);            \
+  float tau##e = min3f(acc[12], acc[13], acc[14]);           \
+  tau = min3f(tau, tau##b, tau##c);                          \
+  tau##d = min3f(tau##d, tau##e, acc[15]);
+#define SWEEP_R2(tau, TT, tile_id, Agv)                      \
+  tau = fminf(tau, tau##d);                                  \
+  tau = fmaf(-g1[TT], Agv, tau); /* lower bound on the exact scores of the group */ \
+  tau = __uint_as_float((__float_as_uint(tau) & tag_mask_v) | (tile_id)); \
+  m3[TT] = med3f(m2[TT], m3[TT], tau);                       \
+  m2[TT] = med3f(m1[TT], m2[TT], tau);                       \
+  m1[TT] = fminf(m1[TT], tau);
+
+// operands of tile `tile` of the chunk in LDS.  A: two 8-byte reads per matrix-core operand
+// (16-byte reads run at half rate); norms: the 16 accumulator inputs of this lane half
+#define SWEEP_LOAD_A(X0, X1, tile)                                                              \
+  {                                                                                             \
+    const uint2 *ap_ = reinterpret_cast<const uint2 *>(lds_A) + (tile) * 256 + (lane ^ ((tile) & 31)); \
+    const uint2 q0_ = ap_[0], q1_ = ap_[64], q2_ = ap_[128], q3_ = ap_[192];                    \
+    X0 = __builtin_bit_cast(half8, make_uint4(q0_.x, q0_.y, q1_.x, q1_.y));                     \
+    X1 = __builtin_bit_cast(half8, make_uint4(q2_.x, q2_.y, q3_.x, q3_.y));                     \
+  }
+#define SWEEP_LOAD_N(tile)                                                                      \
+  {                                                                                             \
+    const f32x4 *np_ = reinterpret_cast<const f32x4 *>(lds_n + ((tile) * 2 + h) * 16);          \
+    const f32x4 w0_ = np_[0], w1_ = np_[1], w2_ = np_[2], w3_ = np_[3];                         \
+    cn[0] = w0_[0]; cn[1] = w0_[1]; cn[2] = w0_[2]; cn[3] = w0_[3];                             \
+    cn[4] = w1_[0]; cn[5] = w1_[1]; cn[6] = w1_[2]; cn[7] = w1_[3];                             \
+    cn[8] = w2_[0]; cn[9] = w2_[1]; cn[10] = w2_[2]; cn[11] = w2_[3];                           \
+    cn[12] = w3_[0]; cn[13] = w3_[1]; cn[14] = w3_[2]; cn[15] = w3_[3];                         \
+    Ag = lds_g[(tile) * 2 + h];                                                                 \
+  }
+// One tile of the sweep: A0 / A1 are its operands, N0 / N1 receive the next tile's.  Two
+// accumulator sets: A holds token tiles 0 and 2, B holds 1 and 3.  Every matrix-core
+// instruction is followed by half of the reduction of the set that finished two instructions
+// earlier, so the reduction never waits for a result and a set is free again before it is
+// overwritten:
+//   MFMA      A(0) a0   A(0) a1   B(1) a0   B(1) a1   A(2) a0   A(2) a1   B(3) a0   B(3) a1
+//   reduce    A(2)' R2  B(3)' R1  B(3)' R2  A(0) R1   A(0) R2   B(1) R1   B(1) R2   A(2) R1
+// (' = previous tile).  Two wavefronts per SIMD interleave their instruction pairs.
+#define SWEEP_TILE(A0, A1, N0, N1, t_)                                                          \
+  {                                                                                             \
+    const unsigned tid_p = (unsigned)(tile0 + max((t_) - 1, 0)), tid_c = (unsigned)(tile0 + (t_)); \
+    const float Agc = Ag;                                                                       \
+    const int tn = min((t_) + 1, ntiles - 1);                                                   \
+    SWEEP_FENCE();                                                                              \
+    accA = __builtin_amdgcn_mfma_f32_32x32x16_f16(A0, B0[0], cn, 0, 0, 0);                      \
+    SWEEP_FENCE();                                                                              \
+    { float v = u2, vd = u2d; SWEEP_R2(v, 2, tid_p, Agp) }                                      \
+    SWEEP_LOAD_A(N0, N1, tn)                                                                    \
+    SWEEP_FENCE();                                                                              \
+    accA = __builtin_amdgcn_mfma_f32_32x32x16_f16(A1, B1[0], accA, 0, 0, 0);                    \
+    SWEEP_FENCE();                                                                              \
+    SWEEP_R1(accB, u3)                                                                          \
+    SWEEP_FENCE();                                                                              \
+    accB = __builtin_amdgcn_mfma_f32_32x32x16_f16(A0, B0[1], cn, 0, 0, 0);                      \
+    SWEEP_FENCE();                                                                              \
+    SWEEP_R2(u3, 3, tid_p, Agp)                                                                 \
+    SWEEP_FENCE();                                                                              \
+    accB = __builtin_amdgcn_mfma_f32_32x32x16_f16(A1, B1[1], accB, 0, 0, 0);                    \
+    SWEEP_FENCE();                                                                              \
+    SWEEP_R1(accA, u0)                                                                          \
+    SWEEP_FENCE();                                                                              \
+    accA = __builtin_amdgcn_mfma_f32_32x32x16_f16(A0, B0[2], cn, 0, 0, 0);                      \
+    SWEEP_FENCE();                                                                              \
+    SWEEP_R2(u0, 0, tid_c, Agc)                                                                 \
+    SWEEP_FENCE();                                                                              \
+    accA = __builtin_amdgcn_mfma_f32_32x32x16_f16(A1, B1[2], accA, 0, 0, 0);                    \
+    SWEEP_FENCE();                                                                              \
+    SWEEP_R1(accB, u1)                                                                          \
+    SWEEP_FENCE();                                                                              \
+    accB = __builtin_amdgcn_mfma_f32_32x32x16_f16(A0, B0[3], cn, 0, 0, 0);                      \
+    SWEEP_FENCE();                                                                              \
+    /* the norms were last used by the instruction above: fetch the next tile's in place */     \
+    SWEEP_LOAD_N(tn)                                                                            \
+    SWEEP_R2(u1, 1, tid_c, Agc)                                                                 \
+    SWEEP_FENCE();                                                                              \
+    accB = __builtin_amdgcn_mfma_f32_32x32x16_f16(A1, B1[3], accB, 0, 0, 0);                    \
+    SWEEP_FENCE();                                                                              \
+    { SWEEP_R1(accA, w2) u2 = w2; u2d = w2d; }                                                  \
+    SWEEP_FENCE();                                                                              \
+    Agp = Agc;                                                                                  \
+  }
 
 template <int DT>
 __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const ScreenArgs a) {
@@ -192,9 +281,29 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
     dma(a.perm16 + (int64_t)st * a.Kpad + cb, lds_p, kcc * 2);
   };
   const bool single_chunk = a.Kpad <= SCR_KC;
-  bool prefetched = false;
+  // A stage has two phases.  Phase L works against the stage's operands in LDS (sweep on the
+  // matrix cores, fp16 re-scores); phase T touches only registers, the token's candidate list
+  // and the fp32 codebook in L2 (exact scores, code, residual update, operands of the next
+  // stage).  The eight wavefronts form two teams that take the phases in opposite order: while
+  // team 0 runs L of stage i, team 1 runs T of stage i - 1, then they swap, so the matrix-core
+  // work of one team shares the SIMDs with the latency-bound work of the other, and the
+  // workgroup meets only once per stage, to swap the operands in LDS.
+  // A codebook larger than LDS is swept in chunks with workgroup barriers inside phase L:
+  // there every wavefront is in team 0.
+  const int team = (single_chunk && wave >= SCR_WAVES / 2) ? 1 : 0;
 
-  for (int stage = a.stage_begin; stage < a.stage_end; ++stage) {
+  // ---- per-stage state of this wavefront's tokens
+  half8 B0[SCR_TT], B1[SCR_TT];  // fp16 residual (matrix-core B operands)
+  float g1[SCR_TT];     // token part of the error bound: e_k = g1 ||2c|| + k4 ||2c||^2 + g0
+  float g0[SCR_TT];     // ||fp16(r)|| * (largest norm of codeword elements dropped to zero)
+  int slow[SCR_TT];     // token goes to the exact wavefront search
+  float bestd[SCR_TT];  // exact distance and index of the best candidate scored so far
+  int bestk[SCR_TT];
+  int done[SCR_TT];     // the codeword has already been subtracted from the residual
+  int nc[SCR_TT];       // candidates found for the token (the list itself is in LDS)
+
+  // fp16 operands and error bounds of `stage` from the current residuals
+  auto convert = [&](int stage) {
     const float rho = a.stats[stage * 8 + 0];
     const bool usable = a.stats[stage * 8 + 1] != 0.0f;
     const float Fdrop = a.stats[stage * 8 + 2];
@@ -202,13 +311,6 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
     const float tiny = 6.103515625e-5f / Tscale;  // below this the scaled value is no normal half
 
     // ---- fp16 B operands and the per-token error bound
-    half8 B0[SCR_TT], B1[SCR_TT];
-    float g1[SCR_TT];     // token part of the error bound: e_k = g1 ||2c|| + k4 ||2c||^2 + g0
-    float g0[SCR_TT];     // ||fp16(r)|| * (largest norm of codeword elements dropped to zero)
-    int slow[SCR_TT];     // token goes to the exact wavefront search
-    float bestd[SCR_TT];  // exact distance and index of the best candidate scored so far
-    int bestk[SCR_TT];
-    int done[SCR_TT];     // the codeword has already been subtracted from the residual
 #pragma unroll
     for (int tt = 0; tt < SCR_TT; ++tt) {
       bestd[tt] = INFINITY;
@@ -242,63 +344,48 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
     if (lane < SCR_TT * 16) lds_cnt[(wtok >> 1) + lane] = 0u;  // this wavefront's candidate counts
 
     PHASE_MARK(1);  // operand conversion
+  };
+
+  // ---- phase L of a stage: everything that reads the stage's operands in LDS
+  auto lds_phase = [&](int stage) {
     for (int cbase = 0; cbase < a.Kpad; cbase += SCR_KC) {
       const int kc = min(SCR_KC, a.Kpad - cbase);
       const int ntiles = kc >> 5;
-      // ---- stage the chunk's operands in LDS: linear copies (the global layouts are already
-      // what the kernel reads), moved by direct global->LDS loads so no registers are tied up.
-      // With a single chunk per stage the copy for this stage was already started right after
-      // the previous stage stopped reading LDS and has been running behind its exact scoring.
-      if (!(prefetched && cbase == 0)) {
+      // ---- stage the chunk's operands in LDS (a codebook that fits LDS whole was staged by the
+      // caller of this phase): linear copies, the global layouts are already what the kernel
+      // reads, moved by direct global->LDS loads so no registers are tied up
+      if (!single_chunk) {
         __syncthreads();
         stage_to_lds(stage, cbase, kc);
+        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's direct loads have landed
+        __syncthreads();
       }
-      __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's direct loads have landed
-      __syncthreads();
       PHASE_MARK(2);  // staging + barriers
 
-      // ---- sweep: three smallest tagged group lower bounds per lane and token tile
+      // ---- sweep: three smallest tagged group lower bounds per lane and token tile.
+      // Software pipeline over two accumulator sets (see SWEEP_TILE); the fences pin its order.
       float m1[SCR_TT], m2[SCR_TT], m3[SCR_TT];
 #pragma unroll
       for (int tt = 0; tt < SCR_TT; ++tt) m1[tt] = m2[tt] = m3[tt] = BIG;
       const int tile0 = cbase >> 5;
-#ifdef RVQ_SKIP_SWEEP
-      for (int t = 0; t < 2; ++t) {
-#else
-      for (int t = 0; t < ntiles; ++t) {
-#endif
-        // the A operands: two 8-byte LDS reads each (16-byte reads run at half rate)
-        const uint2 *ap = reinterpret_cast<const uint2 *>(lds_A) + t * 256 + (lane ^ (t & 31));
-        const uint2 p00 = ap[0], p01 = ap[64], p10 = ap[128], p11 = ap[192];
-        const half8 a0 = __builtin_bit_cast(half8, make_uint4(p00.x, p00.y, p01.x, p01.y));
-        const half8 a1 = __builtin_bit_cast(half8, make_uint4(p10.x, p10.y, p11.x, p11.y));
-        f32x16 cn;
-        const f32x4 *np = reinterpret_cast<const f32x4 *>(lds_n + (t * 2 + h) * 16);
+      {
+        static_assert(SCR_TT == 4, "the sweep pipeline is written for four token tiles");
+        f32x16 accA, accB, cn;
 #pragma unroll
-        for (int b4 = 0; b4 < 4; ++b4) {
-          const f32x4 w = np[b4];
-          cn[b4 * 4 + 0] = w[0]; cn[b4 * 4 + 1] = w[1]; cn[b4 * 4 + 2] = w[2]; cn[b4 * 4 + 3] = w[3];
+        for (int e = 0; e < 16; ++e) { accA[e] = BIG; accB[e] = BIG; }
+        float Agp = 0.f;              // group bound of the previous tile
+        float u2 = BIG, u2d = BIG;    // partial minima of token tile 2 of the previous tile
+        float Ag;
+        half8 ax0, ax1, ay0, ay1;     // A operands of the even / odd tile in flight
+        SWEEP_LOAD_A(ax0, ax1, 0)
+        SWEEP_LOAD_N(0)
+        for (int t = 0; t < ntiles; t += 2) {  // the tile count of a chunk is even
+          SWEEP_TILE(ax0, ax1, ay0, ay1, t)
+          SWEEP_TILE(ay0, ay1, ax0, ax1, t + 1)
         }
-        const unsigned tile_id = (unsigned)(tile0 + t);
-        const float Ag = lds_g[t * 2 + h];
-#pragma unroll
-        for (int tt = 0; tt < SCR_TT; ++tt) {
-          f32x16 acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, B0[tt], cn, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, B1[tt], acc, 0, 0, 0);
-          float tau = min3f(acc[0], acc[1], acc[2]);
-          tau = min3f(tau, acc[3], acc[4]);
-          tau = min3f(tau, acc[5], acc[6]);
-          tau = min3f(tau, acc[7], acc[8]);
-          tau = min3f(tau, acc[9], acc[10]);
-          tau = min3f(tau, acc[11], acc[12]);
-          tau = min3f(tau, acc[13], acc[14]);
-          tau = fminf(tau, acc[15]);
-          tau = fmaf(-g1[tt], Ag, tau);  // lower bound on the exact scores of the group
-          tau = __uint_as_float((__float_as_uint(tau) & tag_mask_v) | tile_id);
-          m3[tt] = med3f(m2[tt], m3[tt], tau);
-          m2[tt] = med3f(m1[tt], m2[tt], tau);
-          m1[tt] = fminf(m1[tt], tau);
-        }
+        const unsigned tid_l = (unsigned)(tile0 + ntiles - 1);
+        { float v = u2, vd = u2d; SWEEP_R2(v, 2, tid_l, Agp) }
+        { SWEEP_R1(accB, u3) SWEEP_R2(u3, 3, tid_l, Agp) }
       }
 
       PHASE_MARK(3);  // sweep
@@ -405,13 +492,6 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
       // re-scored 32 at a time afterwards instead of one extra pass per token tile.
       // The loop body always works on entry 0 of the per-tile arrays, which are rotated.
       int qn = 0;  // queue entries of this wavefront (wave-uniform)
-#ifdef RVQ_SKIP_RESOLVE
-      for (int tt = 0; tt < SCR_TT; ++tt) {
-        lds_c[(wtok + tt * 32 + p) * SCR_CAND] = __float_as_uint(m1[tt]) & 1023u;
-        if (h == 0) atomicAdd(&lds_cnt[(wtok + tt * 32 + p) >> 1], 1u << (16 * (p & 1)));
-      }
-      if (false)
-#endif
 #pragma unroll 1
       for (int rot = 0; rot < SCR_TT; ++rot) {
         const int tok = rot * 32 + p;
@@ -469,7 +549,6 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
 
       PHASE_MARK(6);  // resolve: queued groups
       // candidates per token, as counted in LDS
-      int nc[SCR_TT];
       bool any_over = false;
 #pragma unroll
       for (int tt = 0; tt < SCR_TT; ++tt) {
@@ -540,14 +619,64 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
         }
       }
       PHASE_MARK(7);  // resolve: group-wide exact passes
-      prefetched = false;
-      if (single_chunk && stage + 1 < a.stage_end) {
-        __syncthreads();  // every wavefront has finished reading this stage's operands
-        stage_to_lds(stage + 1, 0, kc);
-        prefetched = true;
-      }
       PHASE_MARK(8);  // barrier + start of the next stage's copy
 
+      if (!single_chunk) {
+        // ---- resolve, step 2 (global): exact fp32 score of every candidate of the chunk,
+        // sum (r - c)^2 with the fp32 codeword; slot s of all four tokens is loaded in one batch,
+        // and slots beyond the first only when some token of the wavefront has them.  A token
+        // whose only candidate this is (97 % of them) has found its codeword: the row is
+        // subtracted from the residual right away, so it is fetched once, not twice.
+  #pragma unroll 1
+        for (int slot = 0; slot < SCR_CAND; ++slot) {
+          bool need = false;
+  #pragma unroll
+          for (int tt = 0; tt < SCR_TT; ++tt) need = need || (nc[tt] > slot && !slow[tt]);
+          if (!__any(need)) break;
+          f32x4 cw[SCR_TT][4];
+          int kk[SCR_TT];
+  #pragma unroll
+          for (int tt = 0; tt < SCR_TT; ++tt) {
+            const int cand = lds_c[(wtok + tt * 32 + p) * SCR_CAND + slot];
+            kk[tt] = (nc[tt] > slot && cand < a.K) ? cand : 0;
+            const f32x4 *crow = reinterpret_cast<const f32x4 *>(
+                a.C32 + ((int64_t)stage * a.K + kk[tt]) * 32 + 16 * h);
+  #pragma unroll
+            for (int c4 = 0; c4 < 4; ++c4) cw[tt][c4] = crow[c4];
+          }
+  #pragma unroll
+          for (int tt = 0; tt < SCR_TT; ++tt) {
+            const bool valid = nc[tt] > slot && !slow[tt];
+            const bool commit = single_chunk && slot == 0 && valid && nc[tt] == 1;
+            const float sel = commit ? 1.0f : 0.0f;
+            float dist = 0.f;
+  #pragma unroll
+            for (int j = 0; j < 16; ++j) {
+              const float c = cw[tt][j >> 2][j & 3];
+              const float dlt = r[tt][j] - c;
+              dist = fmaf(dlt, dlt, dist);
+              r[tt][j] = fmaf(-sel, c, r[tt][j]);  // exact: sel is 0 or 1
+            }
+            dist += xor32(dist);
+            n_exact += __popcll(__ballot(valid && h == 0));
+            if (valid && (dist < bestd[tt] || (dist == bestd[tt] && kk[tt] < bestk[tt]))) {
+              bestd[tt] = dist;
+              bestk[tt] = kk[tt];
+            }
+            if (commit) done[tt] = 1;
+          }
+        }
+
+        if (lane < SCR_TT * 16) lds_cnt[(wtok >> 1) + lane] = 0u;  // new lists per chunk
+      }
+    }
+  };
+
+  // ---- phase T of a stage
+  auto tail_phase = [&](int stage) {
+    if (single_chunk) {
+      const int kc = a.Kpad;
+      (void)kc;
       // ---- resolve, step 2 (global): exact fp32 score of every candidate of the chunk,
       // sum (r - c)^2 with the fp32 codeword; slot s of all four tokens is loaded in one batch,
       // and slots beyond the first only when some token of the wavefront has them.  A token
@@ -592,9 +721,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
           if (commit) done[tt] = 1;
         }
       }
-      if (!single_chunk && lane < SCR_TT * 16) lds_cnt[(wtok >> 1) + lane] = 0u;  // new lists per chunk
     }
-
     // ---- exact search by the whole wavefront for the tokens the screen could not settle
     {
       bool any_slow = false;
@@ -603,11 +730,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
         if (!(bestd[tt] < INFINITY)) slow[tt] = 1;  // no candidate in any chunk
         any_slow = any_slow || slow[tt];
       }
-#ifdef RVQ_SKIP_SLOW
-      if (false) {
-#else
       if (__any(any_slow)) {
-#endif
 #pragma unroll 1
         for (int rot = 0; rot < SCR_TT; ++rot) {
           unsigned long long pending = __ballot(slow[0] && h == 0);
@@ -689,6 +812,27 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
       }
     }
     PHASE_MARK(5);  // exact scores + code emit
+    if (stage + 1 < a.stage_end) convert(stage + 1);
+  };
+
+  convert(a.stage_begin);
+  const int nst = a.stage_end - a.stage_begin;
+  for (int hs = 0; hs <= 2 * nst; ++hs) {
+    const int i = hs >> 1;
+    const bool even = (hs & 1) == 0;
+    if (even && i < nst && single_chunk) {
+      // every wavefront has finished reading the previous stage's operands (team 1 just now)
+      __syncthreads();
+      stage_to_lds(a.stage_begin + i, 0, a.Kpad);
+      __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's direct loads have landed
+      __syncthreads();
+      PHASE_MARK(2);  // staging + barriers
+    }
+    // one call site per phase: the two teams differ only in which half-step runs which
+    const bool do_lds = team == 0 ? (even && i < nst) : !even;
+    const bool do_tail = team == 0 ? !even : (even && i >= 1);
+    if (do_lds) lds_phase(a.stage_begin + i);
+    if (do_tail) tail_phase(a.stage_begin + (team == 0 ? i : i - 1));
   }
 
   // statistics: one update per workgroup (the counters are shared by the whole grid)

@@ -20,7 +20,7 @@ struct rvq_ctx {
   float *C;            // [depth][K][dhat] fp32 codebooks (the values Algorithm 1 uses)
   float *norms;        // [depth][K] squared norms, computed in fp64 and rounded once
 
-  // matrix-core screen operands (dhat == 32 only), K padded to Kpad = 32 * ceil(K / 32)
+  // matrix-core screen operands (dhat == 32 only), K padded to Kpad = 64 * ceil(K / 64)
   // Within a stage the codewords are ordered by norm ("position"), so that the 16 codewords a
   // lane reduces together have similar norms and share a tight error bound.
   uint16_t *C16;       // [depth][Kpad/32][2][64][8] fp16(-2 c), matrix-core A-operand order
