@@ -29,6 +29,10 @@ if ROOT not in sys.path:
 
 PEAK_MFMA_16BIT_TFLOPS = 2500.0  # MI355X dense bf16 / fp16 matrix-core peak
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `--profile encode` and
+# `--profile decode`, scaled by the readings of a plain 1 GiB copy (profiles/*.txt hold the runs)
+TRAFFIC_ENCODE_W2 = 5.5979e5 * 2048 + 1.7143e6 * 1024            # encode_screen_kernel, workload 2
+TRAFFIC_DECODE_SLICE = 0.5 * ((1.3982e5 + 1.4338e5) * 2048) + 1.0486e6 * 1024  # mean of both kernels
 
 W2 = dict(N=32768, d=1024, dhat=32, depth=8, K=2048)
 
@@ -36,8 +40,8 @@ W2 = dict(N=32768, d=1024, dhat=32, depth=8, K=2048)
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-decode-stream", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--decode-slices", type=int, default=64)
@@ -134,7 +138,8 @@ def run_steps(args):
             ema_GBs=ema_bytes / (ema_ms * 1e-3) / 1e9,
         ),
         roofline=dict(bound="mfma", achieved=enc_tflops, peak=PEAK_MFMA_16BIT_TFLOPS,
-                      unit="TFLOP/s", frac=enc_tflops / PEAK_MFMA_16BIT_TFLOPS, traffic=None,
+                      unit="TFLOP/s", frac=enc_tflops / PEAK_MFMA_16BIT_TFLOPS,
+                      traffic=TRAFFIC_ENCODE_W2,
                       kernel="rvq_encode (all 8 stages, one launch per call)",
                       flops_per_launch=flops, avg_launch_ms=enc_ms),
     )
@@ -191,7 +196,7 @@ def run_decode_stream(args):
     return dict(workload="decode-time reconstruction, %d slices x 524288 tokens x 1024 ch" % S,
                 slices=S, ms_per_pass=ms, bytes_per_pass=nbytes, tokens_per_s=S * T / (ms * 1e-3),
                 roofline=dict(bound="hbm", achieved=gbs, peak=PEAK_HBM_GBS, unit="GB/s",
-                              frac=gbs / PEAK_HBM_GBS, traffic=None,
+                              frac=gbs / PEAK_HBM_GBS, traffic=TRAFFIC_DECODE_SLICE,
                               kernel="rvq_decode", bytes_per_launch=nbytes / S,
                               avg_launch_ms=ms / S))
 
@@ -248,7 +253,7 @@ def run_profile(args):
             q = b.Quantizer(d=d, dhat=32, depth=depth, K=K, out_dtype=b.F16, std_dtype=b.F16, grouping=grp)
             q.set_codebooks(Cs[s_])
             codes = synth.uniform_codes_device(T, G, depth, K, "cuda", extra=100 + s_)
-            for _ in range(3):
+            for _ in range(10):
                 b.rvq_decode(q.ctx, codes, std, T, depth, out, d)
             torch.cuda.synchronize()
             q.close()
@@ -264,7 +269,7 @@ def run_profile(args):
     codes = torch.empty((N, d // dhat, depth), dtype=torch.int16, device="cuda")
     std = torch.empty((N,), dtype=torch.float16, device="cuda")
     if args.profile == "encode":
-        for _ in range(5):
+        for _ in range(25):
             b.rvq_encode(q.ctx, dX, N, d, 0, depth, codes, std, None)
     else:
         Z = train.scaled_groups(dX, d=d, dhat=dhat, grouping=b.STRIDED, in_dtype=b.BF16)
