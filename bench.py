@@ -191,10 +191,35 @@ def run_decode_stream(args):
     ms = a.elapsed_time(z) / reps
     nbytes = S * T * (G * depth * 2 + 2 + d * 2)
     gbs = nbytes / (ms * 1e-3) / 1e9
+    # the same decode from 11-bit packed records (352 instead of 512 bytes of codes per token), on
+    # one strided and one contiguous slice, next to the int16 decode of that slice repeated in the
+    # same way (a slice that is decoded over and over keeps part of its codes in the Infinity
+    # Cache, so these two compare with each other, not with the 64-slice stream above)
+    packed = {}
+    for s_ in range(min(S, 2)):
+        pk = qs[s_].pack(codes[s_])
+        res = {}
+        for name, fn in (("int16", lambda: b.rvq_decode(qs[s_].ctx, codes[s_], std[s_], T, depth, out[s_], d)),
+                         ("packed", lambda: b.rvq_decode_packed(qs[s_].ctx, pk, std[s_], T, depth, out[s_], d))):
+            fn()
+            torch.cuda.synchronize()
+            a.record()
+            for _ in range(5):
+                fn()
+            z.record()
+            torch.cuda.synchronize()
+            res[name + "_ms_per_slice"] = a.elapsed_time(z) / 5
+        pbytes = T * (pk.shape[1] * pk.shape[2] + 2 + d * 2)
+        res["packed_bytes_per_slice"] = pbytes
+        res["packed_GBs"] = pbytes / (res["packed_ms_per_slice"] * 1e-3) / 1e9
+        res["packed_tokens_per_s"] = T / (res["packed_ms_per_slice"] * 1e-3)
+        packed["strided" if s_ % 2 == 0 else "contiguous"] = res
+        del pk
     for q in qs:
         q.close()
     return dict(workload="decode-time reconstruction, %d slices x 524288 tokens x 1024 ch" % S,
                 slices=S, ms_per_pass=ms, bytes_per_pass=nbytes, tokens_per_s=S * T / (ms * 1e-3),
+                packed_codes=packed,
                 roofline=dict(bound="hbm", achieved=gbs, peak=PEAK_HBM_GBS, unit="GB/s",
                               frac=gbs / PEAK_HBM_GBS, traffic=TRAFFIC_DECODE_SLICE,
                               kernel="rvq_decode", bytes_per_launch=nbytes / S,

@@ -121,6 +121,28 @@ int rvq_decode(rvq_ctx *ctx, const int16_t *dCodes, const void *dStd, int64_t N,
                int32_t depth_used, void *dOut, int64_t ldo, void *stream);
 
 /*
+ * Packed code storage (Section 3.2: the compression rate of 5.5x counts log2(K) bits per code and a
+ * half-precision std; int16 storage gives 3.98x).  The depth codes of one (token, group) become
+ * one record of rvq_packed_record_bytes() = ceil(depth * b / 8) bytes, b = the smallest number of
+ * bits with 2^b >= K (at least 1); code i occupies bits [b i, b i + b) of the record read as a
+ * little-endian integer; unused high bits of the last byte are 0.  Records follow each other
+ * without padding: dPacked is uint8 [N][G][record bytes] (352 bytes per 1024-channel row at
+ * K = 2048, depth 8).
+ *   rvq_pack_codes     dCodes int16 [N][G][depth] (device) -> dPacked (device); codes are clamped
+ *                      to [0, K)
+ *   rvq_unpack_codes   the inverse
+ *   rvq_decode_packed  rvq_decode reading packed records instead of int16 codes; same output,
+ *                      bit for bit, as rvq_decode on the unpacked codes
+ * Errors as for rvq_decode; rvq_packed_record_bytes returns RVQ_EINVAL for a null context.
+ */
+int64_t rvq_packed_record_bytes(const rvq_ctx *ctx);
+int rvq_pack_codes(rvq_ctx *ctx, const int16_t *dCodes, int64_t N, uint8_t *dPacked, void *stream);
+int rvq_unpack_codes(rvq_ctx *ctx, const uint8_t *dPacked, int64_t N, int16_t *dCodes, void *stream);
+int rvq_decode_packed(rvq_ctx *ctx, const uint8_t *dPacked, const void *dStd, int64_t N,
+                      int32_t depth_used, void *dOut, int64_t ldo, void *stream);
+
+
+/*
  * One exponential-moving-average update of codebook `stage` (Section 2.1; decay 0.99 in
  * Section 3).  With n_k the number of inputs assigned to code k and S_k their sum:
  *     N_k <- decay N_k + (1 - decay) n_k        M_k <- decay M_k + (1 - decay) S_k

@@ -234,5 +234,41 @@ def kmeans_init_codebooks(Z, depth: int, K: int, iters: int, picks):
     return C, mse
 
 
+def code_bits(K: int) -> int:
+    """Bits of one stored code: the smallest b >= 1 with 2**b >= K (Section 3.2 counts log2 K)."""
+    b = 1
+    while (1 << b) < K:
+        b += 1
+    return b
+
+
+def pack_codes(codes, K: int):
+    """Packed code storage: the depth codes of one (token, group) written one after the other,
+    b = code_bits(K) bits each, least significant bit first, into ceil(depth * b / 8) bytes
+    (unused high bits of the last byte are 0).  codes int [N][G][depth] -> uint8 [N][G][bytes].
+    Written as a bit matrix so that it can be checked by eye."""
+    codes = np.asarray(codes).astype(np.int64)
+    N, G, depth = codes.shape
+    b = code_bits(K)
+    rec = (depth * b + 7) // 8
+    bit = np.zeros((N, G, rec * 8), dtype=np.uint8)
+    for i in range(depth):
+        for t in range(b):
+            bit[:, :, i * b + t] = (codes[:, :, i] >> t) & 1
+    return np.packbits(bit, axis=2, bitorder="little")
+
+
+def unpack_codes(packed, K: int, depth: int):
+    """Inverse of pack_codes: uint8 [N][G][bytes] -> int32 [N][G][depth]."""
+    packed = np.asarray(packed, dtype=np.uint8)
+    b = code_bits(K)
+    bit = np.unpackbits(packed, axis=2, bitorder="little").astype(np.int64)
+    codes = np.zeros(packed.shape[:2] + (depth,), dtype=np.int64)
+    for i in range(depth):
+        for t in range(b):
+            codes[:, :, i] |= bit[:, :, i * b + t] << t
+    return codes.astype(np.int32)
+
+
 if __name__ == "__main__":
     print(build(force="--force" in sys.argv))

@@ -20,7 +20,8 @@ DTYPES = {"fp32": F32, "bf16": BF16, "fp16": F16}
 
 EXPORTS = ("rvq_create", "rvq_destroy", "rvq_set_codebooks", "rvq_get_codebooks", "rvq_encode",
            "rvq_decode", "rvq_ema_update", "rvq_strerror", "rvq_last_hip_error", "rvq_version",
-           "rvq_get_counters")
+           "rvq_get_counters", "rvq_packed_record_bytes", "rvq_pack_codes", "rvq_unpack_codes",
+           "rvq_decode_packed")
 
 
 class rvq_config(ctypes.Structure):
@@ -44,13 +45,18 @@ def _load():
     lib.rvq_decode.argtypes = [vp, vp, vp, i64, i32, vp, i64, vp]
     lib.rvq_ema_update.argtypes = [vp, i32, vp, vp, i64, i64, f32, f32, vp, vp, vp]
     lib.rvq_get_counters.argtypes = [vp, ctypes.POINTER(ctypes.c_int64)]
+    lib.rvq_packed_record_bytes.argtypes = [vp]
+    lib.rvq_packed_record_bytes.restype = ctypes.c_int64
+    lib.rvq_pack_codes.argtypes = [vp, vp, i64, vp, vp]
+    lib.rvq_unpack_codes.argtypes = [vp, vp, i64, vp, vp]
+    lib.rvq_decode_packed.argtypes = [vp, vp, vp, i64, i32, vp, i64, vp]
     lib.rvq_strerror.argtypes = [ctypes.c_int]
     lib.rvq_strerror.restype = ctypes.c_char_p
     lib.rvq_last_hip_error.argtypes = [vp]
     lib.rvq_version.restype = ctypes.c_int
     for name in EXPORTS:
         getattr(lib, name)
-        if name not in ("rvq_strerror", "rvq_version"):
+        if name not in ("rvq_strerror", "rvq_version", "rvq_packed_record_bytes"):
             getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -141,6 +147,23 @@ def rvq_ema_update(ctx, stage, dR, dCodes, code_stride, M, decay, eps, dClusterS
                                    _ptr(dClusterSize), _ptr(dEmbedSum), _stream(stream)), ctx)
 
 
+def rvq_packed_record_bytes(ctx) -> int:
+    return int(lib.rvq_packed_record_bytes(ctx))
+
+
+def rvq_pack_codes(ctx, dCodes, N, dPacked, stream=None):
+    return _chk(lib.rvq_pack_codes(ctx, _ptr(dCodes), N, _ptr(dPacked), _stream(stream)), ctx)
+
+
+def rvq_unpack_codes(ctx, dPacked, N, dCodes, stream=None):
+    return _chk(lib.rvq_unpack_codes(ctx, _ptr(dPacked), N, _ptr(dCodes), _stream(stream)), ctx)
+
+
+def rvq_decode_packed(ctx, dPacked, dStd, N, depth_used, dOut, ldo, stream=None):
+    return _chk(lib.rvq_decode_packed(ctx, _ptr(dPacked), _ptr(dStd), N, depth_used, _ptr(dOut),
+                                      ldo, _stream(stream)), ctx)
+
+
 def rvq_get_counters(ctx):
     out = (ctypes.c_int64 * 16)()  # debug builds report more
     _chk(lib.rvq_get_counters(ctx, out), ctx)
@@ -209,6 +232,31 @@ class Quantizer:
             out = torch.empty((N, self.cfg["d"]), dtype=dt, device=codes.device)
         rvq_decode(self.ctx, codes, std, N, depth_used or self.cfg["depth"], out,
                    out.stride(0) if N else self.cfg["d"])
+        return out
+
+    def pack(self, codes):
+        import torch
+        N = codes.shape[0]
+        rec = rvq_packed_record_bytes(self.ctx)
+        packed = torch.empty((N, self.G, rec), dtype=torch.uint8, device=codes.device)
+        rvq_pack_codes(self.ctx, codes, N, packed)
+        return packed
+
+    def unpack(self, packed):
+        import torch
+        N = packed.shape[0]
+        codes = torch.empty((N, self.G, self.cfg["depth"]), dtype=torch.int16, device=packed.device)
+        rvq_unpack_codes(self.ctx, packed, N, codes)
+        return codes
+
+    def decode_packed(self, packed, std, depth_used=None, out=None):
+        import torch
+        N = packed.shape[0]
+        if out is None:
+            dt = torch.float16 if self.cfg["out_dtype"] == F16 else torch.float32
+            out = torch.empty((N, self.cfg["d"]), dtype=dt, device=packed.device)
+        rvq_decode_packed(self.ctx, packed, std, N, depth_used or self.cfg["depth"], out,
+                          out.stride(0) if N else self.cfg["d"])
         return out
 
     def ema_update(self, stage, R, codes, cluster_size, embed_sum, decay=0.99, eps=1e-5,

@@ -216,7 +216,43 @@ int rvq_decode(rvq_ctx *ctx, const int16_t *dCodes, const void *dStd, int64_t N,
   if (dStd && !aligned16(dStd)) return RVQ_EINVAL;
   if (N > (INT64_MAX / 4) / ldo) return RVQ_EINVAL;
   if (!ctx->have_codebooks) return RVQ_ENOCODEBOOK;
-  RVQ_HIP(ctx, rvq_launch_decode(ctx, dCodes, dStd, N, depth_used, dOut, ldo, (hipStream_t)stream));
+  RVQ_HIP(ctx, rvq_launch_decode(ctx, dCodes, 0, dStd, N, depth_used, dOut, ldo, (hipStream_t)stream));
+  return RVQ_OK;
+}
+
+int64_t rvq_packed_record_bytes(const rvq_ctx *ctx) {
+  if (!ctx) return RVQ_EINVAL;
+  return rvq_record_bytes(ctx->cfg.depth, ctx->cfg.K);
+}
+
+int rvq_pack_codes(rvq_ctx *ctx, const int16_t *dCodes, int64_t N, uint8_t *dPacked, void *stream) {
+  if (!ctx || N < 0) return RVQ_EINVAL;
+  if (N == 0) return RVQ_OK;
+  if (!dCodes || !dPacked || !aligned16(dCodes) || !aligned16(dPacked)) return RVQ_EINVAL;
+  RVQ_HIP(ctx, rvq_launch_pack(ctx, dCodes, N, dPacked, (hipStream_t)stream));
+  return RVQ_OK;
+}
+
+int rvq_unpack_codes(rvq_ctx *ctx, const uint8_t *dPacked, int64_t N, int16_t *dCodes, void *stream) {
+  if (!ctx || N < 0) return RVQ_EINVAL;
+  if (N == 0) return RVQ_OK;
+  if (!dCodes || !dPacked || !aligned16(dCodes) || !aligned16(dPacked)) return RVQ_EINVAL;
+  RVQ_HIP(ctx, rvq_launch_unpack(ctx, dPacked, N, dCodes, (hipStream_t)stream));
+  return RVQ_OK;
+}
+
+int rvq_decode_packed(rvq_ctx *ctx, const uint8_t *dPacked, const void *dStd, int64_t N,
+                      int32_t depth_used, void *dOut, int64_t ldo, void *stream) {
+  if (!ctx || N < 0) return RVQ_EINVAL;
+  const rvq_config &c = ctx->cfg;
+  if (depth_used < 1 || depth_used > c.depth) return RVQ_EINVAL;
+  if (ldo < c.d) return RVQ_EINVAL;
+  if (N == 0) return ctx->have_codebooks ? RVQ_OK : RVQ_ENOCODEBOOK;
+  if (!dPacked || !dOut || !aligned16(dPacked) || !aligned16(dOut)) return RVQ_EINVAL;
+  if (dStd && !aligned16(dStd)) return RVQ_EINVAL;
+  if (N > (INT64_MAX / 4) / ldo) return RVQ_EINVAL;
+  if (!ctx->have_codebooks) return RVQ_ENOCODEBOOK;
+  RVQ_HIP(ctx, rvq_launch_decode(ctx, dPacked, 1, dStd, N, depth_used, dOut, ldo, (hipStream_t)stream));
   return RVQ_OK;
 }
 

@@ -25,10 +25,50 @@ __device__ __forceinline__ float load_std(const void *std_in, int std_dtype, int
                               : rvq_f16_bits_to_f32(((const uint16_t *)std_in)[n]);
 }
 
+
+// ---- where the codes of one (token, group) come from -------------------------------------------
+// PK == 0: int16 [depth]; with depth 8 that is one 16-byte word.
+// PK == 11 / 12 (depth 8 only): a packed record of PK bytes holding eight PK-bit codes, code i in
+// bits [PK i, PK i + PK), little endian (rvq_pack_codes).  A record is fetched as its first and
+// its last eight bytes (two unaligned 8-byte loads that never reach beyond the record).
+template <int PK, bool NT>
+__device__ __forceinline__ i32x4 load_codes8(const void *codes, int64_t e) {
+  if constexpr (PK == 0) {
+    const i32x4 *p = reinterpret_cast<const i32x4 *>(codes) + e;
+    return NT ? __builtin_nontemporal_load(p) : *p;
+  } else {
+    const unsigned char *p = reinterpret_cast<const unsigned char *>(codes) + e * PK;
+    typedef unsigned u32x2u __attribute__((ext_vector_type(2), aligned(1)));
+    const u32x2u lo = *reinterpret_cast<const u32x2u *>(p);
+    const u32x2u hi = *reinterpret_cast<const u32x2u *>(p + PK - 8);
+    const i32x4 w = {(int)lo.x, (int)lo.y, (int)hi.x, (int)hi.y};
+    return w;
+  }
+}
+// code i (0..7) of what load_codes8 returned; int16 codes come back sign-extended
+template <int PK>
+__device__ __forceinline__ int code_of(const i32x4 w, int i) {
+  if constexpr (PK == 0) {
+    const int v = i < 2 ? w.x : (i < 4 ? w.y : (i < 6 ? w.z : w.w));
+    return (i & 1) ? (v >> 16) : (int)(int16_t)(v & 0xffff);
+  } else {
+    const unsigned long long lo = (unsigned)w.x | ((unsigned long long)(unsigned)w.y << 32);
+    const unsigned long long hi = (unsigned)w.z | ((unsigned long long)(unsigned)w.w << 32);
+    const unsigned long long up = hi >> (8 * (16 - PK));  // record bytes 8 .. PK - 1
+    const int sft = PK * i;
+    unsigned long long v;
+    if (sft + PK <= 64) v = lo >> sft;
+    else if (sft >= 64) v = up >> (sft - 64);
+    else v = (lo >> sft) | (up << (64 - sft));
+    return (int)(v & ((1u << PK) - 1u));
+  }
+}
+
 // ---- generic kernel: one thread per output channel, any dhat ------------------------------
 template <bool OUT_F16>
 __global__ __launch_bounds__(256) void decode_generic_kernel(
-    const int16_t *__restrict__ codes, const void *__restrict__ std_in, int std_dtype, int64_t N,
+    const void *__restrict__ codes, int pk_bits /* 0: int16 codes, else bits per packed code */,
+    int rec_bytes, const void *__restrict__ std_in, int std_dtype, int64_t N,
     int d, int G, int dhat, int grouping, const float *__restrict__ C, int K, int depth,
     int depth_used, void *__restrict__ out, int64_t ldo) {
   const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -43,10 +83,20 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(
     j = c / G;
     g = c - j * G;
   }
-  const int16_t *cg = codes + (n * G + g) * depth;
+  const int16_t *cg = reinterpret_cast<const int16_t *>(codes) + (n * G + g) * depth;
+  const unsigned char *rec = reinterpret_cast<const unsigned char *>(codes) + (n * G + g) * rec_bytes;
   float acc = 0.f;
   for (int i = 0; i < depth_used; ++i) {
-    const int k = clamp_code(cg[i], K);
+    int k;
+    if (pk_bits == 0) {
+      k = cg[i];
+    } else {  // bits [pk_bits i, pk_bits (i + 1)) of the record, byte by byte
+      const int b0 = pk_bits * i;
+      unsigned v = 0;
+      for (int t = b0 >> 3; t <= (b0 + pk_bits - 1) >> 3; ++t) v |= (unsigned)rec[t] << (8 * (t - (b0 >> 3)));
+      k = (int)((v >> (b0 & 7)) & ((1u << pk_bits) - 1u));
+    }
+    k = clamp_code(k, K);
     acc += C[((int64_t)i * K + k) * dhat + j];
   }
   acc *= load_std(std_in, std_dtype, n);
@@ -57,9 +107,9 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(
 // ---- row-gather kernel, dhat == 32 -------------------------------------------------------
 constexpr int DEC_WAVES = 4;
 
-template <bool OUT_F16, bool STRIDED, int DEPTH8>
+template <bool OUT_F16, bool STRIDED, int DEPTH8, int PK>
 __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
-    const int16_t *__restrict__ codes, const void *__restrict__ std_in, int std_dtype, int64_t N,
+    const void *__restrict__ codes_v, const void *__restrict__ std_in, int std_dtype, int64_t N,
     int G, const float *__restrict__ C, int K, int depth, int depth_used, void *__restrict__ out,
     int64_t ldo, int lds_row /* padded LDS row length in elements (strided only) */) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -79,19 +129,15 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
       const int g = g0 + p;
       float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
       if (g < G) {
-        const int16_t *cg = codes + (n * G + g) * depth;
+        const int16_t *cg = reinterpret_cast<const int16_t *>(codes_v) + (n * G + g) * depth;
         if (DEPTH8) {
           // codes and outputs are streamed once: non-temporal accesses keep them from evicting
           // the codebook rows, which every wavefront gathers again and again, from L2
-          const i32x4 w = __builtin_nontemporal_load(reinterpret_cast<const i32x4 *>(cg));
-          const int kk[8] = {(int16_t)(w.x & 0xffff), (int16_t)(w.x >> 16),
-                             (int16_t)(w.y & 0xffff), (int16_t)(w.y >> 16),
-                             (int16_t)(w.z & 0xffff), (int16_t)(w.z >> 16),
-                             (int16_t)(w.w & 0xffff), (int16_t)(w.w >> 16)};
+          const i32x4 w = load_codes8<PK, false>(codes_v, n * G + g);
 #pragma unroll
           for (int i = 0; i < 8; ++i) {
             if (i < depth_used) {
-              const int k = clamp_code(kk[i], K);
+              const int k = clamp_code(code_of<PK>(w, i), K);
               const float4 c4 =
                   *reinterpret_cast<const float4 *>(C + ((int64_t)i * K + k) * 32 + q * 4);
               acc.x += c4.x; acc.y += c4.y; acc.z += c4.z; acc.w += c4.w;
@@ -171,9 +217,9 @@ constexpr int SPL_UNROLL = 4;  // (token, group) pairs per thread and trip
 // with a mask and the stage offsets become instruction immediates), 0 for any other size.
 // GS: log2 of the group count when that is a power of two, -1 otherwise.
 // DU: the number of stages summed when known at compile time (straight-line gathers), else 0.
-template <bool OUT_F16, int KC, int GS, int DU>
+template <bool OUT_F16, int KC, int GS, int DU, int PK>
 __global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
-    const int16_t *__restrict__ codes, const void *__restrict__ std_in, int std_dtype, int64_t N,
+    const void *__restrict__ codes, const void *__restrict__ std_in, int std_dtype, int64_t N,
     int G, const float *__restrict__ Csplit, int Krt, int depth, int depth_used_rt,
     void *__restrict__ out, int64_t ldo) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -215,14 +261,13 @@ __global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
   // in turn.  Everything inside a trip is addressed with 32-bit offsets from per-trip bases.
   i32x4 cur[SPL_UNROLL], nxt[SPL_UNROLL];
   auto load_trip = [&](int64_t c, i32x4 *dst) {
-    const i32x4 *src = reinterpret_cast<const i32x4 *>(codes) + c * TRIP;  // depth == 8: 16 bytes
     const int64_t left = V - c * TRIP;
 #pragma unroll
     for (int u = 0; u < SPL_UNROLL; ++u) {
       const int q = u * SPL_THREADS + tid;
       const i32x4 zero = {0, 0, 0, 0};
       // plain loads: the other 15 channel-pair workgroups of this XCD find the line in its L2
-      dst[u] = (c < trips && q < left) ? src[q] : zero;
+      dst[u] = (c < trips && q < left) ? load_codes8<PK, false>(codes, c * TRIP + q) : zero;
     }
   };
   const int64_t step = 8 * (int64_t)parts;
@@ -248,16 +293,13 @@ __global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
         g = (int)(e0 + q - n * G);
         nl = (int)n;  // n0 == 0 here; rows beyond 2^31 are refused by the launcher
       }
-      const unsigned wd[4] = {(unsigned)cur[u].x, (unsigned)cur[u].y, (unsigned)cur[u].z,
-                              (unsigned)cur[u].w};
       float2 acc = make_float2(0.f, 0.f);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         if (i < depth_used) {
-          const unsigned half = (i & 1) ? (wd[i >> 1] >> 16) : (wd[i >> 1] & 0xffffu);
-          int k;
-          if (KC) k = (int)(half & (unsigned)(KC - 1));
-          else k = clamp_code((int)(int16_t)half, K);
+          int k = code_of<PK>(cur[u], i);
+          if (KC) k &= KC - 1;
+          else k = clamp_code(k, K);
           const f32x2 t = tab[i * K + k];
           if (DU && i == 0) {
             acc = make_float2(t.x, t.y);  // 0 + t, without the addition
@@ -295,33 +337,41 @@ __global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
 
 }  // namespace
 
-hipError_t rvq_launch_decode(const rvq_ctx *ctx, const int16_t *dCodes, const void *dStd,
+hipError_t rvq_launch_decode(const rvq_ctx *ctx, const void *dCodes, int packed, const void *dStd,
                              int64_t N, int depth_used, void *dOut, int64_t ldo, hipStream_t s) {
   const rvq_config &c = ctx->cfg;
   const bool f16 = c.out_dtype == RVQ_F16;
   const int G = ctx->G;
   const size_t osz = f16 ? 2 : 4;
   const bool strided = c.grouping == RVQ_STRIDED && G > 1;
-  // LDS path: strided grouping, depth-8 codes in one 16-byte word, even G, a channel-pair table
-  // that fits LDS, and enough rows to pay for filling 256 tables
+  const int bits = packed ? rvq_code_bits(c.K) : 0;
+  const int rec = packed ? rvq_record_bytes(c.depth, c.K) : 0;
+  // packed records the depth-8 kernels read directly: 11 or 12 bytes of eight 11- / 12-bit codes
+  const int pk = (packed && c.depth == 8 && (bits == 11 || bits == 12)) ? bits : 0;
+  const bool fast_codes = c.depth == 8 && (!packed || pk);
+  // LDS path: strided grouping, depth-8 codes, even G, a channel-pair table that fits LDS, and
+  // enough rows to pay for filling 256 tables
   const size_t tab_bytes = (size_t)c.depth * c.K * 8;
-  if (ctx->Csplit && strided && c.dhat == 32 && c.depth == 8 && (G % 2) == 0 &&
+  if (ctx->Csplit && strided && c.dhat == 32 && fast_codes && pk != 12 && (G % 2) == 0 &&
       tab_bytes <= RVQ_SPLIT_MAX_LDS && (ldo * osz) % 8 == 0 && N * (int64_t)G >= (1 << 19)) {
     int g_shift = -1;
     if ((G & (G - 1)) == 0 && G <= SPL_THREADS * SPL_UNROLL) { g_shift = 0; while ((1 << g_shift) < G) ++g_shift; }
     if (g_shift < 0 && N > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid(256), block(SPL_THREADS);
     hipError_t e;
-#define RVQ_LAUNCH_SPLIT(F16, KC, GS, DU)                                                           \
-  e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_split_kernel<F16, KC, GS, DU>),      \
+#define RVQ_LAUNCH_SPLIT(F16, KC, GS, DU, PK)                                                     \
+  e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_split_kernel<F16, KC, GS, DU, PK>), \
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)tab_bytes);            \
   if (e != hipSuccess) return e;                                                                  \
-  hipLaunchKernelGGL((decode_split_kernel<F16, KC, GS, DU>), grid, block, tab_bytes, s, dCodes, dStd, \
-                     c.std_dtype, N, G, ctx->Csplit, c.K, c.depth, depth_used, dOut, ldo)
-    if (c.K == 2048 && g_shift == 5 && depth_used == 8) {
-      if (f16) { RVQ_LAUNCH_SPLIT(true, 2048, 5, 8); } else { RVQ_LAUNCH_SPLIT(false, 2048, 5, 8); }
-    } else {
-      if (f16) { RVQ_LAUNCH_SPLIT(true, 0, -1, 0); } else { RVQ_LAUNCH_SPLIT(false, 0, -1, 0); }
+  hipLaunchKernelGGL((decode_split_kernel<F16, KC, GS, DU, PK>), grid, block, tab_bytes, s, dCodes, \
+                     dStd, c.std_dtype, N, G, ctx->Csplit, c.K, c.depth, depth_used, dOut, ldo)
+    const bool fast = c.K == 2048 && g_shift == 5 && depth_used == 8;
+    if (pk == 0) {
+      if (fast) { if (f16) { RVQ_LAUNCH_SPLIT(true, 2048, 5, 8, 0); } else { RVQ_LAUNCH_SPLIT(false, 2048, 5, 8, 0); } }
+      else { if (f16) { RVQ_LAUNCH_SPLIT(true, 0, -1, 0, 0); } else { RVQ_LAUNCH_SPLIT(false, 0, -1, 0, 0); } }
+    } else {  // 11-bit records
+      if (fast) { if (f16) { RVQ_LAUNCH_SPLIT(true, 2048, 5, 8, 11); } else { RVQ_LAUNCH_SPLIT(false, 2048, 5, 8, 11); } }
+      else { if (f16) { RVQ_LAUNCH_SPLIT(true, 0, -1, 0, 11); } else { RVQ_LAUNCH_SPLIT(false, 0, -1, 0, 11); } }
     }
 #undef RVQ_LAUNCH_SPLIT
     return hipGetLastError();
@@ -330,28 +380,30 @@ hipError_t rvq_launch_decode(const rvq_ctx *ctx, const int16_t *dCodes, const vo
   int lds_row = 0;
   size_t lds_bytes = 0;
   if (strided) {
-    const int per16 = (int)(16 / osz);  // elements per 16 bytes
     lds_row = G + (f16 ? 2 : 1);
-    (void)per16;
     lds_bytes = (size_t)DEC_WAVES * 32 * lds_row * osz;
   }
-  const bool rows_ok = c.dhat == 32 && (ldo * osz) % 16 == 0 && (!strided || (G % 2 == 0 && lds_bytes <= 64 * 1024));
+  const bool rows_ok = c.dhat == 32 && (ldo * osz) % 16 == 0 && (!packed || pk) &&
+                       (!strided || (G % 2 == 0 && lds_bytes <= 64 * 1024));
   if (rows_ok) {
     int64_t blocks = (N + DEC_WAVES - 1) / DEC_WAVES;
     const int64_t cap = 256 * 16;  // enough waves to fill the chip; the kernel strides over rows
     if (blocks > cap) blocks = cap;
     const dim3 grid((unsigned)blocks), block(64 * DEC_WAVES);
     const bool d8 = c.depth == 8;
-#define RVQ_LAUNCH_ROWS(F16, STR, D8)                                                            \
-  hipLaunchKernelGGL((decode_rows32_kernel<F16, STR, D8>), grid, block, lds_bytes, s, dCodes,   \
+#define RVQ_LAUNCH_ROWS(F16, STR, D8, PK)                                                        \
+  hipLaunchKernelGGL((decode_rows32_kernel<F16, STR, D8, PK>), grid, block, lds_bytes, s, dCodes, \
                      dStd, c.std_dtype, N, G, ctx->C, c.K, c.depth, depth_used, dOut, ldo, lds_row)
-    if (f16) {
-      if (strided) { if (d8) RVQ_LAUNCH_ROWS(true, true, 1); else RVQ_LAUNCH_ROWS(true, true, 0); }
-      else { if (d8) RVQ_LAUNCH_ROWS(true, false, 1); else RVQ_LAUNCH_ROWS(true, false, 0); }
-    } else {
-      if (strided) { if (d8) RVQ_LAUNCH_ROWS(false, true, 1); else RVQ_LAUNCH_ROWS(false, true, 0); }
-      else { if (d8) RVQ_LAUNCH_ROWS(false, false, 1); else RVQ_LAUNCH_ROWS(false, false, 0); }
-    }
+#define RVQ_LAUNCH_ROWS_FS(F16, STR)                                                             \
+  do {                                                                                           \
+    if (pk == 11) RVQ_LAUNCH_ROWS(F16, STR, 1, 11);                                              \
+    else if (pk == 12) RVQ_LAUNCH_ROWS(F16, STR, 1, 12);                                         \
+    else if (d8) RVQ_LAUNCH_ROWS(F16, STR, 1, 0);                                                \
+    else RVQ_LAUNCH_ROWS(F16, STR, 0, 0);                                                        \
+  } while (0)
+    if (f16) { if (strided) RVQ_LAUNCH_ROWS_FS(true, true); else RVQ_LAUNCH_ROWS_FS(true, false); }
+    else { if (strided) RVQ_LAUNCH_ROWS_FS(false, true); else RVQ_LAUNCH_ROWS_FS(false, false); }
+#undef RVQ_LAUNCH_ROWS_FS
 #undef RVQ_LAUNCH_ROWS
     return hipGetLastError();
   }
@@ -360,11 +412,11 @@ hipError_t rvq_launch_decode(const rvq_ctx *ctx, const int16_t *dCodes, const vo
   if (grid64 > 0x7fffffffLL) return hipErrorInvalidValue;
   if (f16)
     hipLaunchKernelGGL(decode_generic_kernel<true>, dim3((unsigned)grid64), dim3(256), 0, s, dCodes,
-                       dStd, c.std_dtype, N, c.d, G, c.dhat, c.grouping, ctx->C, c.K, c.depth,
-                       depth_used, dOut, ldo);
+                       bits, rec, dStd, c.std_dtype, N, c.d, G, c.dhat, c.grouping, ctx->C, c.K,
+                       c.depth, depth_used, dOut, ldo);
   else
     hipLaunchKernelGGL(decode_generic_kernel<false>, dim3((unsigned)grid64), dim3(256), 0, s,
-                       dCodes, dStd, c.std_dtype, N, c.d, G, c.dhat, c.grouping, ctx->C, c.K,
-                       c.depth, depth_used, dOut, ldo);
+                       dCodes, bits, rec, dStd, c.std_dtype, N, c.d, G, c.dhat, c.grouping, ctx->C,
+                       c.K, c.depth, depth_used, dOut, ldo);
   return hipGetLastError();
 }

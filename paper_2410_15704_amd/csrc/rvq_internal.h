@@ -48,6 +48,16 @@ struct rvq_ctx {
   size_t ws_ema_bytes;
 };
 
+// bits per packed code: the smallest b >= 1 with 2^b >= K; bytes of the record of one (token, group)
+inline __host__ __device__ int rvq_code_bits(int K) {
+  int b = 1;
+  while ((1 << b) < K) ++b;
+  return b;
+}
+inline __host__ __device__ int rvq_record_bytes(int depth, int K) {
+  return (depth * rvq_code_bits(K) + 7) / 8;
+}
+
 #define RVQ_HIP(ctx, call)                       \
   do {                                           \
     hipError_t e_ = (call);                      \
@@ -92,8 +102,13 @@ hipError_t rvq_launch_encode_exact(const rvq_ctx *ctx, const void *dX, int64_t N
 hipError_t rvq_launch_encode_screen(const rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx,
                                     int stage_begin, int stage_end, int16_t *dCodes,
                                     float *dResidual, hipStream_t s);
-hipError_t rvq_launch_decode(const rvq_ctx *ctx, const int16_t *dCodes, const void *dStd,
+// dCodes: int16 [N][G][depth] (packed == 0) or packed records [N][G][rvq_record_bytes] (packed == 1)
+hipError_t rvq_launch_decode(const rvq_ctx *ctx, const void *dCodes, int packed, const void *dStd,
                              int64_t N, int depth_used, void *dOut, int64_t ldo, hipStream_t s);
+hipError_t rvq_launch_pack(const rvq_ctx *ctx, const int16_t *dCodes, int64_t N, uint8_t *dPacked,
+                           hipStream_t s);
+hipError_t rvq_launch_unpack(const rvq_ctx *ctx, const uint8_t *dPacked, int64_t N, int16_t *dCodes,
+                             hipStream_t s);
 hipError_t rvq_launch_ema(rvq_ctx *ctx, int stage, const float *dR, const int16_t *dCodes,
                           int64_t code_stride, int64_t M, float decay, float eps,
                           float *dClusterSize, float *dEmbedSum, hipStream_t s);

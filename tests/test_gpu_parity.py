@@ -497,6 +497,76 @@ def test_ema_mixture_workload_one_pass(gpu_device):
     q.close()
 
 
+@pytest.mark.parametrize("case", [
+    # N, d, depth, K, grouping
+    (600, 1024, 8, 2048, oracle.STRIDED),     # 11-bit records, row-gather kernel
+    (300, 256, 8, 4096, oracle.CONTIGUOUS),   # 12-bit records
+    (257, 96, 5, 100, oracle.STRIDED),        # 7 bits, records of 5 bytes: generic kernel
+    (64, 64, 16, 3, oracle.CONTIGUOUS),       # 2 bits, depth 16
+])
+def test_packed_codes_and_decode_packed(gpu_device, case):
+    """rvq_pack_codes equals the oracle's packing bit for bit, rvq_unpack_codes inverts it, and
+    rvq_decode_packed gives exactly what rvq_decode gives on the unpacked codes."""
+    torch, b = _torch(), _b()
+    N, d, depth, K, grouping = case
+    G = d // 32
+    rng = np.random.Generator(np.random.PCG64(N + K))
+    codes = rng.integers(0, K, size=(N, G, depth)).astype(np.int16)
+    std = np.exp(0.3 * rng.standard_normal(N)).astype(np.float16)
+    C = (rng.standard_normal((depth, K, 32)) * (0.6 ** np.arange(depth))[:, None, None]).astype(np.float32)
+    for odt in (b.F16, b.F32):
+        q = b.Quantizer(d=d, dhat=32, depth=depth, K=K, grouping=grouping, out_dtype=odt,
+                        std_dtype=b.F16)
+        q.set_codebooks(torch.from_numpy(C).cuda())
+        dc, ds = torch.from_numpy(codes).cuda(), torch.from_numpy(std).cuda()
+        packed = q.pack(dc)
+        want = oracle.pack_codes(codes, K)
+        assert b.rvq_packed_record_bytes(q.ctx) == want.shape[2]
+        assert np.array_equal(packed.cpu().numpy(), want)
+        assert torch.equal(q.unpack(packed), dc)
+        a = q.decode(dc, ds)
+        p = q.decode_packed(packed, ds)
+        assert torch.equal(a, p)
+        a = q.decode(dc, ds, depth_used=max(1, depth - 2))
+        p = q.decode_packed(packed, ds, depth_used=max(1, depth - 2))
+        assert torch.equal(a, p)
+        q.close()
+
+
+def test_decode_packed_slice_matches_decode(gpu_device):
+    """A full workload-3 slice (524288 tokens, strided: the LDS kernel; contiguous: the row-gather
+    kernel) decoded from 11-bit records equals the decode from int16 codes bit for bit; the
+    oracle checks 512 seeded rows."""
+    torch, b = _torch(), _b()
+    T, d, G, depth, K = 16 * 32768, 1024, 32, 8, 2048
+    C = synth.decode_codebooks(1)[0]
+    std = torch.from_numpy(synth.decode_std_fp16(T)).cuda()
+    codes = synth.uniform_codes_device(T, G, depth, K, "cuda", extra=300)
+    rows = np.sort(np.random.Generator(np.random.PCG64(3)).choice(T, 512, replace=False))
+    for grouping in (oracle.STRIDED, oracle.CONTIGUOUS):
+        q = b.Quantizer(d=d, dhat=32, depth=depth, K=K, grouping=grouping, out_dtype=b.F16,
+                        std_dtype=b.F16)
+        q.set_codebooks(torch.from_numpy(C).cuda())
+        packed = q.pack(codes)
+        assert packed.shape == (T, G, 11)
+        a = q.decode(codes, std)
+        p = q.decode_packed(packed, std)
+        assert torch.equal(a, p)
+        del a, p
+        q.close()
+    check_decode(None, None, "fp16", C, d, 32, oracle.STRIDED, sample_rows=rows,
+                 dev_codes=q_unpack_roundtrip(b, torch, codes, packed, K, depth, G, d), dev_std=std)
+
+
+def q_unpack_roundtrip(b, torch, codes, packed, K, depth, G, d):
+    """codes -> (already packed) -> unpacked again on the device; must equal the original."""
+    q = b.Quantizer(d=d, dhat=32, depth=depth, K=K)
+    out = q.unpack(packed)
+    q.close()
+    assert torch.equal(out, codes)
+    return out
+
+
 def test_kmeans_init_matches_oracle(gpu_device):
     """Section 3's k-means initialisation driven through rvq_encode + rvq_ema_update (decay 0)
     against the oracle's, from the same picked rows: codebooks within 1e-5 per stage."""

@@ -407,3 +407,32 @@ def test_kmeans_init_stages_chain_through_residuals():
     assert mse[1, 0] <= mse[0, -1] + 1e-15       # a picked residual row can only help
     C0, _ = oracle.kmeans_init_codebooks(Z, 2, 16, 0, picks)
     np.testing.assert_array_equal(C0[0], Z[picks[0]])
+
+
+# ---- Section 3.2: packed code storage -------------------------------------------------------------
+def test_packed_codes_hand_example_roundtrip_and_size():
+    """The packing against records worked out by hand (tests/golden/packed_codes_example.txt),
+    the inverse on random codes, and the size that gives the paper's 5.5x: one 128-channel head
+    with 4 groups, depth 8, K = 2048 packs into 4 x 11 bytes, plus 2 bytes of std = 368 bits."""
+    path = os.path.join(os.path.dirname(__file__), "golden", "packed_codes_example.txt")
+    n = 0
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        head, codes, hexbytes = [x.strip() for x in line.split("|")]
+        K, depth = (int(x) for x in head.split())
+        codes = np.array([int(x) for x in codes.split()]).reshape(1, 1, depth)
+        want = np.array([int(x, 16) for x in hexbytes.split()], dtype=np.uint8)
+        got = oracle.pack_codes(codes, K)
+        assert got.shape == (1, 1, len(want)) and np.array_equal(got[0, 0], want)
+        assert np.array_equal(oracle.unpack_codes(got, K, depth), codes)
+        n += 1
+    assert n == 2
+    rng = np.random.Generator(np.random.PCG64(9))
+    for K, depth in ((2048, 8), (4096, 8), (100, 5), (2, 16), (1, 3), (32768, 16)):
+        codes = rng.integers(0, K, size=(7, 3, depth))
+        packed = oracle.pack_codes(codes, K)
+        assert packed.shape[2] == (depth * oracle.code_bits(K) + 7) // 8
+        assert np.array_equal(oracle.unpack_codes(packed, K, depth), codes)
+    packed = oracle.pack_codes(np.zeros((1, 4, 8), dtype=int), 2048)
+    assert packed[0].size * 8 + 16 == oracle.compressed_bits(128, 32, 8, 2048) == 368
