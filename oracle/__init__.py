@@ -234,6 +234,54 @@ def kmeans_init_codebooks(Z, depth: int, K: int, iters: int, picks):
     return C, mse
 
 
+def ema_train(R0, depth: int, K: int, iters: int, decay: float, eps: float, picks,
+              schedule: str = "sequential"):
+    """Codebook learning by exponential moving average (Sections 2.1 and 3: decay 0.99) on a fixed
+    set of vectors R0 [M][dhat], with moving-average state N_k = 1, M_k = C_k at the start.
+      "sequential": stage by stage: codebook s starts from rows picks[s] of the vectors entering
+          stage s, then `iters` rounds of (assign, update); a last assignment leaves the residuals
+          that enter stage s + 1.
+      "online" (all stages in every step, as in the paper's training): codebooks start from picked
+          rows stage by stage (sample initialisation); then `iters` steps, each walking the stages:
+          assign with the current codebook, pass on the residual formed with that (pre-update)
+          codebook, update the codebook.
+    Returns C [depth][K][dhat] float64."""
+    R0 = _f64(R0)
+    M, dhat = R0.shape
+    C = np.zeros((depth, K, dhat), dtype=np.float64)
+
+    def assign(R, Cs):
+        out = encode(R, Cs[None], dhat, CONTIGUOUS, scale=False, want_residual=True)
+        return out["codes"].reshape(M), out["residual"].reshape(M, dhat)
+
+    if schedule == "sequential":
+        R = R0
+        for s in range(depth):
+            Cs = R[np.asarray(picks[s])].copy()
+            cs, es = np.ones(K), Cs.copy()
+            for _ in range(iters):
+                codes, _ = assign(R, Cs)
+                cs, es, Cs = ema_update(R, codes, K, decay, eps, cs, es)
+            _, R = assign(R, Cs)
+            C[s] = Cs
+        return C
+    if schedule != "online":
+        raise ValueError(schedule)
+    R = R0
+    for s in range(depth):
+        C[s] = R[np.asarray(picks[s])]
+        _, R = assign(R, C[s])
+    cs = [np.ones(K) for _ in range(depth)]
+    es = [C[s].copy() for s in range(depth)]
+    for _ in range(iters):
+        R = R0
+        for s in range(depth):
+            codes, Rn = assign(R, C[s])
+            cs[s], es[s], C[s] = ema_update(R, codes, K, decay, eps, cs[s], es[s])
+            R = Rn
+    return C
+
+
 def code_bits(K: int) -> int:
     """Bits of one stored code: the smallest b >= 1 with 2**b >= K (Section 3.2 counts log2 K)."""
     b = 1

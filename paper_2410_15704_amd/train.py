@@ -50,11 +50,13 @@ def sample_init_codebooks(Z: torch.Tensor, depth: int, K: int, seed: int,
 
 
 def ema_train_sequential(R0: torch.Tensor, depth: int, K: int, iters: int, decay: float,
-                         eps: float, seed: int, encode_path: int = b.PATH_AUTO, timers=None):
+                         eps: float, seed: int, encode_path: int = b.PATH_AUTO, timers=None,
+                         picks=None):
     """Stage-by-stage residual training: for each stage, sample-initialise its codebook from the
     vectors entering it, run `iters` rounds of (assign, moving-average update) with state
     N_k = 1, M_k = C_k at the start, then assign once more and pass the residuals on.
-    R0 float32 [M][dhat].  Returns the learnt codebooks [depth][K][dhat]."""
+    R0 float32 [M][dhat]; `picks[s]` (K row indices) replaces the seeded draw of stage s.
+    Returns the learnt codebooks [depth][K][dhat]."""
     M, dhat = R0.shape
     gen = torch.Generator(device="cpu")
     gen.manual_seed(seed)
@@ -63,7 +65,10 @@ def ema_train_sequential(R0: torch.Tensor, depth: int, K: int, iters: int, decay
     codes = torch.empty((M, 1, depth), dtype=torch.int16, device=R0.device)
     R = R0.contiguous()
     for s in range(depth):
-        pick = torch.randperm(M, generator=gen)[:K].sort().values.to(R.device)
+        if picks is not None:
+            pick = torch.as_tensor(picks[s], dtype=torch.int64, device=R.device)
+        else:
+            pick = torch.randperm(M, generator=gen)[:K].sort().values.to(R.device)
         C[s] = R.index_select(0, pick)
         q.set_codebooks(C)
         cs = torch.ones(K, dtype=torch.float32, device=R.device)
@@ -112,6 +117,38 @@ def kmeans_init_codebooks(Z: torch.Tensor, depth: int, K: int, iters: int, picks
         _, _, res = q.encode(R, want_residual=True, stages=(s, s + 1), codes=codes)
         R = res.view(V, dhat)
         C = q.get_codebooks()
+    torch.cuda.synchronize()
+    q.close()
+    return C
+
+
+def ema_train_online(R0: torch.Tensor, depth: int, K: int, iters: int, decay: float, eps: float,
+                     picks, encode_path: int = b.PATH_AUTO) -> torch.Tensor:
+    """All stages in every step, as in the paper's training (Section 3): the codebooks start from
+    picked rows stage by stage (sample initialisation); then `iters` steps, each walking the
+    stages: assign with the current codebook (rvq_encode over that stage), pass on the residual
+    formed with that pre-update codebook, update the codebook (rvq_ema_update).  Moving-average
+    state N_k = 1, M_k = C_k at the start.  R0 float32 [M][dhat].  Returns C [depth][K][dhat]."""
+    M, dhat = R0.shape
+    dev = R0.device
+    q = b.Quantizer(d=dhat, dhat=dhat, depth=depth, K=K, scale=0, encode_path=encode_path)
+    C = torch.zeros((depth, K, dhat), dtype=torch.float32, device=dev)
+    codes = torch.empty((M, 1, depth), dtype=torch.int16, device=dev)
+    R = R0.contiguous()
+    for s in range(depth):
+        C[s] = R.index_select(0, torch.as_tensor(picks[s], dtype=torch.int64, device=dev))
+        q.set_codebooks(C)
+        _, _, res = q.encode(R, want_residual=True, stages=(s, s + 1), codes=codes)
+        R = res.view(M, dhat)
+    cs = [torch.ones(K, dtype=torch.float32, device=dev) for _ in range(depth)]
+    es = [C[s].clone() for s in range(depth)]
+    for _ in range(iters):
+        R = R0.contiguous()
+        for s in range(depth):
+            _, _, res = q.encode(R, want_residual=True, stages=(s, s + 1), codes=codes)
+            b.rvq_ema_update(q.ctx, s, R, codes.data_ptr() + 2 * s, depth, M, decay, eps, cs[s], es[s])
+            R = res.view(M, dhat)
+    C = q.get_codebooks()
     torch.cuda.synchronize()
     q.close()
     return C

@@ -355,6 +355,31 @@ def test_encode_long_context_shape_reduced_rows(gpu_device):
     print("workload 5 (2048 rows):", r)
 
 
+def test_long_context_shape_mse_per_depth(gpu_device):
+    """Workload 5's report: reconstruction error after 1..8 stages (rvq_decode with depth_used),
+    on 512 rows of its shape; per depth within 1e-3 of the oracle's and falling with depth."""
+    torch, b = _torch(), _b()
+    Xh, _ = synth.heavy_tailed_keys(rows=slice(0, 512))
+    Xw = synth.widen(Xh, "fp16")
+    C = _codebooks_from_samples(Xw[:256], 32, oracle.STRIDED, 8, 4096, seed=5)
+    q = b.Quantizer(d=4096, dhat=32, depth=8, K=4096, grouping=b.STRIDED, in_dtype=b.F16,
+                    out_dtype=b.F32, std_dtype=b.F32)
+    q.set_codebooks(torch.from_numpy(C).cuda())
+    codes, std, _ = q.encode(torch.from_numpy(Xh).cuda())
+    ref = oracle.encode(Xw, C.astype(np.float64), 32, oracle.STRIDED)
+    mse_g, mse_o = [], []
+    for k in range(1, 9):
+        out = q.decode(codes, std, depth_used=k).cpu().numpy().astype(np.float64)
+        mse_g.append(np.mean((Xw - out) ** 2))
+        mse_o.append(np.mean((Xw - oracle.decode(ref["codes"], ref["std"], C.astype(np.float64), 4096,
+                                                 oracle.STRIDED, depth_used=k)) ** 2))
+    q.close()
+    print("MSE per depth, GPU:   ", np.round(mse_g, 5).tolist())
+    print("MSE per depth, oracle:", np.round(mse_o, 5).tolist())
+    np.testing.assert_allclose(mse_g, mse_o, rtol=1e-3)
+    assert np.all(np.diff(mse_g) < 0)
+
+
 # ------------------------------------------------------------------------------------ decode
 @pytest.mark.parametrize("case", [
     # N, d, dhat, depth, K, grouping, std dtype, depth_used
@@ -565,6 +590,30 @@ def q_unpack_roundtrip(b, torch, codes, packed, K, depth, G, d):
     q.close()
     assert torch.equal(out, codes)
     return out
+
+
+@pytest.mark.parametrize("schedule", ["sequential", "online"])
+def test_ema_training_schedule_matches_oracle(gpu_device, schedule):
+    """Workload 4's procedure at reduced size (30000 mixture vectors, depth 3, K = 96, 5 rounds,
+    decay 0.99, eps 1e-5), stage by stage and with all stages per step: learnt codebooks within
+    1e-5 of the oracle's per stage."""
+    torch = _torch()
+    from paper_2410_15704_amd import train
+    R = synth.gaussian_mixture(M=30000)
+    depth, K, iters = 3, 96, 5
+    rng = np.random.Generator(np.random.PCG64(61))
+    picks = [np.sort(rng.choice(30000, K, replace=False)) for _ in range(depth)]
+    dR = torch.from_numpy(R).cuda()
+    if schedule == "sequential":
+        Cg = train.ema_train_sequential(dR, depth, K, iters, 0.99, 1e-5, seed=0, picks=picks)
+    else:
+        Cg = train.ema_train_online(dR, depth, K, iters, 0.99, 1e-5, picks)
+    Co = oracle.ema_train(R.astype(np.float64), depth, K, iters, np.float32(0.99), np.float32(1e-5),
+                          picks, schedule)
+    for s in range(depth):
+        rel = _frob_rel(Cg[s].cpu().numpy(), Co[s])
+        print(f"{schedule} stage {s}: rel {rel:.2e}")
+        assert rel <= 1e-5
 
 
 def test_kmeans_init_matches_oracle(gpu_device):

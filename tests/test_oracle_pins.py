@@ -436,3 +436,23 @@ def test_packed_codes_hand_example_roundtrip_and_size():
         assert np.array_equal(oracle.unpack_codes(packed, K, depth), codes)
     packed = oracle.pack_codes(np.zeros((1, 4, 8), dtype=int), 2048)
     assert packed[0].size * 8 + 16 == oracle.compressed_bits(128, 32, 8, 2048) == 368
+
+
+def test_ema_training_schedules_reduce_to_known_cases():
+    """decay 1 leaves every codebook at its picked rows in both schedules (the moving average
+    starts self-consistent); with decay 0 and no smoothing the sequential schedule is the k-means
+    initialisation; with one stage the two schedules coincide."""
+    rng = np.random.Generator(np.random.PCG64(51))
+    Z = rng.standard_normal((1500, 4)) + 3.0 * rng.integers(0, 3, (1500, 1))
+    picks = [np.sort(rng.choice(1500, 24, replace=False)) for _ in range(2)]
+    Cs = oracle.ema_train(Z, 2, 24, 3, 1.0, 1e-5, picks, "sequential")
+    Co = oracle.ema_train(Z, 2, 24, 3, 1.0, 1e-5, picks, "online")
+    S = Z[picks[0]]
+    np.testing.assert_allclose(Cs[0], S, rtol=1e-12)
+    np.testing.assert_allclose(Co, Cs, rtol=1e-12)
+    Ck, _ = oracle.kmeans_init_codebooks(Z, 2, 24, 3, picks)
+    np.testing.assert_allclose(oracle.ema_train(Z, 2, 24, 3, 0.0, 0.0, picks, "sequential"), Ck,
+                               rtol=1e-12, atol=1e-12)
+    a = oracle.ema_train(Z, 1, 24, 4, 0.9, 1e-5, picks[:1], "sequential")
+    c = oracle.ema_train(Z, 1, 24, 4, 0.9, 1e-5, picks[:1], "online")
+    np.testing.assert_allclose(a, c, rtol=1e-12)
