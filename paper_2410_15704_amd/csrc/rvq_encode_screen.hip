@@ -117,6 +117,46 @@ __device__ __forceinline__ float dot8(const uint4 w, const half8 b, float acc) {
     x[SCR_TT - 1] = t_;                                           \
   } while (0)
 
+// Exact nearest codeword of one vector among the K codewords of a stage, by the whole wavefront
+// (every lane passes the same vector; two codewords per lane in flight; ties to the smallest
+// index).  Kept out of line: it is needed for 0.02 % of the searches, and inlined its 100
+// registers of rows would be made room for on the common path.
+__device__ __noinline__ int exact_scan(const float *__restrict__ Cs, int K, const float *vec, int lane) {
+  float rr32[32];
+#pragma unroll
+  for (int j = 0; j < 32; ++j) rr32[j] = vec[j];
+  float bd = INFINITY;
+  int bk = 0x7fffffff;
+  for (int k0 = lane; k0 < K; k0 += 128) {
+    f32x4 cw[2][8];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int k = min(k0 + 64 * q, K - 1);
+      const f32x4 *crow = reinterpret_cast<const f32x4 *>(Cs + (int64_t)k * 32);
+#pragma unroll
+      for (int c4 = 0; c4 < 8; ++c4) cw[q][c4] = crow[c4];
+    }
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int k = k0 + 64 * q;
+      float dist = 0.f;
+#pragma unroll
+      for (int j = 0; j < 32; ++j) {
+        const float dlt = rr32[j] - cw[q][j >> 2][j & 3];
+        dist = fmaf(dlt, dlt, dist);
+      }
+      if (k < K && dist < bd) { bd = dist; bk = k; }
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float od = __shfl_xor(bd, o, 64);
+    const int ok = __shfl_xor(bk, o, 64);
+    if (od < bd || (od == bd && ok < bk)) { bd = od; bk = ok; }
+  }
+  return bk == 0x7fffffff ? 0 : bk;
+}
+
 // pieces of the sweep's reduction of one accumulator set: R1 folds the 16 scores of a lane into two
 // partial minima (reads the accumulators), R2 finishes the group's tagged lower bound and merges
 // it into the three smallest of token tile TT
@@ -730,10 +770,15 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
         if (!(bestd[tt] < INFINITY)) slow[tt] = 1;  // no candidate in any chunk
         any_slow = any_slow || slow[tt];
       }
-      if (__any(any_slow)) {
+      if (__any(any_slow)) {  // seldom: 0.02 % of the searches
 #pragma unroll 1
         for (int rot = 0; rot < SCR_TT; ++rot) {
-          unsigned long long pending = __ballot(slow[0] && h == 0);
+          // token tile `rot` is picked with selects, so that the common path never moves the
+          // register arrays around
+          int slow_r = slow[0];
+#pragma unroll
+          for (int t2 = 1; t2 < SCR_TT; ++t2) slow_r = rot == t2 ? slow[t2] : slow_r;
+          unsigned long long pending = __ballot(slow_r && h == 0);
           n_slow += __popcll(pending);
           while (pending) {
             const int src = __ffsll((long long)pending) - 1;
@@ -741,47 +786,16 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
             float rr32[32];
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
-              rr32[j] = __shfl(r[0][j], src, 64);
-              rr32[16 + j] = __shfl(r[0][j], src + 32, 64);
+              float rj = r[0][j];
+#pragma unroll
+              for (int t2 = 1; t2 < SCR_TT; ++t2) rj = rot == t2 ? r[t2][j] : rj;
+              rr32[j] = __shfl(rj, src, 64);
+              rr32[16 + j] = __shfl(rj, src + 32, 64);
             }
-            float bd = INFINITY;
-            int bk = 0x7fffffff;
-            for (int k0 = lane; k0 < a.K; k0 += 128) {  // two codewords per lane in flight
-              f32x4 cw[2][8];
+            const int bk = exact_scan(a.C32 + (int64_t)stage * a.K * 32, a.K, rr32, lane);
+            const bool mine = lane == src || lane == src + 32;
 #pragma unroll
-              for (int q = 0; q < 2; ++q) {
-                const int k = min(k0 + 64 * q, a.K - 1);
-                const f32x4 *crow = reinterpret_cast<const f32x4 *>(a.C32 + ((int64_t)stage * a.K + k) * 32);
-#pragma unroll
-                for (int c4 = 0; c4 < 8; ++c4) cw[q][c4] = crow[c4];
-              }
-#pragma unroll
-              for (int q = 0; q < 2; ++q) {
-                const int k = k0 + 64 * q;
-                float dist = 0.f;
-#pragma unroll
-                for (int j = 0; j < 32; ++j) {
-                  const float dlt = rr32[j] - cw[q][j >> 2][j & 3];
-                  dist = fmaf(dlt, dlt, dist);
-                }
-                if (k < a.K && dist < bd) { bd = dist; bk = k; }
-              }
-            }
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) {
-              const float od = __shfl_xor(bd, o, 64);
-              const int ok = __shfl_xor(bk, o, 64);
-              if (od < bd || (od == bd && ok < bk)) { bd = od; bk = ok; }
-            }
-            if (lane == src || lane == src + 32) bestk[0] = bk == 0x7fffffff ? 0 : bk;
-          }
-          ROT4(slow); ROT4(bestk);
-#pragma unroll
-          for (int j = 0; j < 16; ++j) {
-            const float t0 = r[0][j];
-#pragma unroll
-            for (int t2 = 0; t2 + 1 < SCR_TT; ++t2) r[t2][j] = r[t2 + 1][j];
-            r[SCR_TT - 1][j] = t0;
+            for (int t2 = 0; t2 < SCR_TT; ++t2) bestk[t2] = (mine && rot == t2) ? bk : bestk[t2];
           }
         }
       }
