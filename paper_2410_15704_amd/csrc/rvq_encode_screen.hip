@@ -157,6 +157,34 @@ __device__ __noinline__ int exact_scan(const float *__restrict__ Cs, int K, cons
   return bk == 0x7fffffff ? 0 : bk;
 }
 
+// Exact distances of one vector (the same in every lane) to one codeword per lane, and the
+// nearest of them over the wavefront (ties to the smallest index; 0x7fffffff if no lane has a
+// valid codeword).  Out of line for the same reason as exact_scan: 1.8 % of the tokens of the
+// first stage need it, none later.
+__device__ __noinline__ int exact_best_of_lanes(const float *__restrict__ Cs, const float *vec,
+                                                unsigned gk, bool gvalid) {
+  const f32x4 *crow = reinterpret_cast<const f32x4 *>(Cs + (int64_t)(gvalid ? gk : 0u) * 32);
+  float dist = 0.f;
+#pragma unroll
+  for (int c4 = 0; c4 < 8; ++c4) {
+    const f32x4 cw = crow[c4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float dlt = vec[c4 * 4 + e] - cw[e];
+      dist = fmaf(dlt, dlt, dist);
+    }
+  }
+  float bd = gvalid ? dist : INFINITY;
+  int bk = gvalid ? (int)gk : 0x7fffffff;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float od = __shfl_xor(bd, o, 64);
+    const int ok2 = __shfl_xor(bk, o, 64);
+    if (od < bd || (od == bd && ok2 < bk)) { bd = od; bk = ok2; }
+  }
+  return bk;
+}
+
 // pieces of the sweep's reduction of one accumulator set: R1 folds the 16 scores of a lane into two
 // partial minima (reads the accumulators), R2 finishes the group's tagged lower bound and merges
 // it into the three smallest of token tile TT
@@ -629,26 +657,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
               const int gm = 8 * (rw >> 2) + 4 * ghh + (rw & 3);
               const unsigned gk = ((gpend >> gi) & 1u) ? (unsigned)lds_p[gtl * 32 + gm] : 0xffffu;
               const bool gvalid = gk < (unsigned)a.K;
-              const f32x4 *crow = reinterpret_cast<const f32x4 *>(
-                  a.C32 + ((int64_t)stage * a.K + (gvalid ? gk : 0u)) * 32);
-              float dist = 0.f;
-#pragma unroll
-              for (int c4 = 0; c4 < 8; ++c4) {
-                const f32x4 cw = crow[c4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                  const float dlt = rr32[c4 * 4 + e] - cw[e];
-                  dist = fmaf(dlt, dlt, dist);
-                }
-              }
-              float bd = gvalid ? dist : INFINITY;
-              int bk = gvalid ? (int)gk : 0x7fffffff;
-#pragma unroll
-              for (int o = 32; o > 0; o >>= 1) {
-                const float od = __shfl_xor(bd, o, 64);
-                const int ok2 = __shfl_xor(bk, o, 64);
-                if (od < bd || (od == bd && ok2 < bk)) { bd = od; bk = ok2; }
-              }
+              const int bk = exact_best_of_lanes(a.C32 + (int64_t)stage * a.K * 32, rr32, gk, gvalid);
               if (lane == src) lds_c[(wtok + rot * 32 + src) * SCR_CAND] = (uint16_t)(bk == 0x7fffffff ? 0 : bk);
               // bk == 0x7fffffff cannot happen for a token with candidates; it would leave the
               // token without one and send it to the wavefront search below
