@@ -355,6 +355,21 @@ def test_encode_long_context_shape_reduced_rows(gpu_device):
     print("workload 5 (2048 rows):", r)
 
 
+@pytest.mark.parametrize("depth", [4, 6, 8])
+@pytest.mark.parametrize("K", [1024, 2048])
+def test_encode_per_head_ablation_grid(gpu_device, depth, K):
+    """The paper's own setting (Section 3.2): one 128-channel head per vector (d / dhat = 4 groups),
+    number of codebooks in {4, 6, 8}, codes per codebook in {1024, 2048}; keys with channels
+    4 apart in a group (strided), values with contiguous groups (Section 3.1)."""
+    X = synth.gaussian_rows(3072, 128, seed=700 + depth + K, dtype="bf16", outliers=3)
+    Xw = synth.widen(X, "bf16")
+    for grouping in (oracle.STRIDED, oracle.CONTIGUOUS):
+        C = _codebooks_from_samples(Xw, 32, grouping, depth, K, seed=depth * 10 + grouping)
+        r = check_encode(X, "bf16", 128, 32, depth, K, grouping, C, std_dtype="fp16",
+                         sample_rows=np.arange(0, 3072, 6))
+        print(f"depth {depth} K {K} grouping {grouping}:", r)
+
+
 def test_long_context_shape_mse_per_depth(gpu_device):
     """Workload 5's report: reconstruction error after 1..8 stages (rvq_decode with depth_used),
     on 512 rows of its shape; per depth within 1e-3 of the oracle's and falling with depth."""
