@@ -196,11 +196,19 @@ def run_decode_stream(args):
     # same way (a slice that is decoded over and over keeps part of its codes in the Infinity
     # Cache, so these two compare with each other, not with the 64-slice stream above)
     packed = {}
+    # rotary tables (inputs of rvq_decode_rope): 8 heads of 128 channels, positions 0..32767
+    hd = 128
+    ang = (torch.arange(T, device="cuda") % 32768).double()[:, None] * \
+        (10000.0 ** (-2.0 * torch.arange(hd // 2, device="cuda").double() / hd))[None, :]
+    dcos, dsin = torch.cos(ang).float(), torch.sin(ang).float()
+    del ang
     for s_ in range(min(S, 2)):
         pk = qs[s_].pack(codes[s_])
         res = {}
         for name, fn in (("int16", lambda: b.rvq_decode(qs[s_].ctx, codes[s_], std[s_], T, depth, out[s_], d)),
-                         ("packed", lambda: b.rvq_decode_packed(qs[s_].ctx, pk, std[s_], T, depth, out[s_], d))):
+                         ("packed", lambda: b.rvq_decode_packed(qs[s_].ctx, pk, std[s_], T, depth, out[s_], d)),
+                         ("rope", lambda: b.rvq_decode_rope(qs[s_].ctx, codes[s_], std[s_], T, depth, dcos,
+                                                            dsin, hd, out[s_], d))):
             fn()
             torch.cuda.synchronize()
             a.record()
@@ -215,11 +223,12 @@ def run_decode_stream(args):
         res["packed_tokens_per_s"] = T / (res["packed_ms_per_slice"] * 1e-3)
         packed["strided" if s_ % 2 == 0 else "contiguous"] = res
         del pk
+    del dcos, dsin
     for q in qs:
         q.close()
     return dict(workload="decode-time reconstruction, %d slices x 524288 tokens x 1024 ch" % S,
                 slices=S, ms_per_pass=ms, bytes_per_pass=nbytes, tokens_per_s=S * T / (ms * 1e-3),
-                packed_codes=packed,
+                packed_codes_and_rope=packed,
                 roofline=dict(bound="hbm", achieved=gbs, peak=PEAK_HBM_GBS, unit="GB/s",
                               frac=gbs / PEAK_HBM_GBS, traffic=TRAFFIC_DECODE_SLICE,
                               kernel="rvq_decode", bytes_per_launch=nbytes / S,

@@ -121,6 +121,20 @@ int rvq_decode(rvq_ctx *ctx, const int16_t *dCodes, const void *dStd, int64_t N,
                int32_t depth_used, void *dOut, int64_t ldo, void *stream);
 
 /*
+ * Decode fused with the rotary position embedding (Section 3: quantization is applied before the
+ * rotary embedding, so a decoded key is rotated before attention uses it).  The decoded row, still
+ * in fp32, is rotated pair by pair inside every head of head_dim channels,
+ *   (x[2i], x[2i+1]) -> (x[2i] cos[n][i] - x[2i+1] sin[n][i], x[2i] sin[n][i] + x[2i+1] cos[n][i]),
+ * and rounded once to cfg.out_dtype.
+ *   dCos, dSin  device, fp32 [N][head_dim / 2] (row n belongs to token n: its position's angles)
+ *   head_dim    even, divides d; with strided grouping the group count G must be even
+ * Other arguments and errors as for rvq_decode.
+ */
+int rvq_decode_rope(rvq_ctx *ctx, const int16_t *dCodes, const void *dStd, int64_t N,
+                    int32_t depth_used, const float *dCos, const float *dSin, int32_t head_dim,
+                    void *dOut, int64_t ldo, void *stream);
+
+/*
  * Packed code storage (Section 3.2: the compression rate of 5.5x counts log2(K) bits per code and a
  * half-precision std; int16 storage gives 3.98x).  The depth codes of one (token, group) become
  * one record of rvq_packed_record_bytes() = ceil(depth * b / 8) bytes, b = the smallest number of

@@ -282,6 +282,36 @@ def ema_train(R0, depth: int, K: int, iters: int, decay: float, eps: float, pick
     return C
 
 
+def rope_tables(positions, head_dim: int, base: float = 10000.0):
+    """cos / sin of the rotary position embedding the paper cites (RoFormer): pair i of a head is
+    turned by the angle position * base**(-2 i / head_dim).  Returns (cos, sin) float64
+    [len(positions)][head_dim // 2].  Only used to build inputs; both sides receive the tables."""
+    pos = np.asarray(positions, dtype=np.float64)[:, None]
+    inv = base ** (-2.0 * np.arange(head_dim // 2, dtype=np.float64) / head_dim)[None, :]
+    ang = pos * inv
+    return np.cos(ang), np.sin(ang)
+
+
+def decode_rope(codes, std, C, d: int, grouping: int, cos, sin, head_dim: int,
+                depth_used: int | None = None):
+    """Decode followed by the rotary position embedding (the paper quantizes keys BEFORE the
+    rotary embedding, Section 3, so every decoded key is rotated before use): within every head
+    of head_dim channels, the pair (x[2i], x[2i+1]) becomes
+    (x[2i] cos_i - x[2i+1] sin_i, x[2i] sin_i + x[2i+1] cos_i), cos / sin float [N][head_dim/2]."""
+    x = decode(codes, std, C, d, grouping, depth_used)
+    N = x.shape[0]
+    cos = _f64(cos)
+    sin = _f64(sin)
+    heads = d // head_dim
+    xr = x.reshape(N, heads, head_dim // 2, 2)
+    out = np.empty_like(xr)
+    c = cos[:, None, :]
+    s_ = sin[:, None, :]
+    out[..., 0] = xr[..., 0] * c - xr[..., 1] * s_
+    out[..., 1] = xr[..., 0] * s_ + xr[..., 1] * c
+    return out.reshape(N, d)
+
+
 def code_bits(K: int) -> int:
     """Bits of one stored code: the smallest b >= 1 with 2**b >= K (Section 3.2 counts log2 K)."""
     b = 1

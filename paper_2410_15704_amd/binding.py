@@ -21,7 +21,7 @@ DTYPES = {"fp32": F32, "bf16": BF16, "fp16": F16}
 EXPORTS = ("rvq_create", "rvq_destroy", "rvq_set_codebooks", "rvq_get_codebooks", "rvq_encode",
            "rvq_decode", "rvq_ema_update", "rvq_strerror", "rvq_last_hip_error", "rvq_version",
            "rvq_get_counters", "rvq_packed_record_bytes", "rvq_pack_codes", "rvq_unpack_codes",
-           "rvq_decode_packed")
+           "rvq_decode_packed", "rvq_decode_rope")
 
 
 class rvq_config(ctypes.Structure):
@@ -50,6 +50,7 @@ def _load():
     lib.rvq_pack_codes.argtypes = [vp, vp, i64, vp, vp]
     lib.rvq_unpack_codes.argtypes = [vp, vp, i64, vp, vp]
     lib.rvq_decode_packed.argtypes = [vp, vp, vp, i64, i32, vp, i64, vp]
+    lib.rvq_decode_rope.argtypes = [vp, vp, vp, i64, i32, vp, vp, i32, vp, i64, vp]
     lib.rvq_strerror.argtypes = [ctypes.c_int]
     lib.rvq_strerror.restype = ctypes.c_char_p
     lib.rvq_last_hip_error.argtypes = [vp]
@@ -164,6 +165,11 @@ def rvq_decode_packed(ctx, dPacked, dStd, N, depth_used, dOut, ldo, stream=None)
                                       ldo, _stream(stream)), ctx)
 
 
+def rvq_decode_rope(ctx, dCodes, dStd, N, depth_used, dCos, dSin, head_dim, dOut, ldo, stream=None):
+    return _chk(lib.rvq_decode_rope(ctx, _ptr(dCodes), _ptr(dStd), N, depth_used, _ptr(dCos),
+                                    _ptr(dSin), head_dim, _ptr(dOut), ldo, _stream(stream)), ctx)
+
+
 def rvq_get_counters(ctx):
     out = (ctypes.c_int64 * 16)()  # debug builds report more
     _chk(lib.rvq_get_counters(ctx, out), ctx)
@@ -232,6 +238,16 @@ class Quantizer:
             out = torch.empty((N, self.cfg["d"]), dtype=dt, device=codes.device)
         rvq_decode(self.ctx, codes, std, N, depth_used or self.cfg["depth"], out,
                    out.stride(0) if N else self.cfg["d"])
+        return out
+
+    def decode_rope(self, codes, std, cos, sin, head_dim, depth_used=None, out=None):
+        import torch
+        N = codes.shape[0]
+        if out is None:
+            dt = torch.float16 if self.cfg["out_dtype"] == F16 else torch.float32
+            out = torch.empty((N, self.cfg["d"]), dtype=dt, device=codes.device)
+        rvq_decode_rope(self.ctx, codes, std, N, depth_used or self.cfg["depth"], cos, sin, head_dim,
+                        out, out.stride(0) if N else self.cfg["d"])
         return out
 
     def pack(self, codes):

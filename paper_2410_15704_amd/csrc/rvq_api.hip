@@ -216,7 +216,7 @@ int rvq_decode(rvq_ctx *ctx, const int16_t *dCodes, const void *dStd, int64_t N,
   if (dStd && !aligned16(dStd)) return RVQ_EINVAL;
   if (N > (INT64_MAX / 4) / ldo) return RVQ_EINVAL;
   if (!ctx->have_codebooks) return RVQ_ENOCODEBOOK;
-  RVQ_HIP(ctx, rvq_launch_decode(ctx, dCodes, 0, dStd, N, depth_used, dOut, ldo, (hipStream_t)stream));
+  RVQ_HIP(ctx, rvq_launch_decode(ctx, dCodes, 0, dStd, N, depth_used, dOut, ldo, nullptr, nullptr, 0, (hipStream_t)stream));
   return RVQ_OK;
 }
 
@@ -252,7 +252,28 @@ int rvq_decode_packed(rvq_ctx *ctx, const uint8_t *dPacked, const void *dStd, in
   if (dStd && !aligned16(dStd)) return RVQ_EINVAL;
   if (N > (INT64_MAX / 4) / ldo) return RVQ_EINVAL;
   if (!ctx->have_codebooks) return RVQ_ENOCODEBOOK;
-  RVQ_HIP(ctx, rvq_launch_decode(ctx, dPacked, 1, dStd, N, depth_used, dOut, ldo, (hipStream_t)stream));
+  RVQ_HIP(ctx, rvq_launch_decode(ctx, dPacked, 1, dStd, N, depth_used, dOut, ldo, nullptr, nullptr, 0, (hipStream_t)stream));
+  return RVQ_OK;
+}
+
+int rvq_decode_rope(rvq_ctx *ctx, const int16_t *dCodes, const void *dStd, int64_t N,
+                    int32_t depth_used, const float *dCos, const float *dSin, int32_t head_dim,
+                    void *dOut, int64_t ldo, void *stream) {
+  if (!ctx || N < 0) return RVQ_EINVAL;
+  const rvq_config &c = ctx->cfg;
+  if (depth_used < 1 || depth_used > c.depth) return RVQ_EINVAL;
+  if (ldo < c.d) return RVQ_EINVAL;
+  if (head_dim < 2 || (head_dim & 1) || c.d % head_dim != 0) return RVQ_EINVAL;
+  if (c.grouping == RVQ_STRIDED && (ctx->G & 1)) return RVQ_EINVAL;  // pairs of adjacent channels
+  if (N == 0) return ctx->have_codebooks ? RVQ_OK : RVQ_ENOCODEBOOK;
+  if (!dCodes || !dOut || !dCos || !dSin || !aligned16(dCodes) || !aligned16(dOut) ||
+      !aligned16(dCos) || !aligned16(dSin))
+    return RVQ_EINVAL;
+  if (dStd && !aligned16(dStd)) return RVQ_EINVAL;
+  if (N > (INT64_MAX / 4) / ldo) return RVQ_EINVAL;
+  if (!ctx->have_codebooks) return RVQ_ENOCODEBOOK;
+  RVQ_HIP(ctx, rvq_launch_decode(ctx, dCodes, 0, dStd, N, depth_used, dOut, ldo, dCos, dSin, head_dim,
+                                 (hipStream_t)stream));
   return RVQ_OK;
 }
 

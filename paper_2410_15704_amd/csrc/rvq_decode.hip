@@ -17,6 +17,15 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// sum * std, rounded to fp32.  The empty asm keeps the compiler from merging the multiplication
+// with the later conversion to fp16 into one mixed-precision instruction (one rounding instead of
+// two), which it would do in some kernels and not in others: all decode paths agree bit for bit.
+__device__ __forceinline__ float scale_by_std(float acc, float sd) {
+  float v = acc * sd;
+  asm volatile("" : "+v"(v));
+  return v;
+}
+
 __device__ __forceinline__ int clamp_code(int k, int K) { return k < 0 ? 0 : (k >= K ? K - 1 : k); }
 
 __device__ __forceinline__ float load_std(const void *std_in, int std_dtype, int64_t n) {
@@ -64,17 +73,41 @@ __device__ __forceinline__ int code_of(const i32x4 w, int i) {
   }
 }
 
+
+// ---- rotary position embedding fused into the decode (Section 3: keys are quantized before the
+// rotary embedding, so every decoded key is rotated before it is used).  Within a head of hd
+// channels the pair (x[2i], x[2i+1]) of token n becomes
+// (x[2i] cos[n][i] - x[2i+1] sin[n][i], x[2i] sin[n][i] + x[2i+1] cos[n][i]); tables [N][hd/2] fp32.
+struct RopeArgs {
+  const float *cs;  // nullptr: no rotation
+  const float *sn;
+  int hd;
+};
+__device__ __forceinline__ void rope_pair(const RopeArgs &rp, int64_t n, int c_even, float &x0,
+                                          float &x1) {
+  const int i = (c_even % rp.hd) >> 1;
+  const int64_t t = n * (rp.hd >> 1) + i;
+  const float co = rp.cs[t], si = rp.sn[t];
+  const float y0 = x0 * co - x1 * si;
+  const float y1 = x0 * si + x1 * co;
+  x0 = y0;
+  x1 = y1;
+}
+
 // ---- generic kernel: one thread per output channel, any dhat ------------------------------
 template <bool OUT_F16>
 __global__ __launch_bounds__(256) void decode_generic_kernel(
     const void *__restrict__ codes, int pk_bits /* 0: int16 codes, else bits per packed code */,
     int rec_bytes, const void *__restrict__ std_in, int std_dtype, int64_t N,
     int d, int G, int dhat, int grouping, const float *__restrict__ C, int K, int depth,
-    int depth_used, void *__restrict__ out, int64_t ldo) {
+    int depth_used, void *__restrict__ out, int64_t ldo, RopeArgs rp) {
   const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= N * d) return;
   const int64_t n = e / d;
-  const int c = (int)(e - n * d);
+  const int c_own = (int)(e - n * d);
+  float val[2] = {0.f, 0.f};  // [0]: this thread's channel; [1]: its rotation partner c ^ 1
+  for (int which = 0; which < (rp.cs ? 2 : 1); ++which) {
+  const int c = which ? (c_own ^ 1) : c_own;
   int g, j;
   if (grouping == RVQ_CONTIGUOUS) {
     g = c / dhat;
@@ -99,19 +132,28 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(
     k = clamp_code(k, K);
     acc += C[((int64_t)i * K + k) * dhat + j];
   }
-  acc *= load_std(std_in, std_dtype, n);
-  if (OUT_F16) ((uint16_t *)out)[n * ldo + c] = __half_as_ushort(__float2half_rn(acc));
-  else ((float *)out)[n * ldo + c] = acc;
+  val[which] = scale_by_std(acc, load_std(std_in, std_dtype, n));
+  }
+  float acc = val[0];
+  if (rp.cs) {
+    float x0 = (c_own & 1) ? val[1] : val[0], x1 = (c_own & 1) ? val[0] : val[1];
+    rope_pair(rp, n, c_own & ~1, x0, x1);
+    acc = (c_own & 1) ? x1 : x0;
+  }
+  if (OUT_F16) ((uint16_t *)out)[n * ldo + c_own] = __half_as_ushort(__float2half_rn(acc));
+  else ((float *)out)[n * ldo + c_own] = acc;
 }
 
 // ---- row-gather kernel, dhat == 32 -------------------------------------------------------
 constexpr int DEC_WAVES = 4;
 
-template <bool OUT_F16, bool STRIDED, int DEPTH8, int PK>
+// ROPE (strided grouping only matters): the staged row is kept in fp32 so that the rotation sees
+// unrounded values
+template <bool OUT_F16, bool STRIDED, int DEPTH8, int PK, bool ROPE>
 __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
     const void *__restrict__ codes_v, const void *__restrict__ std_in, int std_dtype, int64_t N,
     int G, const float *__restrict__ C, int K, int depth, int depth_used, void *__restrict__ out,
-    int64_t ldo, int lds_row /* padded LDS row length in elements (strided only) */) {
+    int64_t ldo, int lds_row /* padded LDS row length in elements (strided only) */, RopeArgs rp) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -119,7 +161,8 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
   const int q = lane & 7;   // which 4-channel quarter of the codeword
   const int d = G * 32;
   using out_t = typename std::conditional<OUT_F16, uint16_t, float>::type;
-  out_t *stage = reinterpret_cast<out_t *>(smem) + (size_t)wave * lds_row * 32;
+  using stage_t = typename std::conditional<ROPE, float, out_t>::type;
+  stage_t *stage = reinterpret_cast<stage_t *>(smem) + (size_t)wave * lds_row * 32;
 
   const int64_t wave_global = (int64_t)blockIdx.x * DEC_WAVES + wave;
   const int64_t wave_count = (int64_t)gridDim.x * DEC_WAVES;
@@ -151,8 +194,13 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
             acc.x += c4.x; acc.y += c4.y; acc.z += c4.z; acc.w += c4.w;
           }
         }
-        acc.x *= sd; acc.y *= sd; acc.z *= sd; acc.w *= sd;
+        acc.x = scale_by_std(acc.x, sd); acc.y = scale_by_std(acc.y, sd);
+        acc.z = scale_by_std(acc.z, sd); acc.w = scale_by_std(acc.w, sd);
         if (!STRIDED) {
+          if (ROPE) {  // channels g * 32 + 4 q .. + 3: two pairs, both in this lane
+            rope_pair(rp, n, g * 32 + q * 4, acc.x, acc.y);
+            rope_pair(rp, n, g * 32 + q * 4 + 2, acc.z, acc.w);
+          }
           out_t *o = reinterpret_cast<out_t *>(out) + n * ldo + (int64_t)g * 32 + q * 4;
           if (OUT_F16) {
             uint2 pk;
@@ -172,8 +220,9 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
 #pragma unroll
           for (int t = 0; t < 4; ++t) {
             const int j = q * 4 + t;
-            if (OUT_F16) stage[j * lds_row + g] = (out_t)__half_as_ushort(__float2half_rn(a[t]));
-            else stage[j * lds_row + g] = (out_t)a[t];
+            if (ROPE) stage[j * lds_row + g] = (stage_t)a[t];
+            else if (OUT_F16) stage[j * lds_row + g] = (stage_t)__half_as_ushort(__float2half_rn(a[t]));
+            else stage[j * lds_row + g] = (stage_t)a[t];
           }
         }
       }
@@ -182,7 +231,24 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
       // the wavefront's own LDS writes are visible to its later reads (same wave, in order)
       __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
       out_t *o = reinterpret_cast<out_t *>(out) + n * ldo;
-      if (OUT_F16) {
+      if (ROPE) {
+        // adjacent channels (c, c + 1) are adjacent groups of one LDS row: rotate, then round
+        for (int c = lane * 2; c < d; c += 128) {
+          const int j = c / G, g = c - j * G;
+          const float *sp = reinterpret_cast<const float *>(&stage[j * lds_row + g]);
+          float x0 = sp[0], x1 = sp[1];
+          rope_pair(rp, n, c, x0, x1);
+          if (OUT_F16) {
+            const uint32_t v = (uint32_t)__half_as_ushort(__float2half_rn(x0)) |
+                               ((uint32_t)__half_as_ushort(__float2half_rn(x1)) << 16);
+            __builtin_nontemporal_store(v, reinterpret_cast<uint32_t *>(o + c));
+          } else {
+            typedef float f32x2r __attribute__((ext_vector_type(2)));
+            const f32x2r v = {x0, x1};
+            __builtin_nontemporal_store(v, reinterpret_cast<f32x2r *>(o + c));
+          }
+        }
+      } else if (OUT_F16) {
         // two fp16 channels per lane per step (G is even on this path)
         for (int c = lane * 2; c < d; c += 128) {
           const int j = c / G, g = c - j * G;
@@ -221,7 +287,7 @@ template <bool OUT_F16, int KC, int GS, int DU, int PK>
 __global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
     const void *__restrict__ codes, const void *__restrict__ std_in, int std_dtype, int64_t N,
     int G, const float *__restrict__ Csplit, int Krt, int depth, int depth_used_rt,
-    void *__restrict__ out, int64_t ldo) {
+    void *__restrict__ out, int64_t ldo, RopeArgs rp) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int depth_used = DU ? DU : depth_used_rt;
   // the table [depth][K] starts at LDS address 0: this kernel has no other LDS, and a literal
@@ -310,14 +376,15 @@ __global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
         }
       }
       const float sd = valid ? load_std(std_in, std_dtype, n0 + nl) : 0.f;
-      acc.x *= sd;
-      acc.y *= sd;
+      acc.x = scale_by_std(acc.x, sd);
+      acc.y = scale_by_std(acc.y, sd);
       // pair exchange: the even lane ends up with channel 2a of groups (g, g + 1), the odd lane
       // with channel 2a + 1 of groups (g - 1, g): two adjacent outputs each
       const float give = odd ? acc.x : acc.y;
       const float got = __shfl_xor(give, 1, 64);
-      const float lo = odd ? got : acc.x;
-      const float hi = odd ? acc.y : got;
+      float lo = odd ? got : acc.x;
+      float hi = odd ? acc.y : got;
+      if (valid && rp.cs) rope_pair(rp, n0 + nl, chan + (g & ~1), lo, hi);
       if (valid) {
         out_t *o = out0 + ((int64_t)nl * ldo + chan + (g & ~1));
         if (OUT_F16) {
@@ -338,8 +405,11 @@ __global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
 }  // namespace
 
 hipError_t rvq_launch_decode(const rvq_ctx *ctx, const void *dCodes, int packed, const void *dStd,
-                             int64_t N, int depth_used, void *dOut, int64_t ldo, hipStream_t s) {
+                             int64_t N, int depth_used, void *dOut, int64_t ldo, const float *dCos,
+                             const float *dSin, int head_dim, hipStream_t s) {
   const rvq_config &c = ctx->cfg;
+  const RopeArgs rp = {dCos, dSin, head_dim > 0 ? head_dim : 2};
+  const bool rope = dCos != nullptr;
   const bool f16 = c.out_dtype == RVQ_F16;
   const int G = ctx->G;
   const size_t osz = f16 ? 2 : 4;
@@ -364,7 +434,7 @@ hipError_t rvq_launch_decode(const rvq_ctx *ctx, const void *dCodes, int packed,
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)tab_bytes);            \
   if (e != hipSuccess) return e;                                                                  \
   hipLaunchKernelGGL((decode_split_kernel<F16, KC, GS, DU, PK>), grid, block, tab_bytes, s, dCodes, \
-                     dStd, c.std_dtype, N, G, ctx->Csplit, c.K, c.depth, depth_used, dOut, ldo)
+                     dStd, c.std_dtype, N, G, ctx->Csplit, c.K, c.depth, depth_used, dOut, ldo, rp)
     const bool fast = c.K == 2048 && g_shift == 5 && depth_used == 8;
     if (pk == 0) {
       if (fast) { if (f16) { RVQ_LAUNCH_SPLIT(true, 2048, 5, 8, 0); } else { RVQ_LAUNCH_SPLIT(false, 2048, 5, 8, 0); } }
@@ -380,10 +450,10 @@ hipError_t rvq_launch_decode(const rvq_ctx *ctx, const void *dCodes, int packed,
   int lds_row = 0;
   size_t lds_bytes = 0;
   if (strided) {
-    lds_row = G + (f16 ? 2 : 1);
-    lds_bytes = (size_t)DEC_WAVES * 32 * lds_row * osz;
+    lds_row = G + ((f16 || rope) ? 2 : 1);  // the rotation reads pairs: rows of an even length
+    lds_bytes = (size_t)DEC_WAVES * 32 * lds_row * (rope ? 4 : osz);
   }
-  const bool rows_ok = c.dhat == 32 && (ldo * osz) % 16 == 0 && (!packed || pk) &&
+  const bool rows_ok = c.dhat == 32 && (ldo * osz) % 16 == 0 && (!packed || pk) && !(rope && pk) &&
                        (!strided || (G % 2 == 0 && lds_bytes <= 64 * 1024));
   if (rows_ok) {
     int64_t blocks = (N + DEC_WAVES - 1) / DEC_WAVES;
@@ -391,15 +461,17 @@ hipError_t rvq_launch_decode(const rvq_ctx *ctx, const void *dCodes, int packed,
     if (blocks > cap) blocks = cap;
     const dim3 grid((unsigned)blocks), block(64 * DEC_WAVES);
     const bool d8 = c.depth == 8;
-#define RVQ_LAUNCH_ROWS(F16, STR, D8, PK)                                                        \
-  hipLaunchKernelGGL((decode_rows32_kernel<F16, STR, D8, PK>), grid, block, lds_bytes, s, dCodes, \
-                     dStd, c.std_dtype, N, G, ctx->C, c.K, c.depth, depth_used, dOut, ldo, lds_row)
+#define RVQ_LAUNCH_ROWS(F16, STR, D8, PK, RO)                                                    \
+  hipLaunchKernelGGL((decode_rows32_kernel<F16, STR, D8, PK, RO>), grid, block, lds_bytes, s,    \
+                     dCodes, dStd, c.std_dtype, N, G, ctx->C, c.K, c.depth, depth_used, dOut,    \
+                     ldo, lds_row, rp)
 #define RVQ_LAUNCH_ROWS_FS(F16, STR)                                                             \
   do {                                                                                           \
-    if (pk == 11) RVQ_LAUNCH_ROWS(F16, STR, 1, 11);                                              \
-    else if (pk == 12) RVQ_LAUNCH_ROWS(F16, STR, 1, 12);                                         \
-    else if (d8) RVQ_LAUNCH_ROWS(F16, STR, 1, 0);                                                \
-    else RVQ_LAUNCH_ROWS(F16, STR, 0, 0);                                                        \
+    if (rope) { if (d8) RVQ_LAUNCH_ROWS(F16, STR, 1, 0, true); else RVQ_LAUNCH_ROWS(F16, STR, 0, 0, true); } \
+    else if (pk == 11) RVQ_LAUNCH_ROWS(F16, STR, 1, 11, false);                                  \
+    else if (pk == 12) RVQ_LAUNCH_ROWS(F16, STR, 1, 12, false);                                  \
+    else if (d8) RVQ_LAUNCH_ROWS(F16, STR, 1, 0, false);                                         \
+    else RVQ_LAUNCH_ROWS(F16, STR, 0, 0, false);                                                 \
   } while (0)
     if (f16) { if (strided) RVQ_LAUNCH_ROWS_FS(true, true); else RVQ_LAUNCH_ROWS_FS(true, false); }
     else { if (strided) RVQ_LAUNCH_ROWS_FS(false, true); else RVQ_LAUNCH_ROWS_FS(false, false); }
@@ -413,10 +485,10 @@ hipError_t rvq_launch_decode(const rvq_ctx *ctx, const void *dCodes, int packed,
   if (f16)
     hipLaunchKernelGGL(decode_generic_kernel<true>, dim3((unsigned)grid64), dim3(256), 0, s, dCodes,
                        bits, rec, dStd, c.std_dtype, N, c.d, G, c.dhat, c.grouping, ctx->C, c.K,
-                       c.depth, depth_used, dOut, ldo);
+                       c.depth, depth_used, dOut, ldo, rp);
   else
     hipLaunchKernelGGL(decode_generic_kernel<false>, dim3((unsigned)grid64), dim3(256), 0, s,
                        dCodes, bits, rec, dStd, c.std_dtype, N, c.d, G, c.dhat, c.grouping, ctx->C,
-                       c.K, c.depth, depth_used, dOut, ldo);
+                       c.K, c.depth, depth_used, dOut, ldo, rp);
   return hipGetLastError();
 }

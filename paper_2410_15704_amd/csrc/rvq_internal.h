@@ -103,8 +103,10 @@ hipError_t rvq_launch_encode_screen(const rvq_ctx *ctx, const void *dX, int64_t 
                                     int stage_begin, int stage_end, int16_t *dCodes,
                                     float *dResidual, hipStream_t s);
 // dCodes: int16 [N][G][depth] (packed == 0) or packed records [N][G][rvq_record_bytes] (packed == 1)
+// dCos / dSin: rotary tables [N][head_dim / 2] fp32, or nullptr for a plain decode
 hipError_t rvq_launch_decode(const rvq_ctx *ctx, const void *dCodes, int packed, const void *dStd,
-                             int64_t N, int depth_used, void *dOut, int64_t ldo, hipStream_t s);
+                             int64_t N, int depth_used, void *dOut, int64_t ldo, const float *dCos,
+                             const float *dSin, int head_dim, hipStream_t s);
 hipError_t rvq_launch_pack(const rvq_ctx *ctx, const int16_t *dCodes, int64_t N, uint8_t *dPacked,
                            hipStream_t s);
 hipError_t rvq_launch_unpack(const rvq_ctx *ctx, const uint8_t *dPacked, int64_t N, int16_t *dCodes,

@@ -607,6 +607,82 @@ def q_unpack_roundtrip(b, torch, codes, packed, K, depth, G, d):
     return out
 
 
+def _check_rope(out_gpu, ref, mode):
+    if mode == "fp32":
+        g = out_gpu.astype(np.float64)
+        rown = np.linalg.norm(ref, axis=1)
+        rowmax = np.abs(ref).max(axis=1)
+        assert np.all(np.linalg.norm(g - ref, axis=1) <= 1e-6 * rown + 1e-300)
+        assert np.all(np.abs(g - ref) <= 1e-6 * rowmax[:, None] + 1e-300)
+    else:
+        want = ref.astype(np.float16).view(np.uint16)
+        ulp = _half_ulp_distance(out_gpu.view(np.uint16), want)
+        near_zero = np.abs(out_gpu.astype(np.float64) - ref) <= 1e-6 * np.abs(ref).max(axis=1)[:, None]
+        assert np.all((ulp <= 1) | near_zero)
+        assert (ulp == 0).mean() >= 0.999
+
+
+@pytest.mark.parametrize("case", [
+    # N, d, dhat, depth, K, grouping, head_dim
+    (300, 256, 32, 5, 100, oracle.STRIDED, 64),       # row-gather kernel, general depth
+    (300, 256, 32, 5, 100, oracle.CONTIGUOUS, 64),
+    (1000, 1024, 32, 8, 2048, oracle.STRIDED, 128),   # row-gather kernel, depth 8
+    (1000, 1024, 32, 8, 2048, oracle.CONTIGUOUS, 128),
+    (200, 64, 8, 3, 50, oracle.STRIDED, 32),          # generic kernel
+    (200, 40, 20, 2, 17, oracle.CONTIGUOUS, 20),      # generic kernel, odd sizes
+])
+def test_decode_rope_small(gpu_device, case):
+    """rvq_decode_rope against the oracle's decode + rotation (same codes, std and tables)."""
+    torch, b = _torch(), _b()
+    N, d, dhat, depth, K, grouping, hd = case
+    G = d // dhat
+    rng = np.random.Generator(np.random.PCG64(N + d + hd))
+    codes = rng.integers(0, K, size=(N, G, depth)).astype(np.int16)
+    std = np.exp(0.3 * rng.standard_normal(N)).astype(np.float16)
+    C = (rng.standard_normal((depth, K, dhat)) * (0.6 ** np.arange(depth))[:, None, None]).astype(np.float32)
+    cos, sin = oracle.rope_tables(rng.integers(0, 32768, N), hd)
+    cos32, sin32 = cos.astype(np.float32), sin.astype(np.float32)
+    ref = oracle.decode_rope(codes.astype(np.int32), std.astype(np.float64), C.astype(np.float64), d,
+                             grouping, cos32, sin32, hd)
+    for mode, odt in (("fp32", b.F32), ("fp16", b.F16)):
+        q = b.Quantizer(d=d, dhat=dhat, depth=depth, K=K, grouping=grouping, out_dtype=odt,
+                        std_dtype=b.F16)
+        q.set_codebooks(torch.from_numpy(C).cuda())
+        out = q.decode_rope(torch.from_numpy(codes).cuda(), torch.from_numpy(std).cuda(),
+                            torch.from_numpy(cos32).cuda(), torch.from_numpy(sin32).cuda(), hd)
+        _check_rope(out.cpu().numpy(), ref, mode)
+        q.close()
+
+
+def test_decode_rope_full_slice(gpu_device):
+    """A workload-3 slice (524288 tokens x 8 heads of 128, strided: the LDS kernel; contiguous: the
+    row-gather kernel) decoded with the rotation; the oracle checks 512 seeded rows."""
+    torch, b = _torch(), _b()
+    T, d, G, depth, K, hd = 16 * 32768, 1024, 32, 8, 2048, 128
+    C = synth.decode_codebooks(1)[0]
+    std = torch.from_numpy(synth.decode_std_fp16(T)).cuda()
+    codes = synth.uniform_codes_device(T, G, depth, K, "cuda", extra=400)
+    pos = np.arange(T) % 32768
+    cos, sin = oracle.rope_tables(pos, hd)
+    cos32, sin32 = cos.astype(np.float32), sin.astype(np.float32)
+    dcos, dsin = torch.from_numpy(cos32).cuda(), torch.from_numpy(sin32).cuda()
+    rows = np.sort(np.random.Generator(np.random.PCG64(4)).choice(T, 512, replace=False))
+    rows[0], rows[-1] = 0, T - 1
+    rt = torch.from_numpy(rows).cuda()
+    c_np = codes[rt].cpu().numpy().astype(np.int32)
+    s_np = std[rt].cpu().numpy().astype(np.float64)
+    for grouping in (oracle.STRIDED, oracle.CONTIGUOUS):
+        ref = oracle.decode_rope(c_np, s_np, C.astype(np.float64), d, grouping, cos32[rows], sin32[rows], hd)
+        for mode, odt in (("fp16", b.F16), ("fp32", b.F32)):
+            q = b.Quantizer(d=d, dhat=32, depth=depth, K=K, grouping=grouping, out_dtype=odt,
+                            std_dtype=b.F16)
+            q.set_codebooks(torch.from_numpy(C).cuda())
+            out = q.decode_rope(codes, std, dcos, dsin, hd)
+            _check_rope(out[rt].cpu().numpy(), ref, mode)
+            del out
+            q.close()
+
+
 @pytest.mark.parametrize("schedule", ["sequential", "online"])
 def test_ema_training_schedule_matches_oracle(gpu_device, schedule):
     """Workload 4's procedure at reduced size (30000 mixture vectors, depth 3, K = 96, 5 rounds,

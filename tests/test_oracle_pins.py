@@ -456,3 +456,38 @@ def test_ema_training_schedules_reduce_to_known_cases():
     a = oracle.ema_train(Z, 1, 24, 4, 0.9, 1e-5, picks[:1], "sequential")
     c = oracle.ema_train(Z, 1, 24, 4, 0.9, 1e-5, picks[:1], "online")
     np.testing.assert_allclose(a, c, rtol=1e-12)
+
+
+# ---- Section 3: keys are quantized before the rotary embedding -----------------------------------
+def test_decode_rope_against_complex_multiplication_and_special_angles():
+    """The rotary embedding of the decoded vector: pair i as a complex number times
+    exp(1j * angle_i) (an independent formulation); angle 0 leaves the decode untouched; a quarter
+    turn maps (a, b) to (-b, a); turning by p then q equals turning by p + q; pair norms are kept."""
+    rng = np.random.Generator(np.random.PCG64(71))
+    N, d, hd, depth, K = 9, 256, 64, 3, 20
+    C = rng.standard_normal((depth, K, 32))
+    codes = rng.integers(0, K, (N, d // 32, depth))
+    std = np.exp(rng.standard_normal(N))
+    x = oracle.decode(codes, std, C, d, oracle.STRIDED)
+    pos = rng.integers(0, 5000, N)
+    cos, sin = oracle.rope_tables(pos, hd)
+    y = oracle.decode_rope(codes, std, C, d, oracle.STRIDED, cos, sin, hd)
+    z = (x.reshape(N, d // hd, hd // 2, 2) @ np.array([1.0, 1j])) * (cos + 1j * sin)[:, None, :]
+    np.testing.assert_allclose(y.reshape(N, d // hd, hd // 2, 2)[..., 0], z.real, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(y.reshape(N, d // hd, hd // 2, 2)[..., 1], z.imag, rtol=1e-12, atol=1e-12)
+    one, zero = np.ones((N, hd // 2)), np.zeros((N, hd // 2))
+    assert np.array_equal(oracle.decode_rope(codes, std, C, d, oracle.STRIDED, one, zero, hd), x)
+    q = oracle.decode_rope(codes, std, C, d, oracle.STRIDED, zero, one, hd).reshape(N, -1, 2)
+    assert np.array_equal(q[..., 0], -x.reshape(N, -1, 2)[..., 1])
+    assert np.array_equal(q[..., 1], x.reshape(N, -1, 2)[..., 0])
+    np.testing.assert_allclose(np.linalg.norm(y.reshape(N, -1, 2), axis=2),
+                               np.linalg.norm(x.reshape(N, -1, 2), axis=2), rtol=1e-12)
+    # angles add: tables of positions p and q applied one after the other = table of p + q
+    c1, s1 = oracle.rope_tables(pos, hd)
+    c2, s2 = oracle.rope_tables(2 * pos, hd)
+    c3, s3 = oracle.rope_tables(3 * pos, hd)
+    w = y.reshape(N, d // hd, hd // 2, 2)
+    twice = np.stack([w[..., 0] * c2[:, None] - w[..., 1] * s2[:, None],
+                      w[..., 0] * s2[:, None] + w[..., 1] * c2[:, None]], axis=-1).reshape(N, d)
+    np.testing.assert_allclose(twice, oracle.decode_rope(codes, std, C, d, oracle.STRIDED, c3, s3, hd),
+                               rtol=1e-9, atol=1e-9)
