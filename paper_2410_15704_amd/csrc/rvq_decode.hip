@@ -283,7 +283,10 @@ constexpr int SPL_UNROLL = 4;  // (token, group) pairs per thread and trip
 // with a mask and the stage offsets become instruction immediates), 0 for any other size.
 // GS: log2 of the group count when that is a power of two, -1 otherwise.
 // DU: the number of stages summed when known at compile time (straight-line gathers), else 0.
-template <bool OUT_F16, int KC, int GS, int DU, int PK>
+// SDT: the std type when fixed at compile time (RVQ_F16 / RVQ_F32, std present), -1 otherwise.
+// ROPE: 1 rotate, 0 do not, -1 decide at run time.  Fixing both keeps the loop free of branches
+// around its loads, so the loads of the next trip stay in flight while this one is worked on.
+template <bool OUT_F16, int KC, int GS, int DU, int PK, int SDT, int ROPE>
 __global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
     const void *__restrict__ codes, const void *__restrict__ std_in, int std_dtype, int64_t N,
     int G, const float *__restrict__ Csplit, int Krt, int depth, int depth_used_rt,
@@ -325,24 +328,36 @@ __global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
   const int chan = (2 * a + (odd ? 1 : 0)) * G;  // first output channel of this lane's pair
   // trips c = xcd (mod 8) belong to this XCD; its `parts` workgroups per channel pair take them
   // in turn.  Everything inside a trip is addressed with 32-bit offsets from per-trip bases.
+  // codes and std of a trip are fetched one trip ahead
   i32x4 cur[SPL_UNROLL], nxt[SPL_UNROLL];
-  auto load_trip = [&](int64_t c, i32x4 *dst) {
-    const int64_t left = V - c * TRIP;
+  float cur_sd[SPL_UNROLL], nxt_sd[SPL_UNROLL];
+  // Loads carry no bounds branch: a pair index beyond the end is clamped to the last pair (V >= 1
+  // on this path), whose data is fetched and never stored.
+  auto load_trip = [&](int64_t c, i32x4 *dst, float *dst_sd) {
+    const int64_t e0 = c * TRIP;
 #pragma unroll
     for (int u = 0; u < SPL_UNROLL; ++u) {
-      const int q = u * SPL_THREADS + tid;
-      const i32x4 zero = {0, 0, 0, 0};
+      const int64_t e = min(e0 + (u * SPL_THREADS + tid), V - 1);
       // plain loads: the other 15 channel-pair workgroups of this XCD find the line in its L2
-      dst[u] = (c < trips && q < left) ? load_codes8<PK, false>(codes, c * TRIP + q) : zero;
+      dst[u] = load_codes8<PK, false>(codes, e);
+      int64_t n;
+      if constexpr (GS >= 0) n = e >> GS;
+      else n = e / G;
+      if constexpr (SDT == RVQ_F16)
+        // the raw bits travel; they are widened where they are used, a trip later
+        dst_sd[u] = __uint_as_float((uint32_t) reinterpret_cast<const uint16_t *>(std_in)[n]);
+      else if constexpr (SDT == RVQ_F32)
+        dst_sd[u] = reinterpret_cast<const float *>(std_in)[n];
+      else
+        dst_sd[u] = load_std(std_in, std_dtype, n);
     }
   };
   const int64_t step = 8 * (int64_t)parts;
   int64_t c = xcd + 8 * (int64_t)part;
-  load_trip(c, cur);
-  for (; c < trips; c += step) {
-    load_trip(c + step, nxt);
+  load_trip(c, cur, cur_sd);
+  auto do_trip = [&]() {
     const int64_t e0 = c * TRIP;
-    const int64_t left = V - e0;
+    const int left = (int)min((int64_t)TRIP, V - e0);
     int64_t n0 = 0;
     if constexpr (GS >= 0) n0 = e0 >> GS;  // TRIP is a multiple of G: a trip starts at a token boundary
     out_t *out0 = reinterpret_cast<out_t *>(out) + n0 * ldo;
@@ -375,16 +390,23 @@ __global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
           }
         }
       }
-      const float sd = valid ? load_std(std_in, std_dtype, n0 + nl) : 0.f;
+      float sd = cur_sd[u];
+      if constexpr (SDT == RVQ_F16) sd = rvq_f16_bits_to_f32((uint16_t)__float_as_uint(sd));
       acc.x = scale_by_std(acc.x, sd);
       acc.y = scale_by_std(acc.y, sd);
       // pair exchange: the even lane ends up with channel 2a of groups (g, g + 1), the odd lane
-      // with channel 2a + 1 of groups (g - 1, g): two adjacent outputs each
+      // with channel 2a + 1 of groups (g - 1, g): two adjacent outputs each.  Neighbour lanes
+      // swap within their quad (data-parallel-primitive move, no LDS traffic).
       const float give = odd ? acc.x : acc.y;
-      const float got = __shfl_xor(give, 1, 64);
+      const float got = __int_as_float(__builtin_amdgcn_mov_dpp(
+          __float_as_int(give), 0xB1 /* quad_perm [1,0,3,2] */, 0xf, 0xf, true));
       float lo = odd ? got : acc.x;
       float hi = odd ? acc.y : got;
-      if (valid && rp.cs) rope_pair(rp, n0 + nl, chan + (g & ~1), lo, hi);
+      if constexpr (ROPE == 1) {
+        if (valid) rope_pair(rp, n0 + nl, chan + (g & ~1), lo, hi);
+      } else if constexpr (ROPE == -1) {
+        if (valid && rp.cs) rope_pair(rp, n0 + nl, chan + (g & ~1), lo, hi);
+      }
       if (valid) {
         out_t *o = out0 + ((int64_t)nl * ldo + chan + (g & ~1));
         if (OUT_F16) {
@@ -397,8 +419,15 @@ __global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
         }
       }
     }
+  };
+  for (; c < trips; c += step) {
+    load_trip(c + step, nxt, nxt_sd);
+    do_trip();
 #pragma unroll
-    for (int u = 0; u < SPL_UNROLL; ++u) cur[u] = nxt[u];
+    for (int u = 0; u < SPL_UNROLL; ++u) {
+      cur[u] = nxt[u];
+      cur_sd[u] = nxt_sd[u];
+    }
   }
 }
 
@@ -429,19 +458,26 @@ hipError_t rvq_launch_decode(const rvq_ctx *ctx, const void *dCodes, int packed,
     if (g_shift < 0 && N > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid(256), block(SPL_THREADS);
     hipError_t e;
-#define RVQ_LAUNCH_SPLIT(F16, KC, GS, DU, PK)                                                     \
-  e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_split_kernel<F16, KC, GS, DU, PK>), \
-                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)tab_bytes);            \
-  if (e != hipSuccess) return e;                                                                  \
-  hipLaunchKernelGGL((decode_split_kernel<F16, KC, GS, DU, PK>), grid, block, tab_bytes, s, dCodes, \
-                     dStd, c.std_dtype, N, G, ctx->Csplit, c.K, c.depth, depth_used, dOut, ldo, rp)
-    const bool fast = c.K == 2048 && g_shift == 5 && depth_used == 8;
-    if (pk == 0) {
-      if (fast) { if (f16) { RVQ_LAUNCH_SPLIT(true, 2048, 5, 8, 0); } else { RVQ_LAUNCH_SPLIT(false, 2048, 5, 8, 0); } }
-      else { if (f16) { RVQ_LAUNCH_SPLIT(true, 0, -1, 0, 0); } else { RVQ_LAUNCH_SPLIT(false, 0, -1, 0, 0); } }
-    } else {  // 11-bit records
-      if (fast) { if (f16) { RVQ_LAUNCH_SPLIT(true, 2048, 5, 8, 11); } else { RVQ_LAUNCH_SPLIT(false, 2048, 5, 8, 11); } }
-      else { if (f16) { RVQ_LAUNCH_SPLIT(true, 0, -1, 0, 11); } else { RVQ_LAUNCH_SPLIT(false, 0, -1, 0, 11); } }
+#define RVQ_LAUNCH_SPLIT(F16, KC, GS, DU, PK, SDT, RO)                                            \
+  e = hipFuncSetAttribute(                                                                         \
+      reinterpret_cast<const void *>(&decode_split_kernel<F16, KC, GS, DU, PK, SDT, RO>),          \
+      hipFuncAttributeMaxDynamicSharedMemorySize, (int)tab_bytes);                                 \
+  if (e != hipSuccess) return e;                                                                   \
+  hipLaunchKernelGGL((decode_split_kernel<F16, KC, GS, DU, PK, SDT, RO>), grid, block, tab_bytes,  \
+                     s, dCodes, dStd, c.std_dtype, N, G, ctx->Csplit, c.K, c.depth, depth_used,    \
+                     dOut, ldo, rp)
+    // fully specialised: K = 2048, 32 groups, all 8 stages, fp16 std
+    const bool fast = c.K == 2048 && g_shift == 5 && depth_used == 8 && dStd && c.std_dtype == RVQ_F16;
+    if (fast && pk == 0 && !rope) {
+      if (f16) { RVQ_LAUNCH_SPLIT(true, 2048, 5, 8, 0, RVQ_F16, 0); } else { RVQ_LAUNCH_SPLIT(false, 2048, 5, 8, 0, RVQ_F16, 0); }
+    } else if (fast && pk == 0) {
+      if (f16) { RVQ_LAUNCH_SPLIT(true, 2048, 5, 8, 0, RVQ_F16, 1); } else { RVQ_LAUNCH_SPLIT(false, 2048, 5, 8, 0, RVQ_F16, 1); }
+    } else if (fast && !rope) {  // 11-bit records
+      if (f16) { RVQ_LAUNCH_SPLIT(true, 2048, 5, 8, 11, RVQ_F16, 0); } else { RVQ_LAUNCH_SPLIT(false, 2048, 5, 8, 11, RVQ_F16, 0); }
+    } else if (pk == 0) {
+      if (f16) { RVQ_LAUNCH_SPLIT(true, 0, -1, 0, 0, -1, -1); } else { RVQ_LAUNCH_SPLIT(false, 0, -1, 0, 0, -1, -1); }
+    } else {
+      if (f16) { RVQ_LAUNCH_SPLIT(true, 0, -1, 0, 11, -1, -1); } else { RVQ_LAUNCH_SPLIT(false, 0, -1, 0, 11, -1, -1); }
     }
 #undef RVQ_LAUNCH_SPLIT
     return hipGetLastError();
