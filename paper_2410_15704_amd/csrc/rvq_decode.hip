@@ -61,14 +61,13 @@ __device__ __forceinline__ int code_of(const i32x4 w, int i) {
     const int v = i < 2 ? w.x : (i < 4 ? w.y : (i < 6 ? w.z : w.w));
     return (i & 1) ? (v >> 16) : (int)(int16_t)(v & 0xffff);
   } else {
-    const unsigned long long lo = (unsigned)w.x | ((unsigned long long)(unsigned)w.y << 32);
-    const unsigned long long hi = (unsigned)w.z | ((unsigned long long)(unsigned)w.w << 32);
-    const unsigned long long up = hi >> (8 * (16 - PK));  // record bytes 8 .. PK - 1
-    const int sft = PK * i;
-    unsigned long long v;
-    if (sft + PK <= 64) v = lo >> sft;
-    else if (sft >= 64) v = up >> (sft - 64);
-    else v = (lo >> sft) | (up << (64 - sft));
+    // the record as three 32-bit words: bits 0..63 are the first load, bits 64.. the tail of the
+    // second (which starts at byte PK - 8); a code lies in one word or straddles two
+    const uint32_t W[3] = {(uint32_t)w.x, (uint32_t)w.y, (uint32_t)w.w >> (8 * (12 - PK))};
+    const int word = (PK * i) >> 5, sh = (PK * i) & 31;
+    uint32_t v;
+    if (sh + PK <= 32) v = W[word] >> sh;
+    else v = __builtin_amdgcn_alignbit(W[word + 1], W[word], sh);
     return (int)(v & ((1u << PK) - 1u));
   }
 }
@@ -327,35 +326,35 @@ __global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
   const bool odd = lane & 1;
   const int chan = (2 * a + (odd ? 1 : 0)) * G;  // first output channel of this lane's pair
   // trips c = xcd (mod 8) belong to this XCD; its `parts` workgroups per channel pair take them
-  // in turn.  Everything inside a trip is addressed with 32-bit offsets from per-trip bases.
-  // codes and std of a trip are fetched one trip ahead
-  i32x4 cur[SPL_UNROLL], nxt[SPL_UNROLL];
-  float cur_sd[SPL_UNROLL], nxt_sd[SPL_UNROLL];
+  // in turn.  Everything inside a trip is addressed with 32-bit offsets from per-trip bases that
+  // are the same for the whole workgroup (scalar registers).
+  // Codes and std of a trip are fetched one trip ahead, into two register sets used in turn.
   // Loads carry no bounds branch: a pair index beyond the end is clamped to the last pair (V >= 1
   // on this path), whose data is fetched and never stored.
+  constexpr int REC = PK ? PK : 16;  // bytes of one pair's codes (this kernel is for depth 8)
   auto load_trip = [&](int64_t c, i32x4 *dst, float *dst_sd) {
-    const int64_t e0 = c * TRIP;
+    const int64_t e0 = min(c, trips - 1) * TRIP;
+    const uint32_t last = (uint32_t)min((int64_t)TRIP, V - e0) - 1u;
 #pragma unroll
     for (int u = 0; u < SPL_UNROLL; ++u) {
-      const int64_t e = min(e0 + (u * SPL_THREADS + tid), V - 1);
+      const uint32_t q = min((uint32_t)(u * SPL_THREADS + tid), last);
       // plain loads: the other 15 channel-pair workgroups of this XCD find the line in its L2
-      dst[u] = load_codes8<PK, false>(codes, e);
-      int64_t n;
-      if constexpr (GS >= 0) n = e >> GS;
-      else n = e / G;
-      if constexpr (SDT == RVQ_F16)
+      dst[u] = load_codes8<PK, false>(reinterpret_cast<const char *>(codes) + e0 * REC, q);
+      if constexpr (GS >= 0 && SDT == RVQ_F16) {
         // the raw bits travel; they are widened where they are used, a trip later
-        dst_sd[u] = __uint_as_float((uint32_t) reinterpret_cast<const uint16_t *>(std_in)[n]);
-      else if constexpr (SDT == RVQ_F32)
-        dst_sd[u] = reinterpret_cast<const float *>(std_in)[n];
-      else
+        const uint16_t *sb = reinterpret_cast<const uint16_t *>(std_in) + (e0 >> GS);
+        dst_sd[u] = __uint_as_float((uint32_t)sb[q >> GS]);
+      } else {
+        int64_t n;
+        if constexpr (GS >= 0) n = (e0 + q) >> GS;
+        else n = (e0 + q) / G;
         dst_sd[u] = load_std(std_in, std_dtype, n);
+      }
     }
   };
   const int64_t step = 8 * (int64_t)parts;
   int64_t c = xcd + 8 * (int64_t)part;
-  load_trip(c, cur, cur_sd);
-  auto do_trip = [&]() {
+  auto do_trip = [&](const i32x4 *cur, const float *cur_sd) {
     const int64_t e0 = c * TRIP;
     const int left = (int)min((int64_t)TRIP, V - e0);
     int64_t n0 = 0;
@@ -375,23 +374,54 @@ __global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
         nl = (int)n;  // n0 == 0 here; rows beyond 2^31 are refused by the launcher
       }
       float2 acc = make_float2(0.f, 0.f);
+      if constexpr (KC == 2048 && PK == 0 && DU == 8) {
+        // two codes per 32-bit word: one mask for both, which for stages 4..7 also sets the bit
+        // that becomes the 64 KiB these stages lie beyond the reach of an instruction's offset
+        // field; each half is then shifted into a byte address
+        const int w4[4] = {cur[u].x, cur[u].y, cur[u].z, cur[u].w};
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        if (i < depth_used) {
-          int k = code_of<PK>(cur[u], i);
-          if (KC) k &= KC - 1;
-          else k = clamp_code(k, K);
-          const f32x2 t = tab[i * K + k];
-          if (DU && i == 0) {
-            acc = make_float2(t.x, t.y);  // 0 + t, without the addition
+        for (int h = 0; h < 4; ++h) {
+          const uint32_t m = ((uint32_t)w4[h] & 0x07ff07ffu) | (h >= 2 ? 0x20002000u : 0u);
+          // (one sub-dword-addressed shift per half; written out because the compiler folds
+          // the common mask back into two instructions per code)
+          uint32_t a0, a1;
+          asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD "
+              "src1_sel:WORD_0" : "=v"(a0) : "v"(3u), "v"(m));
+          asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD "
+              "src1_sel:WORD_1" : "=v"(a1) : "v"(3u), "v"(m));
+          typedef __attribute__((address_space(3))) const char lds_c;
+          const f32x2 t0 = *reinterpret_cast<lds_f2 *>(
+              reinterpret_cast<lds_c *>(a0) + (2 * h - (h >= 2 ? 4 : 0)) * 2048 * 8);
+          const f32x2 t1 = *reinterpret_cast<lds_f2 *>(
+              reinterpret_cast<lds_c *>(a1) + (2 * h + 1 - (h >= 2 ? 4 : 0)) * 2048 * 8);
+          if (h == 0) {
+            acc = make_float2(t0.x, t0.y);  // 0 + t, without the addition
           } else {
-            acc.x += t.x;
-            acc.y += t.y;
+            acc.x += t0.x;
+            acc.y += t0.y;
+          }
+          acc.x += t1.x;
+          acc.y += t1.y;
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          if (i < depth_used) {
+            int k = code_of<PK>(cur[u], i);
+            if (KC) k &= KC - 1;
+            else k = clamp_code(k, K);
+            const f32x2 t = tab[i * K + k];
+            if (DU && i == 0) {
+              acc = make_float2(t.x, t.y);  // 0 + t, without the addition
+            } else {
+              acc.x += t.x;
+              acc.y += t.y;
+            }
           }
         }
       }
       float sd = cur_sd[u];
-      if constexpr (SDT == RVQ_F16) sd = rvq_f16_bits_to_f32((uint16_t)__float_as_uint(sd));
+      if constexpr (GS >= 0 && SDT == RVQ_F16) sd = rvq_f16_bits_to_f32((uint16_t)__float_as_uint(sd));
       acc.x = scale_by_std(acc.x, sd);
       acc.y = scale_by_std(acc.y, sd);
       // pair exchange: the even lane ends up with channel 2a of groups (g, g + 1), the odd lane
@@ -408,7 +438,11 @@ __global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
         if (valid && rp.cs) rope_pair(rp, n0 + nl, chan + (g & ~1), lo, hi);
       }
       if (valid) {
-        out_t *o = out0 + ((int64_t)nl * ldo + chan + (g & ~1));
+        // 32-bit byte offset within the trip's rows (the launcher checks that they fit)
+        const uint32_t boff =
+            ((uint32_t)nl * (uint32_t)ldo + (uint32_t)(chan + (g & ~1))) * (uint32_t)sizeof(out_t);
+        out_t *o = GS >= 0 ? reinterpret_cast<out_t *>(reinterpret_cast<char *>(out0) + boff)
+                           : out0 + ((int64_t)nl * ldo + chan + (g & ~1));
         if (OUT_F16) {
           const uint32_t pk = (uint32_t)__half_as_ushort(__float2half_rn(lo)) |
                               ((uint32_t)__half_as_ushort(__float2half_rn(hi)) << 16);
@@ -420,14 +454,17 @@ __global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
       }
     }
   };
-  for (; c < trips; c += step) {
-    load_trip(c + step, nxt, nxt_sd);
-    do_trip();
-#pragma unroll
-    for (int u = 0; u < SPL_UNROLL; ++u) {
-      cur[u] = nxt[u];
-      cur_sd[u] = nxt_sd[u];
-    }
+  i32x4 bufA[SPL_UNROLL], bufB[SPL_UNROLL];
+  float sdA[SPL_UNROLL], sdB[SPL_UNROLL];
+  load_trip(c, bufA, sdA);
+  while (c < trips) {
+    load_trip(c + step, bufB, sdB);
+    do_trip(bufA, sdA);
+    c += step;
+    if (c >= trips) break;
+    load_trip(c + step, bufA, sdA);
+    do_trip(bufB, sdB);
+    c += step;
   }
 }
 
@@ -452,7 +489,8 @@ hipError_t rvq_launch_decode(const rvq_ctx *ctx, const void *dCodes, int packed,
   // enough rows to pay for filling 256 tables
   const size_t tab_bytes = (size_t)c.depth * c.K * 8;
   if (ctx->Csplit && strided && c.dhat == 32 && fast_codes && pk != 12 && (G % 2) == 0 &&
-      tab_bytes <= RVQ_SPLIT_MAX_LDS && (ldo * osz) % 8 == 0 && N * (int64_t)G >= (1 << 19)) {
+      tab_bytes <= RVQ_SPLIT_MAX_LDS && (ldo * osz) % 8 == 0 && N * (int64_t)G >= (1 << 19) &&
+      ldo < (1 << 20)) {  // offsets within a trip's rows are 32-bit
     int g_shift = -1;
     if ((G & (G - 1)) == 0 && G <= SPL_THREADS * SPL_UNROLL) { g_shift = 0; while ((1 << g_shift) < G) ++g_shift; }
     if (g_shift < 0 && N > 0x7fffffffLL) return hipErrorInvalidValue;
