@@ -66,7 +66,7 @@ int rvq_create(rvq_ctx **out, const rvq_config *cfg) {
   ctx->stats = nullptr;
   ctx->groupA = nullptr;
   ctx->perm = nullptr;
-  ctx->prep_tmp = nullptr;
+  ctx->rowmax = nullptr;
   ctx->dup = nullptr;
   ctx->perm16 = nullptr;
   ctx->counters = nullptr;
@@ -92,7 +92,7 @@ int rvq_create(rvq_ctx **out, const rvq_config *cfg) {
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->groupA, (size_t)cfg->depth * (ctx->Kpad / 16) * sizeof(float) + 64);  // + slack: read in 16-byte pieces
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->perm, (size_t)cfg->depth * ctx->Kpad * sizeof(int32_t));
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->perm16, (size_t)cfg->depth * ctx->Kpad * sizeof(uint16_t));
-    if (e == hipSuccess) e = hipMalloc((void **)&ctx->prep_tmp, (size_t)cfg->depth * ctx->Kpad * 2 * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->rowmax, (size_t)cfg->depth * cfg->K * sizeof(float));
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->counters, 16 * sizeof(unsigned long long));
     if (e == hipSuccess) e = hipMemset(ctx->counters, 0, 16 * sizeof(unsigned long long));
     // channel-split copy for the LDS decode path, when one channel pair of all stages fits LDS
@@ -107,7 +107,7 @@ int rvq_create(rvq_ctx **out, const rvq_config *cfg) {
     if (ctx->stats) (void)hipFree(ctx->stats);
     if (ctx->groupA) (void)hipFree(ctx->groupA);
     if (ctx->perm) (void)hipFree(ctx->perm);
-    if (ctx->prep_tmp) (void)hipFree(ctx->prep_tmp);
+    if (ctx->rowmax) (void)hipFree(ctx->rowmax);
     if (ctx->dup) (void)hipFree(ctx->dup);
     if (ctx->perm16) (void)hipFree(ctx->perm16);
     if (ctx->counters) (void)hipFree(ctx->counters);
@@ -130,7 +130,7 @@ int rvq_destroy(rvq_ctx *ctx) {
   if (ctx->stats) (void)hipFree(ctx->stats);
   if (ctx->groupA) (void)hipFree(ctx->groupA);
   if (ctx->perm) (void)hipFree(ctx->perm);
-  if (ctx->prep_tmp) (void)hipFree(ctx->prep_tmp);
+  if (ctx->rowmax) (void)hipFree(ctx->rowmax);
   if (ctx->dup) (void)hipFree(ctx->dup);
   if (ctx->perm16) (void)hipFree(ctx->perm16);
   if (ctx->counters) (void)hipFree(ctx->counters);
