@@ -53,7 +53,7 @@ constexpr int SCR_QCAP = 16;                           // queued (token, group) 
 constexpr size_t SCR_LDS_BYTES = (size_t)SCR_KC * 64 + (size_t)SCR_KC * 4 +
                                  (size_t)(SCR_KC / 16) * 4 + (size_t)SCR_KC * 2 +
                                  (size_t)SCR_TOKENS * SCR_CAND * 2 + (size_t)SCR_TOKENS * 2 +
-                                 (size_t)SCR_WAVES * SCR_QCAP * 72;
+                                 (size_t)SCR_WAVES * SCR_QCAP * 72 + 16 /* team counters */;
 static_assert(SCR_LDS_BYTES <= 160 * 1024, "one workgroup must fit the 160 KiB of LDS");
 constexpr float BIG = 3.0e38f;
 
@@ -333,11 +333,12 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
 
   // asynchronous copy of one chunk of a stage's operands into LDS; every piece is a whole number
   // of 16-byte lanes, a wavefront moves 1 KiB per instruction (lane i lands at base + 16 i)
-  auto stage_to_lds = [&](int st, int cb, int kcc) {
+  // the copy is shared by nw wavefronts, of which this one is number w
+  auto stage_to_lds = [&](int st, int cb, int kcc, int w, int nw) {
     auto dma = [&](const void *gsrc, void *ldst, int bytes) {
       const char *src = reinterpret_cast<const char *>(gsrc);
       char *dstb = reinterpret_cast<char *>(ldst);
-      for (int off = wave * 1024; off < bytes; off += SCR_WAVES * 1024)
+      for (int off = w * 1024; off < bytes; off += nw * 1024)
         if (off + lane * 16 < bytes)
           __builtin_amdgcn_global_load_lds(
               (const __attribute__((address_space(1))) void *)(src + off + lane * 16),
@@ -424,7 +425,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
       // reads, moved by direct global->LDS loads so no registers are tied up
       if (!single_chunk) {
         __syncthreads();
-        stage_to_lds(stage, cbase, kc);
+        stage_to_lds(stage, cbase, kc, wave, SCR_WAVES);
         __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's direct loads have landed
         __syncthreads();
       }
@@ -668,7 +669,6 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
         }
       }
       PHASE_MARK(7);  // resolve: group-wide exact passes
-      PHASE_MARK(8);  // barrier + start of the next stage's copy
 
       if (!single_chunk) {
         // ---- resolve, step 2 (global): exact fp32 score of every candidate of the chunk,
@@ -840,21 +840,57 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
 
   convert(a.stage_begin);
   const int nst = a.stage_end - a.stage_begin;
+  // The teams do not meet at workgroup barriers between stages: they count in LDS.
+  //   lds_f[t]: wavefronts of team t that have finished phase L (all reads of the operands in
+  //             LDS) of a stage, summed over the stages;
+  //   lds_f[2]: team-0 wavefronts whose share of a stage's operand copy has landed.
+  // Team 0, which needs the next stage's operands first, copies them as soon as both teams have
+  // left phase L of the current stage, while team 1 is already in its phase T; team 1 only checks
+  // that the copy is complete before its own phase L.  Every wavefront of the workgroup runs all
+  // stages (tokens beyond the end are padding), so every count is reached.
+  unsigned *lds_f = reinterpret_cast<unsigned *>(reinterpret_cast<char *>(smem) + SCR_LDS_BYTES - 16);
+  typedef __attribute__((address_space(3))) unsigned lds_u32;
+  auto spin_ge = [&](int idx, unsigned target) {
+    volatile lds_u32 *f = (volatile lds_u32 *)(lds_f + idx);
+    while (*f < target) __builtin_amdgcn_s_sleep(2);
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  };
+  auto signal = [&](int idx) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    if (lane == 0)
+      __hip_atomic_fetch_add((lds_u32 *)(lds_f + idx), 1u, __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_WORKGROUP);
+  };
+  if (single_chunk) {
+    if (tid < 4) lds_f[tid] = 0u;
+    // the first stage's operands: copied by all wavefronts
+    stage_to_lds(a.stage_begin, 0, a.Kpad, wave, SCR_WAVES);
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's direct loads have landed
+    __syncthreads();
+    PHASE_MARK(2);  // staging
+  }
   for (int hs = 0; hs <= 2 * nst; ++hs) {
     const int i = hs >> 1;
     const bool even = (hs & 1) == 0;
-    if (even && i < nst && single_chunk) {
-      // every wavefront has finished reading the previous stage's operands (team 1 just now)
-      __syncthreads();
-      stage_to_lds(a.stage_begin + i, 0, a.Kpad);
-      __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's direct loads have landed
-      __syncthreads();
-      PHASE_MARK(2);  // staging + barriers
-    }
     // one call site per phase: the two teams differ only in which half-step runs which
     const bool do_lds = team == 0 ? (even && i < nst) : !even;
     const bool do_tail = team == 0 ? !even : (even && i >= 1);
-    if (do_lds) lds_phase(a.stage_begin + i);
+    if (do_lds) {
+      if (single_chunk && i > 0) {
+        if (team == 0) {
+          spin_ge(0, 4u * i);
+          spin_ge(1, 4u * i);
+          PHASE_MARK(8);  // waiting for the end of the previous stage's phase L
+          stage_to_lds(a.stage_begin + i, 0, a.Kpad, wave, SCR_WAVES / 2);
+          __builtin_amdgcn_s_waitcnt(0x0f70);
+          signal(2);
+        }
+        spin_ge(2, 4u * i);
+        PHASE_MARK(2);  // staging
+      }
+      lds_phase(a.stage_begin + i);
+      if (single_chunk) signal(team);
+    }
     if (do_tail) tail_phase(a.stage_begin + (team == 0 ? i : i - 1));
   }
 

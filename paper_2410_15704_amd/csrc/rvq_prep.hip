@@ -94,7 +94,10 @@ __global__ __launch_bounds__(256) void dup_kernel(const float *__restrict__ C,
     if (n[j] != nk) continue;  // equal rows have equal norms
     bool same = true;
     for (int e = 0; e < 32; ++e) same = same && Cs[(int64_t)j * 32 + e] == Cs[(int64_t)k * 32 + e];
-    found |= same ? 1 : 0;
+    if (same) {  // one earlier repeat is enough (many equal rows, e.g. dead codes at 0, stay cheap)
+      found = 1;
+      break;
+    }
   }
   found = __syncthreads_or(found);
   if (threadIdx.x == 0) dup[(int64_t)stage * K + k] = found ? 1 : 0;
