@@ -54,6 +54,17 @@ __device__ __forceinline__ i32x4 load_codes8(const void *codes, int64_t e) {
     return w;
   }
 }
+// code i (0..7) of a packed record given as three 32-bit words (bits 0..31, 32..63, 64..)
+template <int PK>
+__device__ __forceinline__ int code_from_words(const uint32_t W0, const uint32_t W1,
+                                               const uint32_t W2, int i) {
+  const uint32_t W[3] = {W0, W1, W2};
+  const int word = (PK * i) >> 5, sh = (PK * i) & 31;
+  uint32_t v;
+  if (sh + PK <= 32) v = W[word] >> sh;  // a code lies in one word
+  else v = __builtin_amdgcn_alignbit(W[word + 1], W[word], sh);  // or straddles two
+  return (int)(v & ((1u << PK) - 1u));
+}
 // code i (0..7) of what load_codes8 returned; int16 codes come back sign-extended
 template <int PK>
 __device__ __forceinline__ int code_of(const i32x4 w, int i) {
@@ -61,14 +72,9 @@ __device__ __forceinline__ int code_of(const i32x4 w, int i) {
     const int v = i < 2 ? w.x : (i < 4 ? w.y : (i < 6 ? w.z : w.w));
     return (i & 1) ? (v >> 16) : (int)(int16_t)(v & 0xffff);
   } else {
-    // the record as three 32-bit words: bits 0..63 are the first load, bits 64.. the tail of the
-    // second (which starts at byte PK - 8); a code lies in one word or straddles two
-    const uint32_t W[3] = {(uint32_t)w.x, (uint32_t)w.y, (uint32_t)w.w >> (8 * (12 - PK))};
-    const int word = (PK * i) >> 5, sh = (PK * i) & 31;
-    uint32_t v;
-    if (sh + PK <= 32) v = W[word] >> sh;
-    else v = __builtin_amdgcn_alignbit(W[word + 1], W[word], sh);
-    return (int)(v & ((1u << PK) - 1u));
+    // bits 0..63 are the first load, bits 64.. the tail of the second (which starts at byte
+    // PK - 8)
+    return code_from_words<PK>((uint32_t)w.x, (uint32_t)w.y, (uint32_t)w.w >> (8 * (12 - PK)), i);
   }
 }
 
@@ -332,14 +338,29 @@ __global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
   // Loads carry no bounds branch: a pair index beyond the end is clamped to the last pair (V >= 1
   // on this path), whose data is fetched and never stored.
   constexpr int REC = PK ? PK : 16;  // bytes of one pair's codes (this kernel is for depth 8)
-  auto load_trip = [&](int64_t c, i32x4 *dst, float *dst_sd) {
+  auto load_trip = [&](int64_t c, i32x4 *dst, float *dst_sd, int *dst_sb) {
     const int64_t e0 = min(c, trips - 1) * TRIP;
     const uint32_t last = (uint32_t)min((int64_t)TRIP, V - e0) - 1u;
+    const uint32_t win_last = (last + 1u) * REC - 16u;  // start of the trip's last 16-byte window
 #pragma unroll
     for (int u = 0; u < SPL_UNROLL; ++u) {
       const uint32_t q = min((uint32_t)(u * SPL_THREADS + tid), last);
       // plain loads: the other 15 channel-pair workgroups of this XCD find the line in its L2
-      dst[u] = load_codes8<PK, false>(reinterpret_cast<const char *>(codes) + e0 * REC, q);
+      if constexpr (PK == 0) {
+        dst[u] = load_codes8<PK, false>(reinterpret_cast<const char *>(codes) + e0 * REC, q);
+      } else {
+        // a packed record lies inside the 16 bytes that start at the 4-byte boundary below it
+        // (the launcher checks that the buffer is a whole number of 32-bit words); one aligned
+        // load fetches that window, moved back where it would pass the end of the buffer, and
+        // the record's place in it (0..5 bytes) is kept beside it
+        const uint32_t boff = q * PK;
+        const uint32_t start = min(boff & ~3u, win_last);
+        typedef int i32x4a4 __attribute__((ext_vector_type(4), aligned(4)));
+        const i32x4a4 w = *reinterpret_cast<const i32x4a4 *>(
+            reinterpret_cast<const char *>(codes) + e0 * REC + start);
+        dst[u] = w;
+        dst_sb[u] = (int)(boff - start);
+      }
       if constexpr (GS >= 0 && SDT == RVQ_F16) {
         // the raw bits travel; they are widened where they are used, a trip later
         const uint16_t *sb = reinterpret_cast<const uint16_t *>(std_in) + (e0 >> GS);
@@ -354,7 +375,7 @@ __global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
   };
   const int64_t step = 8 * (int64_t)parts;
   int64_t c = xcd + 8 * (int64_t)part;
-  auto do_trip = [&](const i32x4 *cur, const float *cur_sd) {
+  auto do_trip = [&](const i32x4 *cur, const float *cur_sd, const int *cur_sb) {
     const int64_t e0 = c * TRIP;
     const int left = (int)min((int64_t)TRIP, V - e0);
     int64_t n0 = 0;
@@ -404,10 +425,21 @@ __global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
           acc.y += t1.y;
         }
       } else {
+        uint32_t W0 = 0, W1 = 0, W2 = 0;  // a packed record as three words
+        if constexpr (PK != 0) {
+          uint32_t w0 = (uint32_t)cur[u].x, w1 = (uint32_t)cur[u].y, w2 = (uint32_t)cur[u].z;
+          const uint32_t w3 = (uint32_t)cur[u].w;
+          const int sb = cur_sb[u];
+          if (sb >= 4) { w0 = w1; w1 = w2; w2 = w3; }
+          const int sh = (sb & 3) * 8;
+          W0 = __builtin_amdgcn_alignbit(w1, w0, sh);
+          W1 = __builtin_amdgcn_alignbit(w2, w1, sh);
+          W2 = __builtin_amdgcn_alignbit(w3, w2, sh);  // its upper bits are not part of any code
+        }
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           if (i < depth_used) {
-            int k = code_of<PK>(cur[u], i);
+            int k = PK ? code_from_words<PK ? PK : 11>(W0, W1, W2, i) : code_of<PK>(cur[u], i);
             if (KC) k &= KC - 1;
             else k = clamp_code(k, K);
             const f32x2 t = tab[i * K + k];
@@ -456,14 +488,15 @@ __global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
   };
   i32x4 bufA[SPL_UNROLL], bufB[SPL_UNROLL];
   float sdA[SPL_UNROLL], sdB[SPL_UNROLL];
-  load_trip(c, bufA, sdA);
+  int sbA[SPL_UNROLL], sbB[SPL_UNROLL];  // packed records only
+  load_trip(c, bufA, sdA, sbA);
   while (c < trips) {
-    load_trip(c + step, bufB, sdB);
-    do_trip(bufA, sdA);
+    load_trip(c + step, bufB, sdB, sbB);
+    do_trip(bufA, sdA, sbA);
     c += step;
     if (c >= trips) break;
-    load_trip(c + step, bufA, sdA);
-    do_trip(bufB, sdB);
+    load_trip(c + step, bufA, sdA, sbA);
+    do_trip(bufB, sdB, sbB);
     c += step;
   }
 }
@@ -490,7 +523,8 @@ hipError_t rvq_launch_decode(const rvq_ctx *ctx, const void *dCodes, int packed,
   const size_t tab_bytes = (size_t)c.depth * c.K * 8;
   if (ctx->Csplit && strided && c.dhat == 32 && fast_codes && pk != 12 && (G % 2) == 0 &&
       tab_bytes <= RVQ_SPLIT_MAX_LDS && (ldo * osz) % 8 == 0 && N * (int64_t)G >= (1 << 19) &&
-      ldo < (1 << 20)) {  // offsets within a trip's rows are 32-bit
+      ldo < (1 << 20) &&  // offsets within a trip's rows are 32-bit
+      (pk == 0 || (G % 4) == 0)) {  // packed: the buffer is a whole number of 32-bit words
     int g_shift = -1;
     if ((G & (G - 1)) == 0 && G <= SPL_THREADS * SPL_UNROLL) { g_shift = 0; while ((1 << g_shift) < G) ++g_shift; }
     if (g_shift < 0 && N > 0x7fffffffLL) return hipErrorInvalidValue;

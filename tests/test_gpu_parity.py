@@ -346,8 +346,8 @@ def test_encode_llama_key_full_size_sampled_oracle(gpu_device):
 
 
 def test_encode_long_context_shape_reduced_rows(gpu_device):
-    """Workload 5's shape (d=4096, G=128, K=4096, fp16, strided) on 2048 rows (the full
-    131072-row input is exercised by the benchmark driver, not here); oracle on 64 rows."""
+    """Workload 5's shape (d=4096, G=128, K=4096, fp16, strided) on its first 2048 rows (rows are
+    independent, so fewer rows change nothing per row); oracle on 64 rows."""
     Xh, _ = synth.heavy_tailed_keys(rows=slice(0, 2048))
     C = _codebooks_from_samples(synth.widen(Xh[:256], "fp16"), 32, oracle.STRIDED, 8, 4096, seed=5)
     rows = np.sort(np.random.Generator(np.random.PCG64(55)).choice(2048, 64, replace=False))
@@ -592,7 +592,12 @@ def test_decode_packed_slice_matches_decode(gpu_device):
         a = q.decode(codes, std)
         p = q.decode_packed(packed, std)
         assert torch.equal(a, p)
-        del a, p
+        # a ragged token count: the last trip of the LDS kernel is partial, and the last record's
+        # 16-byte window is moved back to end with the buffer
+        Tr = 100003
+        pr = q.decode_packed(packed[:Tr].contiguous(), std[:Tr].contiguous())
+        assert torch.equal(a[:Tr], pr)
+        del a, p, pr
         q.close()
     check_decode(None, None, "fp16", C, d, 32, oracle.STRIDED, sample_rows=rows,
                  dev_codes=q_unpack_roundtrip(b, torch, codes, packed, K, depth, G, d), dev_std=std)
