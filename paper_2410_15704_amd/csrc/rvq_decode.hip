@@ -87,16 +87,27 @@ struct RopeArgs {
   const float *cs;  // nullptr: no rotation
   const float *sn;
   int hd;
+  int hmask;  // hd - 1 when hd is a power of two (the channel within the head is then a mask), else 0
 };
-__device__ __forceinline__ void rope_pair(const RopeArgs &rp, int64_t n, int c_even, float &x0,
-                                          float &x1) {
-  const int i = (c_even % rp.hd) >> 1;
-  const int64_t t = n * (rp.hd >> 1) + i;
-  const float co = rp.cs[t], si = rp.sn[t];
+// cos and sin of the pair that starts at channel c_even of token n
+__device__ __forceinline__ void rope_load(const RopeArgs &rp, int64_t n, int c_even, float &co,
+                                          float &si) {
+  const int ch = rp.hmask ? (c_even & rp.hmask) : (c_even % rp.hd);
+  const int64_t t = n * (rp.hd >> 1) + (ch >> 1);
+  co = rp.cs[t];
+  si = rp.sn[t];
+}
+__device__ __forceinline__ void rope_apply(float co, float si, float &x0, float &x1) {
   const float y0 = x0 * co - x1 * si;
   const float y1 = x0 * si + x1 * co;
   x0 = y0;
   x1 = y1;
+}
+__device__ __forceinline__ void rope_pair(const RopeArgs &rp, int64_t n, int c_even, float &x0,
+                                          float &x1) {
+  float co, si;
+  rope_load(rp, n, c_even, co, si);
+  rope_apply(co, si, x0, x1);
 }
 
 // ---- generic kernel: one thread per output channel, any dhat ------------------------------
@@ -176,12 +187,17 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
     for (int g0 = 0; g0 < G; g0 += 8) {
       const int g = g0 + p;
       float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+      float rco[2] = {1.f, 1.f}, rsi[2] = {0.f, 0.f};
       if (g < G) {
         const int16_t *cg = reinterpret_cast<const int16_t *>(codes_v) + (n * G + g) * depth;
         if (DEPTH8) {
           // codes and outputs are streamed once: non-temporal accesses keep them from evicting
           // the codebook rows, which every wavefront gathers again and again, from L2
           const i32x4 w = load_codes8<PK, false>(codes_v, n * G + g);
+          if (ROPE && !STRIDED) {  // fetched now, used after the gathers
+            rope_load(rp, n, g * 32 + q * 4, rco[0], rsi[0]);
+            rope_load(rp, n, g * 32 + q * 4 + 2, rco[1], rsi[1]);
+          }
 #pragma unroll
           for (int i = 0; i < 8; ++i) {
             if (i < depth_used) {
@@ -203,8 +219,13 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
         acc.z = scale_by_std(acc.z, sd); acc.w = scale_by_std(acc.w, sd);
         if (!STRIDED) {
           if (ROPE) {  // channels g * 32 + 4 q .. + 3: two pairs, both in this lane
-            rope_pair(rp, n, g * 32 + q * 4, acc.x, acc.y);
-            rope_pair(rp, n, g * 32 + q * 4 + 2, acc.z, acc.w);
+            if (DEPTH8) {
+              rope_apply(rco[0], rsi[0], acc.x, acc.y);
+              rope_apply(rco[1], rsi[1], acc.z, acc.w);
+            } else {
+              rope_pair(rp, n, g * 32 + q * 4, acc.x, acc.y);
+              rope_pair(rp, n, g * 32 + q * 4 + 2, acc.z, acc.w);
+            }
           }
           out_t *o = reinterpret_cast<out_t *>(out) + n * ldo + (int64_t)g * 32 + q * 4;
           if (OUT_F16) {
@@ -381,6 +402,14 @@ __global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
     int64_t n0 = 0;
     if constexpr (GS >= 0) n0 = e0 >> GS;  // TRIP is a multiple of G: a trip starts at a token boundary
     out_t *out0 = reinterpret_cast<out_t *>(out) + n0 * ldo;
+    float rco[SPL_UNROLL], rsi[SPL_UNROLL];
+    if constexpr (ROPE == 1 && GS >= 0) {  // fetched now, used after the gathers
+#pragma unroll
+      for (int u = 0; u < SPL_UNROLL; ++u) {
+        const int q = min(u * SPL_THREADS + tid, left - 1);
+        rope_load(rp, n0 + (q >> GS), chan + (q & ((1 << GS) - 1) & ~1), rco[u], rsi[u]);
+      }
+    }
 #pragma unroll
     for (int u = 0; u < SPL_UNROLL; ++u) {
       const int q = u * SPL_THREADS + tid;
@@ -464,7 +493,9 @@ __global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
           __float_as_int(give), 0xB1 /* quad_perm [1,0,3,2] */, 0xf, 0xf, true));
       float lo = odd ? got : acc.x;
       float hi = odd ? acc.y : got;
-      if constexpr (ROPE == 1) {
+      if constexpr (ROPE == 1 && GS >= 0) {
+        rope_apply(rco[u], rsi[u], lo, hi);
+      } else if constexpr (ROPE == 1) {
         if (valid) rope_pair(rp, n0 + nl, chan + (g & ~1), lo, hi);
       } else if constexpr (ROPE == -1) {
         if (valid && rp.cs) rope_pair(rp, n0 + nl, chan + (g & ~1), lo, hi);
@@ -507,7 +538,8 @@ hipError_t rvq_launch_decode(const rvq_ctx *ctx, const void *dCodes, int packed,
                              int64_t N, int depth_used, void *dOut, int64_t ldo, const float *dCos,
                              const float *dSin, int head_dim, hipStream_t s) {
   const rvq_config &c = ctx->cfg;
-  const RopeArgs rp = {dCos, dSin, head_dim > 0 ? head_dim : 2};
+  const int hd = head_dim > 0 ? head_dim : 2;
+  const RopeArgs rp = {dCos, dSin, hd, (hd & (hd - 1)) == 0 ? hd - 1 : 0};
   const bool rope = dCos != nullptr;
   const bool f16 = c.out_dtype == RVQ_F16;
   const int G = ctx->G;
