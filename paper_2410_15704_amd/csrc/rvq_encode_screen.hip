@@ -75,8 +75,33 @@ struct ScreenArgs {
   float kappa;
 };
 
-__device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, 64); }
-__device__ __forceinline__ int xor32i(int v) { return __shfl_xor(v, 32, 64); }
+// Exchange between the two lanes (l, l + 32) that share a token.  v_permlane32_swap trades the
+// upper half of one register for the lower half of another inside the vector unit; swapping a
+// value with itself leaves the value of lane half 0 in every lane of one result and that of lane
+// half 1 in the other (an LDS permute would cost an LDS round trip each time).
+__device__ __forceinline__ void halves32(unsigned v, unsigned &h0, unsigned &h1) {
+  const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+  h0 = r[0];
+  h1 = r[1];
+}
+__device__ __forceinline__ int xor32i(int v) {
+  unsigned h0, h1;
+  halves32((unsigned)v, h0, h1);
+  return (int)((threadIdx.x & 32) ? h0 : h1);
+}
+__device__ __forceinline__ float xor32(float v) { return __int_as_float(xor32i(__float_as_int(v))); }
+__device__ __forceinline__ void halves32f(float v, float &h0, float &h1) {
+  unsigned u0, u1;
+  halves32(__float_as_uint(v), u0, u1);
+  h0 = __uint_as_float(u0);
+  h1 = __uint_as_float(u1);
+}
+// v of this lane + v of its partner, the same bits in both
+__device__ __forceinline__ float sum32(float v) {
+  unsigned h0, h1;
+  halves32(__float_as_uint(v), h0, h1);
+  return __uint_as_float(h0) + __uint_as_float(h1);
+}
 
 __device__ __forceinline__ float min3f(float a, float b, float c) {
   return __builtin_fminf(__builtin_fminf(a, b), c);  // one v_min3_f32
@@ -397,8 +422,8 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
         s_q = fmaf(xr, xr, s_q);
         s_d = fmaf(dx, dx, s_d);
       }
-      s_q += xor32(s_q);
-      s_d += xor32(s_d);
+      s_q = sum32(s_q);
+      s_d = sum32(s_d);
       const float nq = sqrtf(s_q) * 1.000001f;
       const float nd = sqrtf(s_d) * 1.000001f;
       g1[tt] = (nd + (rho + a.kappa * (1.0f + rho)) * nq) * 1.000001f;
@@ -461,38 +486,40 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
       // ---- resolve, step 1 (LDS only): the candidate codewords of every token of the chunk.
       //
       // fp16 re-score of the 16 rows of group (tl, hh) for the token whose fp16 residual halves
-      // the lane pair holds in (Bx0, Bx1): every lane forms the partial dot product of its 16
-      // channels with two rows per step, one that it finishes itself (rows 8 h .. 8 h + 7 of
-      // the group) and one that its partner lane finishes.  A row survives when its score minus
-      // the group's error bound is within the token's window: score <= tadj = thr + g1 A_g
-      // (the second-order part of the bound is already inside the stored norms).  Returns the
-      // survivors of the pair as a 16-bit row mask, the same in both lanes.
+      // the lane pair holds in (Bx0, Bx1).  A row survives when its score minus the group's error
+      // bound is within the token's window: score <= tadj = thr + g1 A_g (the second-order part
+      // of the bound is already inside the stored norms).  Returns the survivors of the pair as
+      // a 16-bit row mask, the same in both lanes.
       auto rescore = [&](int tl, int hh, const half8 &Bx0, const half8 &Bx1, float tadj,
                          bool act) -> unsigned {
         const uint2 *rows = reinterpret_cast<const uint2 *>(lds_A) + tl * 256 + h * 32;
         const int swz = tl & 31;  // row m of tile tl is stored in slot m ^ swz
-        const float *nrow = lds_n + (tl * 2 + hh) * 16 + 8 * h;
-        // all reads of one quarter of the rows are issued before their dot products, and the
-        // eight partner partials are exchanged together: few dependent LDS round trips
-        float pm[8], ps[8];
+        // Both lanes of the pair take the partial dot products (over their half of the channels)
+        // of all 16 rows: px of the group's rows in the lower half of the tile, py of those in
+        // the upper half.  One half-swap per row pair then leaves, added up, the full product of
+        // an upper row in lane half 0 and of a lower row in lane half 1.
+        const float *nrow = lds_n + (tl * 2 + hh) * 16 + 8 * (1 - h);
+        // all reads of one quarter of the rows are issued before their dot products: few
+        // dependent LDS round trips
+        float px[8], py[8];
 #pragma unroll
-        for (int qt = 0; qt < 4; ++qt) {  // two group rows per lane role and step
-          uint4 xm0[2], xm1[2], xs0[2], xs1[2];
+        for (int qt = 0; qt < 4; ++qt) {  // two rows of either half per step
+          uint4 xa0[2], xa1[2], xb0[2], xb1[2];
 #pragma unroll
           for (int q = 0; q < 2; ++q) {
             const int u = 2 * qt + q;
             const int mo = 8 * (u >> 2) + (u & 3);  // tile row of group row u, within 16 rows
-            const uint2 *rm = rows + ((16 * h + 4 * hh + mo) ^ swz);
-            const uint2 *rs = rows + ((16 * (1 - h) + 4 * hh + mo) ^ swz);
-            xm0[q] = make_uint4(rm[0].x, rm[0].y, rm[64].x, rm[64].y);
-            xm1[q] = make_uint4(rm[128].x, rm[128].y, rm[192].x, rm[192].y);
-            xs0[q] = make_uint4(rs[0].x, rs[0].y, rs[64].x, rs[64].y);
-            xs1[q] = make_uint4(rs[128].x, rs[128].y, rs[192].x, rs[192].y);
+            const uint2 *ra = rows + ((4 * hh + mo) ^ swz);
+            const uint2 *rb = rows + ((16 + 4 * hh + mo) ^ swz);
+            xa0[q] = make_uint4(ra[0].x, ra[0].y, ra[64].x, ra[64].y);
+            xa1[q] = make_uint4(ra[128].x, ra[128].y, ra[192].x, ra[192].y);
+            xb0[q] = make_uint4(rb[0].x, rb[0].y, rb[64].x, rb[64].y);
+            xb1[q] = make_uint4(rb[128].x, rb[128].y, rb[192].x, rb[192].y);
           }
 #pragma unroll
           for (int q = 0; q < 2; ++q) {
-            pm[2 * qt + q] = dot8(xm1[q], Bx1, dot8(xm0[q], Bx0, 0.f));
-            ps[2 * qt + q] = dot8(xs1[q], Bx1, dot8(xs0[q], Bx0, 0.f));
+            px[2 * qt + q] = dot8(xa1[q], Bx1, dot8(xa0[q], Bx0, 0.f));
+            py[2 * qt + q] = dot8(xb1[q], Bx1, dot8(xb0[q], Bx0, 0.f));
           }
         }
         const f32x4 nlo = *reinterpret_cast<const f32x4 *>(nrow);
@@ -500,12 +527,16 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
         unsigned mask = 0;
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-          const float sc = (pm[u] + xor32(ps[u])) + (u < 4 ? nlo[u & 3] : nhi[u & 3]);
+          const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(py[u]),
+                                                          __float_as_uint(px[u]), false, false);
+          const float sc = (__uint_as_float(r[0]) + __uint_as_float(r[1])) + (u < 4 ? nlo[u & 3] : nhi[u & 3]);
           mask |= (sc <= tadj ? 1u : 0u) << u;
         }
-        mask = act ? mask << (8 * h) : 0u;
+        mask = act ? mask << (8 * (1 - h)) : 0u;  // bits 0..7: lower rows, 8..15: upper rows
         n_groups += __popcll(__ballot(act && h == 0));
-        return mask | (unsigned)xor32i((int)mask);
+        unsigned k0, k1;
+        halves32(mask, k0, k1);
+        return k0 | k1;
       };
       // append the surviving rows of group (tl, hh), as codeword indices, to the candidate list
       // of token slot `tok` of this wavefront; a count beyond the list marks the token for the
@@ -536,16 +567,20 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
       struct Window { float thr, e0, e1, e2, e3; unsigned pend; bool afirst; };
       auto window = [&]() -> Window {
         Window w;
-        const float o1 = xor32(m1[0]), o2 = xor32(m2[0]), o3 = xor32(m3[0]);
+        // a = the tracked groups of lane half 0, b = those of lane half 1, the same in both lanes
+        float a1, b1, a2, b2, a3, b3;
+        halves32f(m1[0], a1, b1);
+        halves32f(m2[0], a2, b2);
+        halves32f(m3[0], a3, b3);
         {
           const float A1 = lds_g[tile_of(m1[0]) * 2 + h];
           const float mine = m1[0] + 2.5f * (g1[0] * A1 + k4 * A1 * A1 + g0[0]);
-          w.thr = fminf(mine, xor32(mine));
+          float t0, t1;
+          halves32f(mine, t0, t1);
+          w.thr = fminf(t0, t1);
         }
         // a third group of one lane inside the window: more groups than are tracked
-        if (m3[0] <= w.thr || o3 <= w.thr) slow[0] = 1;
-        const float a1 = h ? o1 : m1[0], a2 = h ? o2 : m2[0];
-        const float b1 = h ? m1[0] : o1, b2 = h ? m2[0] : o2;
+        if (a3 <= w.thr || b3 <= w.thr) slow[0] = 1;
         w.afirst = a1 <= b1;
         w.e0 = w.afirst ? a1 : b1; w.e1 = w.afirst ? b1 : a1;
         w.e2 = w.afirst ? a2 : b2; w.e3 = w.afirst ? b2 : a2;
@@ -706,7 +741,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
               dist = fmaf(dlt, dlt, dist);
               r[tt][j] = fmaf(-sel, c, r[tt][j]);  // exact: sel is 0 or 1
             }
-            dist += xor32(dist);
+            dist = sum32(dist);
             n_exact += __popcll(__ballot(valid && h == 0));
             if (valid && (dist < bestd[tt] || (dist == bestd[tt] && kk[tt] < bestk[tt]))) {
               bestd[tt] = dist;
@@ -761,7 +796,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
             dist = fmaf(dlt, dlt, dist);
             r[tt][j] = fmaf(-sel, c, r[tt][j]);  // exact: sel is 0 or 1
           }
-          dist += xor32(dist);
+          dist = sum32(dist);
           n_exact += __popcll(__ballot(valid && h == 0));
           if (valid && (dist < bestd[tt] || (dist == bestd[tt] && kk[tt] < bestk[tt]))) {
             bestd[tt] = dist;
