@@ -178,17 +178,26 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
   const int d = G * 32;
   using out_t = typename std::conditional<OUT_F16, uint16_t, float>::type;
   using stage_t = typename std::conditional<ROPE, float, out_t>::type;
-  stage_t *stage = reinterpret_cast<stage_t *>(smem) + (size_t)wave * lds_row * 32;
+  // A pass of the wavefront covers eight (token, group) pairs: eight groups of one token, or,
+  // when a token has fewer (G = 1, 2, 4: e.g. one 128-channel head per row), all groups of
+  // tpp = 8 / G tokens.
+  const int tpp = (G < 8 && (8 % G) == 0) ? 8 / G : 1;
+  const int gsh = (G & (G - 1)) == 0 ? __ffs(G) - 1 : -1;  // log2 G when G is a power of two
+  const int ts = tpp > 1 ? p >> gsh : 0;  // this lane's token within the pass
+  stage_t *stage_w = reinterpret_cast<stage_t *>(smem) + (size_t)wave * lds_row * 32 * tpp;
+  stage_t *stage = stage_w + (size_t)ts * lds_row * 32;
 
   const int64_t wave_global = (int64_t)blockIdx.x * DEC_WAVES + wave;
   const int64_t wave_count = (int64_t)gridDim.x * DEC_WAVES;
-  for (int64_t n = wave_global; n < N; n += wave_count) {
+  for (int64_t nb = wave_global * tpp; nb < N; nb += wave_count * tpp) {
+    const int64_t n = min(nb + ts, N - 1);
+    const bool tok_ok = nb + ts < N;
     const float sd = load_std(std_in, std_dtype, n);
     for (int g0 = 0; g0 < G; g0 += 8) {
-      const int g = g0 + p;
+      const int g = tpp > 1 ? p - ts * G : g0 + p;
       float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
       float rco[2] = {1.f, 1.f}, rsi[2] = {0.f, 0.f};
-      if (g < G) {
+      if (g < G && tok_ok) {
         const int16_t *cg = reinterpret_cast<const int16_t *>(codes_v) + (n * G + g) * depth;
         if (DEPTH8) {
           // codes and outputs are streamed once: non-temporal accesses keep them from evicting
@@ -256,35 +265,39 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
     if (STRIDED) {
       // the wavefront's own LDS writes are visible to its later reads (same wave, in order)
       __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
-      out_t *o = reinterpret_cast<out_t *>(out) + n * ldo;
-      if (ROPE) {
-        // adjacent channels (c, c + 1) are adjacent groups of one LDS row: rotate, then round
-        for (int c = lane * 2; c < d; c += 128) {
-          const int j = c / G, g = c - j * G;
-          const float *sp = reinterpret_cast<const float *>(&stage[j * lds_row + g]);
-          float x0 = sp[0], x1 = sp[1];
-          rope_pair(rp, n, c, x0, x1);
-          if (OUT_F16) {
-            const uint32_t v = (uint32_t)__half_as_ushort(__float2half_rn(x0)) |
-                               ((uint32_t)__half_as_ushort(__float2half_rn(x1)) << 16);
-            __builtin_nontemporal_store(v, reinterpret_cast<uint32_t *>(o + c));
-          } else {
-            typedef float f32x2r __attribute__((ext_vector_type(2)));
-            const f32x2r v = {x0, x1};
-            __builtin_nontemporal_store(v, reinterpret_cast<f32x2r *>(o + c));
+      for (int t = 0; t < tpp && nb + t < N; ++t) {
+        const int64_t nt = nb + t;
+        const stage_t *st = stage_w + (size_t)t * lds_row * 32;
+        out_t *o = reinterpret_cast<out_t *>(out) + nt * ldo;
+        if (ROPE) {
+          // adjacent channels (c, c + 1) are adjacent groups of one LDS row: rotate, then round
+          for (int c = lane * 2; c < d; c += 128) {
+            const int j = gsh >= 0 ? c >> gsh : c / G, g = c - j * G;
+            const float *sp = reinterpret_cast<const float *>(&st[j * lds_row + g]);
+            float x0 = sp[0], x1 = sp[1];
+            rope_pair(rp, nt, c, x0, x1);
+            if (OUT_F16) {
+              const uint32_t v = (uint32_t)__half_as_ushort(__float2half_rn(x0)) |
+                                 ((uint32_t)__half_as_ushort(__float2half_rn(x1)) << 16);
+              __builtin_nontemporal_store(v, reinterpret_cast<uint32_t *>(o + c));
+            } else {
+              typedef float f32x2r __attribute__((ext_vector_type(2)));
+              const f32x2r v = {x0, x1};
+              __builtin_nontemporal_store(v, reinterpret_cast<f32x2r *>(o + c));
+            }
           }
-        }
-      } else if (OUT_F16) {
-        // two fp16 channels per lane per step (G is even on this path)
-        for (int c = lane * 2; c < d; c += 128) {
-          const int j = c / G, g = c - j * G;
-          const uint32_t v = *reinterpret_cast<const uint32_t *>(&stage[j * lds_row + g]);
-          __builtin_nontemporal_store(v, reinterpret_cast<uint32_t *>(o + c));
-        }
-      } else {
-        for (int c = lane; c < d; c += 64) {
-          const int j = c / G, g = c - j * G;
-          __builtin_nontemporal_store(stage[j * lds_row + g], o + c);
+        } else if (OUT_F16) {
+          // two fp16 channels per lane per step (G is even on this path)
+          for (int c = lane * 2; c < d; c += 128) {
+            const int j = gsh >= 0 ? c >> gsh : c / G, g = c - j * G;
+            const uint32_t v = *reinterpret_cast<const uint32_t *>(&st[j * lds_row + g]);
+            __builtin_nontemporal_store(v, reinterpret_cast<uint32_t *>(o + c));
+          }
+        } else {
+          for (int c = lane; c < d; c += 64) {
+            const int j = gsh >= 0 ? c >> gsh : c / G, g = c - j * G;
+            __builtin_nontemporal_store(st[j * lds_row + g], o + c);
+          }
         }
       }
       __builtin_amdgcn_s_waitcnt(0xc07f);
@@ -553,7 +566,9 @@ hipError_t rvq_launch_decode(const rvq_ctx *ctx, const void *dCodes, int packed,
   // LDS path: strided grouping, depth-8 codes, even G, a channel-pair table that fits LDS, and
   // enough rows to pay for filling 256 tables
   const size_t tab_bytes = (size_t)c.depth * c.K * 8;
-  if (ctx->Csplit && strided && c.dhat == 32 && fast_codes && pk != 12 && (G % 2) == 0 &&
+  // (with fewer than 16 groups a token's piece of a channel pair is under 64 bytes: the row kernel
+  // writes whole rows instead)
+  if (ctx->Csplit && strided && c.dhat == 32 && fast_codes && pk != 12 && (G % 2) == 0 && G >= 16 &&
       tab_bytes <= RVQ_SPLIT_MAX_LDS && (ldo * osz) % 8 == 0 && N * (int64_t)G >= (1 << 19) &&
       ldo < (1 << 20) &&  // offsets within a trip's rows are 32-bit
       (pk == 0 || (G % 4) == 0)) {  // packed: the buffer is a whole number of 32-bit words
@@ -591,12 +606,14 @@ hipError_t rvq_launch_decode(const rvq_ctx *ctx, const void *dCodes, int packed,
   size_t lds_bytes = 0;
   if (strided) {
     lds_row = G + ((f16 || rope) ? 2 : 1);  // the rotation reads pairs: rows of an even length
-    lds_bytes = (size_t)DEC_WAVES * 32 * lds_row * (rope ? 4 : osz);
+    const int tpp = (G < 8 && (8 % G) == 0) ? 8 / G : 1;  // tokens per pass of a wavefront
+    lds_bytes = (size_t)DEC_WAVES * 32 * lds_row * tpp * (rope ? 4 : osz);
   }
   const bool rows_ok = c.dhat == 32 && (ldo * osz) % 16 == 0 && (!packed || pk) && !(rope && pk) &&
                        (!strided || (G % 2 == 0 && lds_bytes <= 64 * 1024));
   if (rows_ok) {
-    int64_t blocks = (N + DEC_WAVES - 1) / DEC_WAVES;
+    const int tpp = (G < 8 && (8 % G) == 0) ? 8 / G : 1;
+    int64_t blocks = ((N + tpp - 1) / tpp + DEC_WAVES - 1) / DEC_WAVES;
     const int64_t cap = 256 * 16;  // enough waves to fill the chip; the kernel strides over rows
     if (blocks > cap) blocks = cap;
     const dim3 grid((unsigned)blocks), block(64 * DEC_WAVES);
