@@ -406,6 +406,9 @@ def test_long_context_shape_mse_per_depth(gpu_device):
     (77, 40, 20, 2, 17, oracle.CONTIGUOUS, "fp32", None),
     (64, 48, 8, 5, 50, oracle.STRIDED, "fp16", 1),
     (5, 64, 32, 6, 9, oracle.STRIDED, None, None),          # no std buffer: std = 1
+    (1001, 128, 32, 8, 2048, oracle.STRIDED, "fp16", None),    # one head per row: two rows per pass,
+    (1001, 128, 32, 8, 2048, oracle.CONTIGUOUS, "fp16", None), # and an odd row count
+    (37, 32, 32, 4, 64, oracle.CONTIGUOUS, "fp32", None),      # one group per row: eight rows per pass
 ])
 def test_decode_small_and_ragged(gpu_device, case):
     N, d, dhat, depth, K, grouping, sdt, used = case
