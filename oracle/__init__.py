@@ -235,7 +235,7 @@ def kmeans_init_codebooks(Z, depth: int, K: int, iters: int, picks):
 
 
 def ema_train(R0, depth: int, K: int, iters: int, decay: float, eps: float, picks,
-              schedule: str = "sequential"):
+              schedule: str = "sequential", batches=None):
     """Codebook learning by exponential moving average (Sections 2.1 and 3: decay 0.99) on a fixed
     set of vectors R0 [M][dhat], with moving-average state N_k = 1, M_k = C_k at the start.
       "sequential": stage by stage: codebook s starts from rows picks[s] of the vectors entering
@@ -244,7 +244,9 @@ def ema_train(R0, depth: int, K: int, iters: int, decay: float, eps: float, pick
       "online" (all stages in every step, as in the paper's training): codebooks start from picked
           rows stage by stage (sample initialisation); then `iters` steps, each walking the stages:
           assign with the current codebook, pass on the residual formed with that (pre-update)
-          codebook, update the codebook.
+          codebook, update the codebook.  With `batches` (a list of `iters` arrays [M_t][dhat])
+          step t works on batches[t] instead of R0, as the paper's training does with a fresh
+          batch of tokens in every step; R0 then only serves the initialisation.
     Returns C [depth][K][dhat] float64."""
     R0 = _f64(R0)
     M, dhat = R0.shape
@@ -252,7 +254,7 @@ def ema_train(R0, depth: int, K: int, iters: int, decay: float, eps: float, pick
 
     def assign(R, Cs):
         out = encode(R, Cs[None], dhat, CONTIGUOUS, scale=False, want_residual=True)
-        return out["codes"].reshape(M), out["residual"].reshape(M, dhat)
+        return out["codes"].reshape(R.shape[0]), out["residual"].reshape(R.shape[0], dhat)
 
     if schedule == "sequential":
         R = R0
@@ -273,8 +275,8 @@ def ema_train(R0, depth: int, K: int, iters: int, decay: float, eps: float, pick
         _, R = assign(R, C[s])
     cs = [np.ones(K) for _ in range(depth)]
     es = [C[s].copy() for s in range(depth)]
-    for _ in range(iters):
-        R = R0
+    for t in range(iters):
+        R = R0 if batches is None else _f64(batches[t])
         for s in range(depth):
             codes, Rn = assign(R, C[s])
             cs[s], es[s], C[s] = ema_update(R, codes, K, decay, eps, cs[s], es[s])

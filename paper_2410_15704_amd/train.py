@@ -123,31 +123,42 @@ def kmeans_init_codebooks(Z: torch.Tensor, depth: int, K: int, iters: int, picks
 
 
 def ema_train_online(R0: torch.Tensor, depth: int, K: int, iters: int, decay: float, eps: float,
-                     picks, encode_path: int = b.PATH_AUTO) -> torch.Tensor:
+                     picks, encode_path: int = b.PATH_AUTO, batches=None,
+                     init: torch.Tensor | None = None) -> torch.Tensor:
     """All stages in every step, as in the paper's training (Section 3): the codebooks start from
     picked rows stage by stage (sample initialisation); then `iters` steps, each walking the
     stages: assign with the current codebook (rvq_encode over that stage), pass on the residual
     formed with that pre-update codebook, update the codebook (rvq_ema_update).  Moving-average
-    state N_k = 1, M_k = C_k at the start.  R0 float32 [M][dhat].  Returns C [depth][K][dhat]."""
+    state N_k = 1, M_k = C_k at the start.  R0 float32 [M][dhat].  With `batches` (a callable:
+    step -> float32 [M_t][dhat] on the device) every step works on a fresh batch, as the paper's
+    training does, and R0 only serves the initialisation; `init` [depth][K][dhat] replaces the
+    sample initialisation (e.g. by kmeans_init_codebooks).  Returns C [depth][K][dhat]."""
     M, dhat = R0.shape
     dev = R0.device
     q = b.Quantizer(d=dhat, dhat=dhat, depth=depth, K=K, scale=0, encode_path=encode_path)
     C = torch.zeros((depth, K, dhat), dtype=torch.float32, device=dev)
     codes = torch.empty((M, 1, depth), dtype=torch.int16, device=dev)
     R = R0.contiguous()
-    for s in range(depth):
-        C[s] = R.index_select(0, torch.as_tensor(picks[s], dtype=torch.int64, device=dev))
+    if init is not None:
+        C = init.to(device=dev, dtype=torch.float32).contiguous().clone()
         q.set_codebooks(C)
-        _, _, res = q.encode(R, want_residual=True, stages=(s, s + 1), codes=codes)
-        R = res.view(M, dhat)
+    else:
+        for s in range(depth):
+            C[s] = R.index_select(0, torch.as_tensor(picks[s], dtype=torch.int64, device=dev))
+            q.set_codebooks(C)
+            _, _, res = q.encode(R, want_residual=True, stages=(s, s + 1), codes=codes)
+            R = res.view(M, dhat)
     cs = [torch.ones(K, dtype=torch.float32, device=dev) for _ in range(depth)]
     es = [C[s].clone() for s in range(depth)]
-    for _ in range(iters):
-        R = R0.contiguous()
+    for t in range(iters):
+        R = (R0 if batches is None else batches(t)).contiguous()
+        Mt = R.shape[0]
+        if codes.shape[0] != Mt:
+            codes = torch.empty((Mt, 1, depth), dtype=torch.int16, device=dev)
         for s in range(depth):
             _, _, res = q.encode(R, want_residual=True, stages=(s, s + 1), codes=codes)
-            b.rvq_ema_update(q.ctx, s, R, codes.data_ptr() + 2 * s, depth, M, decay, eps, cs[s], es[s])
-            R = res.view(M, dhat)
+            b.rvq_ema_update(q.ctx, s, R, codes.data_ptr() + 2 * s, depth, Mt, decay, eps, cs[s], es[s])
+            R = res.view(Mt, dhat)
     C = q.get_codebooks()
     torch.cuda.synchronize()
     q.close()

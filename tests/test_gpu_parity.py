@@ -715,6 +715,44 @@ def test_ema_training_schedule_matches_oracle(gpu_device, schedule):
         assert rel <= 1e-5
 
 
+def test_ema_training_fresh_batches_matches_oracle(gpu_device):
+    """The paper's online training with a new batch in every step (here 4 steps of 20000 mixture
+    vectors, depth 3, K = 96, decay 0.99): learnt codebooks within 1e-5 of the oracle's."""
+    torch = _torch()
+    from paper_2410_15704_amd import train
+    depth, K, iters, M = 3, 96, 4, 20000
+    Rall = synth.gaussian_mixture(M=M * (iters + 1))
+    B = [Rall[i * M:(i + 1) * M] for i in range(iters + 1)]
+    rng = np.random.Generator(np.random.PCG64(62))
+    picks = [np.sort(rng.choice(M, K, replace=False)) for _ in range(depth)]
+    dB = [torch.from_numpy(np.ascontiguousarray(x)).cuda() for x in B]
+    Cg = train.ema_train_online(dB[0], depth, K, iters, 0.99, 1e-5, picks,
+                                batches=lambda t: dB[t + 1])
+    Co = oracle.ema_train(B[0].astype(np.float64), depth, K, iters, np.float32(0.99),
+                          np.float32(1e-5), picks, "online",
+                          batches=[x.astype(np.float64) for x in B[1:]])
+    for s in range(depth):
+        rel = _frob_rel(Cg[s].cpu().numpy(), Co[s])
+        print(f"fresh batches, stage {s}: rel {rel:.2e}")
+        assert rel <= 1e-5
+
+
+def test_ablation_driver_small(gpu_device):
+    """The ablation driver (k-means initialisation, moving-average training on a fresh batch per
+    step, held-out evaluation) at toy size: runs through the library for keys (strided) and values
+    (contiguous), the error falls with the number of codebooks, and a run repeats bit for bit."""
+    from paper_2410_15704_amd import ablation
+    argv = ["--steps", "3", "--tokens", "512", "--heads", "4", "--depths", "2", "4", "--codes", "64",
+            "--kmeans-iters", "2"]
+    r1 = ablation.main(argv)
+    r2 = ablation.main(argv)
+    assert [x["relative_error"] for x in r1] == [x["relative_error"] for x in r2]
+    for kind in ("k", "v"):
+        e = {x["codebooks"]: x["relative_error"] for x in r1 if x["tensor"] == kind}
+        assert 0.0 < e[4] < e[2] < 1.0
+    assert r1[0]["bits_per_head_vector"] == 4 * 2 * 6 + 16
+
+
 def test_kmeans_init_matches_oracle(gpu_device):
     """Section 3's k-means initialisation driven through rvq_encode + rvq_ema_update (decay 0)
     against the oracle's, from the same picked rows: codebooks within 1e-5 per stage."""

@@ -458,6 +458,29 @@ def test_ema_training_schedules_reduce_to_known_cases():
     np.testing.assert_allclose(a, c, rtol=1e-12)
 
 
+def test_ema_training_with_a_fresh_batch_per_step():
+    """The paper's training sees a new batch in every step.  With decay 0 and no smoothing a step
+    forgets the past: after two steps the first codebook holds the centroids of the SECOND batch
+    under the assignment to the codebook left by the first step (brute force here), a codeword
+    nobody chose being 0; and with the same batch in every step it is the fixed-batch schedule."""
+    rng = np.random.Generator(np.random.PCG64(53))
+    K, dh = 12, 3
+    B = [rng.standard_normal((400, dh)) + 2.0 * rng.integers(0, 3, (400, 1)) for _ in range(3)]
+    picks = [np.sort(rng.choice(400, K, replace=False))]
+    C1 = oracle.ema_train(B[0], 1, K, 1, 0.0, 0.0, picks, "online", batches=[B[1]])[0]
+    C2 = oracle.ema_train(B[0], 1, K, 2, 0.0, 0.0, picks, "online", batches=[B[1], B[2]])[0]
+    d2 = ((B[2][:, None, :] - C1[None, :, :]) ** 2).sum(-1)
+    near = d2.argmin(1)
+    for k in range(K):
+        sel = B[2][near == k]
+        want = sel.mean(0) if len(sel) else np.zeros(dh)
+        np.testing.assert_allclose(C2[k], want, rtol=1e-12, atol=1e-12)
+    picks2 = [np.sort(rng.choice(400, K, replace=False)) for _ in range(2)]
+    a = oracle.ema_train(B[0], 2, K, 3, 0.9, 1e-5, picks2, "online")
+    b = oracle.ema_train(B[0], 2, K, 3, 0.9, 1e-5, picks2, "online", batches=[B[0]] * 3)
+    assert np.array_equal(a, b)
+
+
 # ---- Section 3: keys are quantized before the rotary embedding -----------------------------------
 def test_decode_rope_against_complex_multiplication_and_special_angles():
     """The rotary embedding of the decoded vector: pair i as a complex number times
