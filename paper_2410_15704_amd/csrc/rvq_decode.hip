@@ -16,6 +16,7 @@ namespace {
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 // sum * std, rounded to fp32.  The empty asm keeps the compiler from merging the multiplication
 // with the later conversion to fp16 into one mixed-precision instruction (one rounding instead of
@@ -183,7 +184,10 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
   // tpp = 8 / G tokens.
   const int tpp = (G < 8 && (8 % G) == 0) ? 8 / G : 1;
   const int gsh = (G & (G - 1)) == 0 ? __ffs(G) - 1 : -1;  // log2 G when G is a power of two
-  const int ts = tpp > 1 ? p >> gsh : 0;  // this lane's token within the pass
+  // tokens in the low bits of p, groups in the high ones: with G = 4 the four lanes that hold one
+  // token's groups are then 16 and 32 lanes apart, which the half-swap instructions reach
+  const int ts = tpp > 1 ? p & (tpp - 1) : 0;  // this lane's token within the pass
+  const bool xpose4 = STRIDED && G == 4;        // strided rows of 4 groups: transposed in registers
   stage_t *stage_w = reinterpret_cast<stage_t *>(smem) + (size_t)wave * lds_row * 32 * tpp;
   stage_t *stage = stage_w + (size_t)ts * lds_row * 32;
 
@@ -194,7 +198,7 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
     const bool tok_ok = nb + ts < N;
     const float sd = load_std(std_in, std_dtype, n);
     for (int g0 = 0; g0 < G; g0 += 8) {
-      const int g = tpp > 1 ? p - ts * G : g0 + p;
+      const int g = tpp > 1 ? p / tpp : g0 + p;
       float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
       float rco[2] = {1.f, 1.f}, rsi[2] = {0.f, 0.f};
       if (g < G && tok_ok) {
@@ -207,13 +211,22 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
             rope_load(rp, n, g * 32 + q * 4, rco[0], rsi[0]);
             rope_load(rp, n, g * 32 + q * 4 + 2, rco[1], rsi[1]);
           }
+          if (ROPE && xpose4) {  // the four channels this lane stores after the transpose
+            rope_load(rp, n, 16 * q + 4 * g, rco[0], rsi[0]);
+            rope_load(rp, n, 16 * q + 4 * g + 2, rco[1], rsi[1]);
+          }
+          // the rows of all eight stages are fetched without a condition, so that the eight
+          // loads are in flight together; stages beyond depth_used are left out of the sum
+          float4 c4[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const int k = clamp_code(code_of<PK>(w, i), K);
+            c4[i] = *reinterpret_cast<const float4 *>(C + ((int64_t)i * K + k) * 32 + q * 4);
+          }
 #pragma unroll
           for (int i = 0; i < 8; ++i) {
             if (i < depth_used) {
-              const int k = clamp_code(code_of<PK>(w, i), K);
-              const float4 c4 =
-                  *reinterpret_cast<const float4 *>(C + ((int64_t)i * K + k) * 32 + q * 4);
-              acc.x += c4.x; acc.y += c4.y; acc.z += c4.z; acc.w += c4.w;
+              acc.x += c4[i].x; acc.y += c4[i].y; acc.z += c4[i].z; acc.w += c4[i].w;
             }
           }
         } else {
@@ -249,6 +262,63 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
             const f32x4 av = {acc.x, acc.y, acc.z, acc.w};
             __builtin_nontemporal_store(av, reinterpret_cast<f32x4 *>(o));
           }
+        } else if (DEPTH8 && xpose4) {
+          // G = 4: element j = 4q + t of group g goes to channel 4 j + g.  The lanes of groups
+          // 0..3 (16 and 32 lanes apart) transpose their 4 x 4 values with four half-swaps; lane
+          // g then holds element j = 4q + g of all four groups: channels 16 q + 4 g .. + 3.
+          unsigned a0 = __float_as_uint(acc.x), a1 = __float_as_uint(acc.y);
+          unsigned a2 = __float_as_uint(acc.z), a3 = __float_as_uint(acc.w);
+          {
+            const auto r = __builtin_amdgcn_permlane16_swap(a0, a1, false, false);
+            a0 = r[0]; a1 = r[1];
+          }
+          {
+            const auto r = __builtin_amdgcn_permlane16_swap(a2, a3, false, false);
+            a2 = r[0]; a3 = r[1];
+          }
+          {
+            const auto r = __builtin_amdgcn_permlane32_swap(a0, a2, false, false);
+            a0 = r[0]; a2 = r[1];
+          }
+          {
+            const auto r = __builtin_amdgcn_permlane32_swap(a1, a3, false, false);
+            a1 = r[0]; a3 = r[1];
+          }
+          float x0 = __uint_as_float(a0), x1 = __uint_as_float(a1);
+          float x2 = __uint_as_float(a2), x3 = __uint_as_float(a3);
+          if (ROPE) {
+            rope_apply(rco[0], rsi[0], x0, x1);
+            rope_apply(rco[1], rsi[1], x2, x3);
+          }
+          // The four lanes now hold 4 adjacent channels each, 16 q + 4 g .. + 3; stored like that,
+          // neighbouring lanes would write 32 bytes apart.  Two more rounds of half-swaps hand
+          // all 16 channels of the quarter to the lane of group 0, whose stores continue those
+          // of the lanes next to it.
+          constexpr int NW = OUT_F16 ? 2 : 4;  // 32-bit words of this lane's four channels
+          unsigned W[4 * NW];
+          if (OUT_F16) {
+            W[0] = (uint32_t)__half_as_ushort(__float2half_rn(x0)) |
+                   ((uint32_t)__half_as_ushort(__float2half_rn(x1)) << 16);
+            W[1] = (uint32_t)__half_as_ushort(__float2half_rn(x2)) |
+                   ((uint32_t)__half_as_ushort(__float2half_rn(x3)) << 16);
+          } else {
+            W[0] = __float_as_uint(x0); W[1 % NW] = __float_as_uint(x1);
+            W[2 % NW] = __float_as_uint(x2); W[3 % NW] = __float_as_uint(x3);
+          }
+#pragma unroll
+          for (int i = 0; i < NW; ++i)  // groups 0 and 2 receive the words of groups 1 and 3
+            W[NW + i] = __builtin_amdgcn_permlane16_swap(W[i], W[i], false, false)[1];
+#pragma unroll
+          for (int i = 0; i < 2 * NW; ++i)  // group 0 receives the words of groups 2 and 3
+            W[2 * NW + i] = __builtin_amdgcn_permlane32_swap(W[i], W[i], false, false)[1];
+          if (g == 0) {
+            u32x4 *o = reinterpret_cast<u32x4 *>(reinterpret_cast<out_t *>(out) + n * ldo + 16 * q);
+#pragma unroll
+            for (int i = 0; i < NW; ++i) {
+              const u32x4 v = {W[4 * i], W[4 * i + 1], W[4 * i + 2], W[4 * i + 3]};
+              __builtin_nontemporal_store(v, o + i);
+            }
+          }
         } else {
           // element j = 4q + t of group g goes to channel j * G + g: LDS row j, column g
           const float a[4] = {acc.x, acc.y, acc.z, acc.w};
@@ -262,7 +332,7 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
         }
       }
     }
-    if (STRIDED) {
+    if (STRIDED && !(DEPTH8 && xpose4)) {
       // the wavefront's own LDS writes are visible to its later reads (same wave, in order)
       __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
       for (int t = 0; t < tpp && nb + t < N; ++t) {
