@@ -491,6 +491,41 @@ def test_ema_update_matches_oracle(gpu_device, M, K, dhat, decay, eps):
     q.close()
 
 
+def test_largest_codebook(gpu_device):
+    """K = 32768, the most an int16 code can name: encode sweeps the codebook in 16 chunks of
+    LDS, decode gathers from a 4 MiB stage, and the moving-average update takes the global-atomic
+    path (no LDS histogram fits).  512 vectors, 2 stages, against the oracle."""
+    torch, b = _torch(), _b()
+    K, depth, dhat, d, N = 32768, 2, 32, 64, 256
+    rng = np.random.Generator(np.random.PCG64(777))
+    X = rng.standard_normal((N, d)).astype(np.float32)
+    C = (rng.standard_normal((depth, K, dhat)) * np.array([0.9, 0.5])[:, None, None]).astype(np.float32)
+    r = check_encode(X, "fp32", d, dhat, depth, K, oracle.STRIDED, C)
+    print("K = 32768 encode:", r)
+    codes = rng.integers(0, K, size=(N, d // dhat, depth)).astype(np.int16)
+    codes[0, 0, :] = K - 1
+    std = np.exp(0.3 * rng.standard_normal(N)).astype(np.float32)
+    check_decode(codes, std, "fp32", C, d, dhat, oracle.STRIDED)
+    # one update of stage 0 from 5000 vectors that use the whole range of codes
+    M = 5000
+    R = rng.standard_normal((M, dhat)).astype(np.float32)
+    kc = rng.integers(0, K, size=M).astype(np.int16)
+    kc[:3] = [0, K - 1, K - 1]
+    q = b.Quantizer(d=dhat, dhat=dhat, depth=depth, K=K, scale=0)
+    q.set_codebooks(torch.from_numpy(C).cuda())
+    cs0, es0 = np.ones(K, dtype=np.float32), C[0].copy()
+    d_cs, d_es = torch.from_numpy(cs0).cuda(), torch.from_numpy(es0).cuda()
+    b.rvq_ema_update(q.ctx, 0, torch.from_numpy(R).cuda(), torch.from_numpy(kc).cuda(), 1, M,
+                     0.9, 1e-5, d_cs, d_es)
+    torch.cuda.synchronize()
+    cs, es, cb = oracle.ema_update(R.astype(np.float64), kc, K, np.float32(0.9), np.float32(1e-5),
+                                   cs0.astype(np.float64), es0.astype(np.float64))
+    assert _frob_rel(d_cs.cpu().numpy(), cs) <= 1e-5
+    assert _frob_rel(d_es.cpu().numpy(), es) <= 1e-5
+    assert _frob_rel(q.get_codebooks().cpu().numpy()[0], cb) <= 1e-5
+    q.close()
+
+
 def test_ema_strided_codes_and_code_stride(gpu_device):
     """Codes taken from an [M][depth] encode output with stride depth."""
     torch, b = _torch(), _b()
