@@ -183,6 +183,7 @@ def test_encode_tiny_workload_full_parity(gpu_device):
     (77, 40, 20, 2, 17, oracle.CONTIGUOUS, "fp16"),    # dhat that is no power of two
     (50, 128, 32, 1, 1, oracle.CONTIGUOUS, "fp32"),    # single codeword, single stage
     (1, 1024, 32, 8, 512, oracle.STRIDED, "bf16"),     # one row
+    (90, 64, 32, 16, 40, oracle.STRIDED, "fp32"),      # the largest number of stages
 ])
 def test_encode_small_and_ragged(gpu_device, case):
     N, d, dhat, depth, K, grouping, dtype = case
@@ -409,6 +410,7 @@ def test_long_context_shape_mse_per_depth(gpu_device):
     (1001, 128, 32, 8, 2048, oracle.STRIDED, "fp16", None),    # one head per row: two rows per pass,
     (1001, 128, 32, 8, 2048, oracle.CONTIGUOUS, "fp16", None), # and an odd row count
     (37, 32, 32, 4, 64, oracle.CONTIGUOUS, "fp32", None),      # one group per row: eight rows per pass
+    (70, 128, 32, 16, 40, oracle.STRIDED, "fp16", 11),         # the largest number of stages
 ])
 def test_decode_small_and_ragged(gpu_device, case):
     N, d, dhat, depth, K, grouping, sdt, used = case
