@@ -81,6 +81,13 @@ int rvq_create(rvq_ctx **out, const rvq_config *cfg) {
   ctx->ws_ema = nullptr;
   ctx->ws_ema_bytes = 0;
   hipError_t e = hipGetDevice(&ctx->device);
+  ctx->num_cus = 256;
+  if (e == hipSuccess) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ctx->device) == hipSuccess &&
+        cus > 0)
+      ctx->num_cus = cus;
+  }
   const size_t cb = (size_t)cfg->depth * cfg->K * cfg->dhat * sizeof(float);
   if (e == hipSuccess) e = hipMalloc((void **)&ctx->C, cb);
   if (e == hipSuccess) e = hipMalloc((void **)&ctx->norms, (size_t)cfg->depth * cfg->K * sizeof(float));

@@ -325,30 +325,61 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
   const int wave = tid >> 6;
   const int p = lane & 31;
   const int h = lane >> 5;
-  const int64_t vbase = (int64_t)blockIdx.x * SCR_TOKENS + wave * (SCR_TT * 32);
+  // A workgroup walks the chunks of SCR_TOKENS vectors blockIdx.x, blockIdx.x + gridDim.x, ...;
+  // vbase is the first vector of this wavefront in the chunk it is working on (the two teams may
+  // be in different chunks for a while).
+  const int64_t nchunks_all = (a.V + SCR_TOKENS - 1) / SCR_TOKENS;
+  const int nmy = (int)((nchunks_all - blockIdx.x + gridDim.x - 1) / gridDim.x);  // chunks of this workgroup
+  int64_t vbase = 0;
   const int wtok = wave * (SCR_TT * 32);  // first token slot of this wavefront in the workgroup
   uint4 *qB = lds_qB + wave * SCR_QCAP * 4;
   uint2 *qM = lds_qM + wave * SCR_QCAP;
 
   // ---- load this lane's 16 channels of its 4 tokens, scaled by the row std (Section 2.2)
   float r[SCR_TT][16];
+  auto load_chunk = [&](int64_t chunk) {
+    vbase = chunk * SCR_TOKENS + wave * (SCR_TT * 32);
 #pragma unroll
-  for (int tt = 0; tt < SCR_TT; ++tt) {
-    const int64_t v = vbase + tt * 32 + p;
-    const bool valid = v < a.V;
-    const int64_t n = valid ? v / a.G : 0;
-    const int g = valid ? (int)(v - n * a.G) : 0;
-    const float sd = (valid && a.std32) ? a.std32[n] : 1.0f;
+    for (int tt = 0; tt < SCR_TT; ++tt) {
+      // no branch around the loads, so that all 16 of a token are in flight together: a vector
+      // beyond the end reads the last vector (V >= 1) and is set to zero afterwards
+      const int64_t v = vbase + tt * 32 + p;
+      const bool valid = v < a.V;
+      const int64_t vc = valid ? v : a.V - 1;
+      const int64_t n = vc / a.G;
+      const int g = (int)(vc - n * a.G);
+      const float sd = a.std32 ? a.std32[n] : 1.0f;
+      float x[16];
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const int dim = 16 * h + j;
-      const int64_t ch = a.grouping == RVQ_CONTIGUOUS ? (int64_t)g * 32 + dim : (int64_t)dim * a.G + g;
-      float x = 0.f;
-      if (valid) x = rvq_load_in<DT>(a.X, n * a.ldx + ch);
-      r[tt][j] = a.std32 ? x / sd : x;
+      for (int j = 0; j < 16; ++j) {
+        const int dim = 16 * h + j;
+        const int64_t ch = a.grouping == RVQ_CONTIGUOUS ? (int64_t)g * 32 + dim : (int64_t)dim * a.G + g;
+        x[j] = rvq_load_in<DT>(a.X, n * a.ldx + ch);
+      }
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const float xv = valid ? x[j] : 0.f;
+        r[tt][j] = a.std32 ? xv / sd : xv;
+      }
     }
-  }
-
+  };
+  // the residuals of the chunk just finished, if the caller wants them
+  auto store_chunk = [&]() {
+    if (a.residual) {
+#pragma unroll
+      for (int tt = 0; tt < SCR_TT; ++tt) {
+        const int64_t v = vbase + tt * 32 + p;
+        if (v < a.V) {
+          f32x4 *dst = reinterpret_cast<f32x4 *>(a.residual + v * 32 + 16 * h);
+#pragma unroll
+          for (int c4 = 0; c4 < 4; ++c4) {
+            const f32x4 w = {r[tt][c4 * 4 + 0], r[tt][c4 * 4 + 1], r[tt][c4 * 4 + 2], r[tt][c4 * 4 + 3]};
+            dst[c4] = w;
+          }
+        }
+      }
+    }
+  };
   PHASE_MARK(0);  // input load
   unsigned n_slow = 0, n_over = 0, n_exact = 0, n_groups = 0, n_search = 0;  // wave-uniform
   const unsigned tag_mask = ~((1u << a.tag_bits) - 1u);
@@ -757,7 +788,9 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
   };
 
   // ---- phase T of a stage
-  auto tail_phase = [&](int stage) {
+  int64_t load_next = blockIdx.x;  // chunk to load at the top of the next half-step (-1: none)
+  // `next_chunk`: the chunk this wavefront takes up after the last stage (-1: none)
+  auto tail_phase = [&](int stage, int64_t next_chunk) {
     if (single_chunk) {
       const int kc = a.Kpad;
       (void)kc;
@@ -870,10 +903,14 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
       }
     }
     PHASE_MARK(5);  // exact scores + code emit
-    if (stage + 1 < a.stage_end) convert(stage + 1);
+    if (stage + 1 < a.stage_end) {
+      convert(stage + 1);
+    } else {
+      store_chunk();
+      load_next = next_chunk;  // taken up at the top of the next half-step
+    }
   };
 
-  convert(a.stage_begin);
   const int nst = a.stage_end - a.stage_begin;
   // The teams do not meet at workgroup barriers between stages: they count in LDS.
   //   lds_f[t]: wavefronts of team t that have finished phase L (all reads of the operands in
@@ -904,29 +941,47 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
     __syncthreads();
     PHASE_MARK(2);  // staging
   }
-  for (int hs = 0; hs <= 2 * nst; ++hs) {
-    const int i = hs >> 1;
+  // sg counts the (chunk, stage) pairs of this workgroup: stage sg % nst of its chunk sg / nst.
+  // The teams carry straight on from the last stage of one chunk to the first of the next (the
+  // tail phase of a chunk's last stage stores its residuals and loads the next chunk), so the
+  // half-idle first and last half-steps are paid once per workgroup, not once per chunk.
+  const int SG = nmy * nst;
+  for (int hs = 0; hs <= 2 * SG; ++hs) {
+    const int sg = hs >> 1;
     const bool even = (hs & 1) == 0;
     // one call site per phase: the two teams differ only in which half-step runs which
-    const bool do_lds = team == 0 ? (even && i < nst) : !even;
-    const bool do_tail = team == 0 ? !even : (even && i >= 1);
+    const bool do_lds = team == 0 ? (even && sg < SG) : !even;
+    const bool do_tail = team == 0 ? !even : (even && sg >= 1);
+    if (load_next >= 0) {  // the first chunk, or the one after a chunk's last stage
+      load_chunk(load_next);
+      load_next = -1;
+      PHASE_MARK(0);  // input load
+      convert(a.stage_begin);
+    }
     if (do_lds) {
-      if (single_chunk && i > 0) {
+      const int i = sg % nst;
+      if (single_chunk && sg > 0) {
         if (team == 0) {
-          spin_ge(0, 4u * i);
-          spin_ge(1, 4u * i);
+          spin_ge(0, 4u * sg);
+          spin_ge(1, 4u * sg);
           PHASE_MARK(8);  // waiting for the end of the previous stage's phase L
           stage_to_lds(a.stage_begin + i, 0, a.Kpad, wave, SCR_WAVES / 2);
           __builtin_amdgcn_s_waitcnt(0x0f70);
           signal(2);
         }
-        spin_ge(2, 4u * i);
+        spin_ge(2, 4u * sg);
         PHASE_MARK(2);  // staging
       }
       lds_phase(a.stage_begin + i);
       if (single_chunk) signal(team);
     }
-    if (do_tail) tail_phase(a.stage_begin + (team == 0 ? i : i - 1));
+    if (do_tail) {
+      const int sgt = team == 0 ? sg : sg - 1;
+      const int i = sgt % nst;
+      const int64_t nextc = (sgt + 1 < SG && i == nst - 1)
+                                ? (int64_t)blockIdx.x + (int64_t)(sgt / nst + 1) * gridDim.x : -1;
+      tail_phase(a.stage_begin + i, nextc);
+    }
   }
 
   // statistics: one update per workgroup (the counters are shared by the whole grid)
@@ -950,20 +1005,6 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
   if (lane == 0)
     for (int i = 0; i < 9; ++i) atomicAdd(&a.counters[(i < 6 ? 4 : 5) + i], (unsigned long long)phase_acc[i]);
 #endif
-  if (a.residual) {
-#pragma unroll
-    for (int tt = 0; tt < SCR_TT; ++tt) {
-      const int64_t v = vbase + tt * 32 + p;
-      if (v < a.V) {
-        f32x4 *dst = reinterpret_cast<f32x4 *>(a.residual + v * 32 + 16 * h);
-#pragma unroll
-        for (int c4 = 0; c4 < 4; ++c4) {
-          const f32x4 w = {r[tt][c4 * 4 + 0], r[tt][c4 * 4 + 1], r[tt][c4 * 4 + 2], r[tt][c4 * 4 + 3]};
-          dst[c4] = w;
-        }
-      }
-    }
-  }
 }
 
 }  // namespace
@@ -997,8 +1038,10 @@ hipError_t rvq_launch_encode_screen(const rvq_ctx *ctx, const void *dX, int64_t 
   a.stage_begin = stage_begin;
   a.stage_end = stage_end;
   a.tag_bits = ctx->tag_bits;
-  const int64_t grid64 = (a.V + SCR_TOKENS - 1) / SCR_TOKENS;
-  if (grid64 > 0x7fffffffLL) return hipErrorInvalidValue;
+  // one workgroup fills a CU (LDS): as many workgroups as CUs, each walking its share of the chunks
+  const int64_t nchunks = (a.V + SCR_TOKENS - 1) / SCR_TOKENS;
+  const int64_t grid64 = nchunks < ctx->num_cus ? nchunks : ctx->num_cus;
+  if (grid64 < 1) return hipSuccess;
   const dim3 grid((unsigned)grid64), block(64 * SCR_WAVES);
   hipError_t e;
 #define RVQ_LAUNCH_SCREEN(DT)                                                                   \

@@ -32,6 +32,7 @@ struct rvq_ctx {
   float *stats;        // [depth][8]: rounding-error bounds and scales of the fp16 operands
   int32_t *dup;        // [depth][K] 1 if the codeword repeats an earlier one exactly
   float *rowmax;       // [depth][K] largest |2 c| of each codeword (infinity: not finite)
+  int32_t num_cus;     // compute units of the device (persistent kernels launch one workgroup each)
   int32_t Kpad;
   int32_t tag_bits;    // low mantissa bits that carry the tile number
   float kappa;         // relative bound on accumulation + tagging error of a screened score
