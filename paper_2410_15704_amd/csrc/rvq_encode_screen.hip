@@ -394,16 +394,24 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
     auto dma = [&](const void *gsrc, void *ldst, int bytes) {
       const char *src = reinterpret_cast<const char *>(gsrc);
       char *dstb = reinterpret_cast<char *>(ldst);
-      for (int off = w * 1024; off < bytes; off += nw * 1024)
-        if (off + lane * 16 < bytes)
-          __builtin_amdgcn_global_load_lds(
-              (const __attribute__((address_space(1))) void *)(src + off + lane * 16),
-              (__attribute__((address_space(3))) void *)(dstb + off), 16, 0, 0);
+      // four instructions per LDS base (register M0): the instruction's offset field moves both
+      // the global and the LDS address, and rewriting M0 waits for the copies in flight
+      for (int off = w * 4096; off < bytes; off += nw * 4096) {
+        const __attribute__((address_space(1))) void *gp =
+            (const __attribute__((address_space(1))) void *)(src + off + lane * 16);
+        __attribute__((address_space(3))) void *lp = (__attribute__((address_space(3))) void *)(dstb + off);
+        if (off + lane * 16 < bytes) __builtin_amdgcn_global_load_lds(gp, lp, 16, 0, 0);
+        if (off + 1024 + lane * 16 < bytes) __builtin_amdgcn_global_load_lds(gp, lp, 16, 1024, 0);
+        if (off + 2048 + lane * 16 < bytes) __builtin_amdgcn_global_load_lds(gp, lp, 16, 2048, 0);
+        if (off + 3072 + lane * 16 < bytes) __builtin_amdgcn_global_load_lds(gp, lp, 16, 3072, 0);
+      }
     };
-    dma(a.C16 + ((int64_t)st * a.Kpad + cb) * 4, lds_A, kcc * 64);
+    // the three short copies first: whatever the compiler waits for between the calls (reloads
+    // of spilled addresses) then waits for a few loads only, not for the 128 KiB of operands
     dma(a.normp + (int64_t)st * a.Kpad + cb, lds_n, kcc * 4);
     dma(a.groupA + ((int64_t)st * a.Kpad + cb) / 16, lds_g, kcc / 4);
     dma(a.perm16 + (int64_t)st * a.Kpad + cb, lds_p, kcc * 2);
+    dma(a.C16 + ((int64_t)st * a.Kpad + cb) * 4, lds_A, kcc * 64);
   };
   const bool single_chunk = a.Kpad <= SCR_KC;
   // A stage has two phases.  Phase L works against the stage's operands in LDS (sweep on the
