@@ -31,9 +31,10 @@
 // codeword, so stages never round-trip through memory (the fusion Section 3 of the paper
 // describes for its own kernel).
 //
-// Work decomposition: one workgroup = 8 wavefronts x 4 token tiles x 32 tokens = 1024 group
-// vectors; LDS holds one stage (up to 2048 codewords = 128 KiB of fp16 operands + 8 KiB of
-// norms); larger codebooks are swept in chunks of 2048 with the resolve step run per chunk.
+// Work decomposition: a chunk = 8 wavefronts x 4 token tiles x 32 tokens = 1024 group vectors;
+// one workgroup per CU (LDS admits no second) walks the chunks blockIdx.x, blockIdx.x +
+// gridDim.x, ...; LDS holds one stage (up to 2048 codewords = 128 KiB of fp16 operands + 8 KiB
+// of norms); larger codebooks are swept in pieces of 2048 with the resolve step run per piece.
 // A token is split over the lane pair (p, p + 32): each lane owns 16 of its 32 channels.
 #include "rvq_internal.h"
 
