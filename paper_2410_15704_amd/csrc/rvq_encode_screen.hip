@@ -123,9 +123,12 @@ __device__ __forceinline__ float dot8(const uint4 w, const half8 b, float acc) {
 }
 
 #ifdef RVQ_PHASE_CLOCKS
+#ifndef RVQ_PHASE_CLOCK_FN
+#define RVQ_PHASE_CLOCK_FN wall_clock64  // 100 MHz; clock64 counts shader cycles instead
+#endif
 #define PHASE_MARK(i)                                            \
   do {                                                           \
-    const long long now_ = wall_clock64();                       \
+    const long long now_ = RVQ_PHASE_CLOCK_FN();                 \
     phase_acc[i] += now_ - phase_t;                              \
     phase_t = now_;                                              \
   } while (0)
@@ -306,7 +309,7 @@ template <int DT>
 __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const ScreenArgs a) {
 #ifdef RVQ_PHASE_CLOCKS
   long long phase_acc[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
-  long long phase_t = wall_clock64();
+  long long phase_t = RVQ_PHASE_CLOCK_FN();
 #endif
   extern __shared__ uint4 smem[];
   uint4 *lds_A = smem;                                              // SCR_KC * 4 chunks of 16 B
