@@ -98,6 +98,22 @@ __device__ __forceinline__ void rope_load(const RopeArgs &rp, int64_t n, int c_e
   co = rp.cs[t];
   si = rp.sn[t];
 }
+// the two pairs that start at channels c4 and c4 + 2 (c4 a multiple of 4 inside the head): their
+// table entries are neighbours, one 8-byte load per table when the head size is a multiple of 4
+__device__ __forceinline__ void rope_load2(const RopeArgs &rp, int64_t n, int c4, float (&co)[2],
+                                           float (&si)[2]) {
+  if ((rp.hd & 3) == 0) {
+    const int ch = rp.hmask ? (c4 & rp.hmask) : (c4 % rp.hd);
+    const int64_t t = n * (rp.hd >> 1) + (ch >> 1);  // even: the tables are 16-byte aligned
+    const float2 c2 = *reinterpret_cast<const float2 *>(rp.cs + t);
+    const float2 s2 = *reinterpret_cast<const float2 *>(rp.sn + t);
+    co[0] = c2.x; co[1] = c2.y;
+    si[0] = s2.x; si[1] = s2.y;
+  } else {
+    rope_load(rp, n, c4, co[0], si[0]);
+    rope_load(rp, n, c4 + 2, co[1], si[1]);
+  }
+}
 __device__ __forceinline__ void rope_apply(float co, float si, float &x0, float &x1) {
   const float y0 = x0 * co - x1 * si;
   const float y1 = x0 * si + x1 * co;
@@ -197,24 +213,40 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
     const int64_t n = min(nb + ts, N - 1);
     const bool tok_ok = nb + ts < N;
     const float sd = load_std(std_in, std_dtype, n);
-    for (int g0 = 0; g0 < G; g0 += 8) {
+    // Contiguous groups: a pass covers 256 channels; when that is a whole number of heads, a
+    // lane's two pairs sit at the same place of their head in every pass, and their table entries
+    // are fetched once per token
+    float rco[2] = {1.f, 1.f}, rsi[2] = {0.f, 0.f};
+    const bool rope_once = ROPE && !STRIDED && DEPTH8 && (256 % rp.hd) == 0;
+    if (rope_once) rope_load2(rp, n, (tpp > 1 ? p / tpp : p) * 32 + q * 4, rco, rsi);
+    for (int gb = 0; gb < G; gb += 32) {
+    // The codes of up to four passes are fetched together, ahead of the first pass: a pass is a
+    // chain of dependent loads (codes from HBM, then the rows they select from L2), and with one
+    // code fetch per pass a wavefront spent most of its time waiting for HBM, once per pass.
+    // Indices are clamped, so the loads need no condition.
+    i32x4 wq[4];
+    if (DEPTH8) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int gu = tpp > 1 ? p / tpp : gb + 8 * u + p;
+        if (u == 0 || gb + 8 * u < G) wq[u] = load_codes8<PK, false>(codes_v, n * G + min(gu, G - 1));
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int g0 = gb + 8 * u;
+      if (g0 >= G) break;
       const int g = tpp > 1 ? p / tpp : g0 + p;
       float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-      float rco[2] = {1.f, 1.f}, rsi[2] = {0.f, 0.f};
       if (g < G && tok_ok) {
         const int16_t *cg = reinterpret_cast<const int16_t *>(codes_v) + (n * G + g) * depth;
         if (DEPTH8) {
           // codes and outputs are streamed once: non-temporal accesses keep them from evicting
           // the codebook rows, which every wavefront gathers again and again, from L2
-          const i32x4 w = load_codes8<PK, false>(codes_v, n * G + g);
-          if (ROPE && !STRIDED) {  // fetched now, used after the gathers
-            rope_load(rp, n, g * 32 + q * 4, rco[0], rsi[0]);
-            rope_load(rp, n, g * 32 + q * 4 + 2, rco[1], rsi[1]);
-          }
-          if (ROPE && xpose4) {  // the four channels this lane stores after the transpose
-            rope_load(rp, n, 16 * q + 4 * g, rco[0], rsi[0]);
-            rope_load(rp, n, 16 * q + 4 * g + 2, rco[1], rsi[1]);
-          }
+          const i32x4 w = wq[u];
+          if (ROPE && !STRIDED && !rope_once) rope_load2(rp, n, g * 32 + q * 4, rco, rsi);
+          // the four channels this lane stores after the transpose
+          if (ROPE && xpose4) rope_load2(rp, n, 16 * q + 4 * g, rco, rsi);
           // the rows of all eight stages are fetched without a condition, so that the eight
           // loads are in flight together; stages beyond depth_used are left out of the sum
           float4 c4[8];
@@ -331,6 +363,7 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
           }
         }
       }
+    }
     }
     if (STRIDED && !(DEPTH8 && xpose4)) {
       // the wavefront's own LDS writes are visible to its later reads (same wave, in order)
