@@ -209,29 +209,52 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
 
   const int64_t wave_global = (int64_t)blockIdx.x * DEC_WAVES + wave;
   const int64_t wave_count = (int64_t)gridDim.x * DEC_WAVES;
-  for (int64_t nb = wave_global * tpp; nb < N; nb += wave_count * tpp) {
-    const int64_t n = min(nb + ts, N - 1);
-    const bool tok_ok = nb + ts < N;
-    const float sd = load_std(std_in, std_dtype, n);
-    // Contiguous groups: a pass covers 256 channels; when that is a whole number of heads, a
-    // lane's two pairs sit at the same place of their head in every pass, and their table entries
-    // are fetched once per token
-    float rco[2] = {1.f, 1.f}, rsi[2] = {0.f, 0.f};
-    const bool rope_once = ROPE && !STRIDED && DEPTH8 && (256 % rp.hd) == 0;
-    if (rope_once) rope_load2(rp, n, (tpp > 1 ? p / tpp : p) * 32 + q * 4, rco, rsi);
-    for (int gb = 0; gb < G; gb += 32) {
-    // The codes of up to four passes are fetched together, ahead of the first pass: a pass is a
-    // chain of dependent loads (codes from HBM, then the rows they select from L2), and with one
-    // code fetch per pass a wavefront spent most of its time waiting for HBM, once per pass.
-    // Indices are clamped, so the loads need no condition.
+  // A unit of work = (token(s) of a pass, chunk of up to four passes = 32 groups).  What a unit
+  // reads from HBM (std, the codes of its passes, and for contiguous groups the rotary table
+  // entries: a pass covers 256 channels, and when that is a whole number of heads a lane's two
+  // pairs sit at the same place of their head in every pass) is fetched while the unit before it
+  // is worked on: a pass is a chain of dependent loads (codes from HBM, then the rows they select
+  // from L2), and with one code fetch per pass a wavefront spent most of its time waiting for
+  // HBM.  Indices are clamped, so these loads need no condition, also beyond the last token.
+  const bool rope_once = ROPE && !STRIDED && DEPTH8 && (256 % rp.hd) == 0;
+  struct Unit {
     i32x4 wq[4];
+    float sd;
+    float rco[2], rsi[2];
+  };
+  auto fetch = [&](int64_t nb_, int gb_, Unit &U) {
+    const int64_t n_ = min(nb_ + ts, N - 1);
+    U.sd = load_std(std_in, std_dtype, n_);
     if (DEPTH8) {
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        const int gu = tpp > 1 ? p / tpp : gb + 8 * u + p;
-        if (u == 0 || gb + 8 * u < G) wq[u] = load_codes8<PK, false>(codes_v, n * G + min(gu, G - 1));
+        const int gu = tpp > 1 ? p / tpp : gb_ + 8 * u + p;
+        if (u == 0 || gb_ + 8 * u < G)
+          U.wq[u] = load_codes8<PK, false>(codes_v, n_ * G + min(gu, G - 1));
       }
     }
+    U.rco[0] = U.rco[1] = 1.f;
+    U.rsi[0] = U.rsi[1] = 0.f;
+    if (rope_once) rope_load2(rp, n_, (tpp > 1 ? p / tpp : p) * 32 + q * 4, U.rco, U.rsi);
+  };
+  int64_t nb = wave_global * tpp;
+  int gb = 0;
+  Unit nxt;
+  if (nb < N) fetch(nb, 0, nxt);
+  while (nb < N) {
+    const Unit cur = nxt;
+    int64_t nbn = nb;
+    int gbn = gb + 32;
+    if (gbn >= G) {
+      gbn = 0;
+      nbn = nb + wave_count * tpp;
+    }
+    fetch(nbn, gbn, nxt);
+    const int64_t n = min(nb + ts, N - 1);
+    const bool tok_ok = nb + ts < N;
+    const float sd = cur.sd;
+    float rco[2] = {cur.rco[0], cur.rco[1]}, rsi[2] = {cur.rsi[0], cur.rsi[1]};
+    {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int g0 = gb + 8 * u;
@@ -243,7 +266,7 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
         if (DEPTH8) {
           // codes and outputs are streamed once: non-temporal accesses keep them from evicting
           // the codebook rows, which every wavefront gathers again and again, from L2
-          const i32x4 w = wq[u];
+          const i32x4 w = cur.wq[u];
           if (ROPE && !STRIDED && !rope_once) rope_load2(rp, n, g * 32 + q * 4, rco, rsi);
           // the four channels this lane stores after the transpose
           if (ROPE && xpose4) rope_load2(rp, n, 16 * q + 4 * g, rco, rsi);
@@ -365,7 +388,7 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
       }
     }
     }
-    if (STRIDED && !(DEPTH8 && xpose4)) {
+    if (STRIDED && !(DEPTH8 && xpose4) && gbn == 0) {
       // the wavefront's own LDS writes are visible to its later reads (same wave, in order)
       __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
       for (int t = 0; t < tpp && nb + t < N; ++t) {
@@ -405,6 +428,8 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
       }
       __builtin_amdgcn_s_waitcnt(0xc07f);
     }
+    nb = nbn;
+    gb = gbn;
   }
 }
 
