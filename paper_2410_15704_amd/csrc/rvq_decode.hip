@@ -182,7 +182,9 @@ constexpr int DEC_WAVES = 4;
 
 // ROPE (strided grouping only matters): the staged row is kept in fp32 so that the rotation sees
 // unrounded values
-template <bool OUT_F16, bool STRIDED, int DEPTH8, int PK, bool ROPE>
+// NP: passes per unit of work, 4 (32 groups), or 1 for rows of at most 8 groups (registers are
+// allotted for the gathers of all NP passes, which a one-pass row would hold for nothing)
+template <bool OUT_F16, bool STRIDED, int DEPTH8, int PK, bool ROPE, int NP>
 __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
     const void *__restrict__ codes_v, const void *__restrict__ std_in, int std_dtype, int64_t N,
     int G, const float *__restrict__ C, int K, int depth, int depth_used, void *__restrict__ out,
@@ -218,7 +220,7 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
   // HBM.  Indices are clamped, so these loads need no condition, also beyond the last token.
   const bool rope_once = ROPE && !STRIDED && DEPTH8 && (256 % rp.hd) == 0;
   struct Unit {
-    i32x4 wq[4];
+    i32x4 wq[NP];
     float sd;
     float rco[2], rsi[2];
   };
@@ -227,7 +229,7 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
     U.sd = load_std(std_in, std_dtype, n_);
     if (DEPTH8) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < NP; ++u) {
         const int gu = tpp > 1 ? p / tpp : gb_ + 8 * u + p;
         if (u == 0 || gb_ + 8 * u < G)
           U.wq[u] = load_codes8<PK, false>(codes_v, n_ * G + min(gu, G - 1));
@@ -244,7 +246,7 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
   while (nb < N) {
     const Unit cur = nxt;
     int64_t nbn = nb;
-    int gbn = gb + 32;
+    int gbn = gb + 8 * NP;
     if (gbn >= G) {
       gbn = 0;
       nbn = nb + wave_count * tpp;
@@ -256,7 +258,7 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
     float rco[2] = {cur.rco[0], cur.rco[1]}, rsi[2] = {cur.rsi[0], cur.rsi[1]};
     {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < NP; ++u) {
       const int g0 = gb + 8 * u;
       if (g0 >= G) break;
       const int g = tpp > 1 ? p / tpp : g0 + p;
@@ -746,10 +748,15 @@ hipError_t rvq_launch_decode(const rvq_ctx *ctx, const void *dCodes, int packed,
     if (blocks > cap) blocks = cap;
     const dim3 grid((unsigned)blocks), block(64 * DEC_WAVES);
     const bool d8 = c.depth == 8;
-#define RVQ_LAUNCH_ROWS(F16, STR, D8, PK, RO)                                                    \
-  hipLaunchKernelGGL((decode_rows32_kernel<F16, STR, D8, PK, RO>), grid, block, lds_bytes, s,    \
-                     dCodes, dStd, c.std_dtype, N, G, ctx->C, c.K, c.depth, depth_used, dOut,    \
+#define RVQ_LAUNCH_ROWS_NP(F16, STR, D8, PK, RO, NP)                                             \
+  hipLaunchKernelGGL((decode_rows32_kernel<F16, STR, D8, PK, RO, NP>), grid, block, lds_bytes,   \
+                     s, dCodes, dStd, c.std_dtype, N, G, ctx->C, c.K, c.depth, depth_used, dOut, \
                      ldo, lds_row, rp)
+#define RVQ_LAUNCH_ROWS(F16, STR, D8, PK, RO)                                                    \
+  do {                                                                                           \
+    if (D8 && G > 8) RVQ_LAUNCH_ROWS_NP(F16, STR, D8, PK, RO, 4);                                \
+    else RVQ_LAUNCH_ROWS_NP(F16, STR, D8, PK, RO, 1);                                            \
+  } while (0)
 #define RVQ_LAUNCH_ROWS_FS(F16, STR)                                                             \
   do {                                                                                           \
     if (rope) { if (d8) RVQ_LAUNCH_ROWS(F16, STR, 1, 0, true); else RVQ_LAUNCH_ROWS(F16, STR, 0, 0, true); } \
@@ -762,6 +769,7 @@ hipError_t rvq_launch_decode(const rvq_ctx *ctx, const void *dCodes, int packed,
     else { if (strided) RVQ_LAUNCH_ROWS_FS(false, true); else RVQ_LAUNCH_ROWS_FS(false, false); }
 #undef RVQ_LAUNCH_ROWS_FS
 #undef RVQ_LAUNCH_ROWS
+#undef RVQ_LAUNCH_ROWS_NP
     return hipGetLastError();
   }
   const int64_t total = N * c.d;
