@@ -411,6 +411,8 @@ def test_long_context_shape_mse_per_depth(gpu_device):
     (1001, 128, 32, 8, 2048, oracle.CONTIGUOUS, "fp16", None), # and an odd row count
     (37, 32, 32, 4, 64, oracle.CONTIGUOUS, "fp32", None),      # one group per row: eight rows per pass
     (70, 128, 32, 16, 40, oracle.STRIDED, "fp16", 11),         # the largest number of stages
+    (203, 1280, 32, 8, 300, oracle.CONTIGUOUS, "fp16", None),  # 40 groups: units of four passes and of one
+    (203, 2304, 32, 8, 300, oracle.STRIDED, "fp16", 7),        # 72 groups through the row-gather kernel
 ])
 def test_decode_small_and_ragged(gpu_device, case):
     N, d, dhat, depth, K, grouping, sdt, used = case
@@ -675,6 +677,11 @@ def _check_rope(out_gpu, ref, mode):
     (1000, 1024, 32, 8, 2048, oracle.CONTIGUOUS, 128),
     (200, 64, 8, 3, 50, oracle.STRIDED, 32),          # generic kernel
     (200, 40, 20, 2, 17, oracle.CONTIGUOUS, 20),      # generic kernel, odd sizes
+    (301, 1024, 32, 8, 300, oracle.CONTIGUOUS, 64),   # four heads per pass: table entries once per token
+    (301, 1152, 32, 8, 300, oracle.CONTIGUOUS, 96),   # a pass is no whole number of heads: entries per pass
+    (50, 96, 32, 8, 64, oracle.CONTIGUOUS, 6),        # head size no multiple of 4: single-entry loads
+    (501, 128, 32, 8, 300, oracle.CONTIGUOUS, 128),   # one head per row, two rows per pass
+    (501, 128, 32, 8, 300, oracle.STRIDED, 128),      # the same, transposed in registers
 ])
 def test_decode_rope_small(gpu_device, case):
     """rvq_decode_rope against the oracle's decode + rotation (same codes, std and tables)."""
