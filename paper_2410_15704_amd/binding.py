@@ -9,6 +9,11 @@ from __future__ import annotations
 import ctypes
 import os
 
+# PyTorch comes first: it carries its own HIP runtime, and librvq.so must bind to that copy.  Loaded
+# the other way round, the system's runtime is in the process before PyTorch's and PyTorch then
+# finds no GPU.
+import torch  # noqa: F401
+
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "librvq.so")
 
