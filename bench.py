@@ -320,8 +320,9 @@ def run_profile(args):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (rows shard without communication; "
-              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (rows shard across GPUs without "
+              "communication, the moving-average update needs one all-reduce per stage); "
+              "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     import torch
 
