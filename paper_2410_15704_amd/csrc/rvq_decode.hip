@@ -184,7 +184,11 @@ constexpr int DEC_WAVES = 4;
 // unrounded values
 // NP: passes per unit of work, 4 (32 groups), or 1 for rows of at most 8 groups (registers are
 // allotted for the gathers of all NP passes, which a one-pass row would hold for nothing)
-template <bool OUT_F16, bool STRIDED, int DEPTH8, int PK, bool ROPE, int NP>
+// WIDE (int16 codes, 32 or 64 groups, NP = 4, no rotation): a 16-byte load per lane fetches the
+// codes of two units at once (1 KiB), two such loads make a fetch, and the lanes take their
+// passes' codes from them by lane permutes; a wavefront then waits for HBM once per four units
+// instead of once per unit.
+template <bool OUT_F16, bool STRIDED, int DEPTH8, int PK, bool ROPE, int NP, bool WIDE>
 __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
     const void *__restrict__ codes_v, const void *__restrict__ std_in, int std_dtype, int64_t N,
     int G, const float *__restrict__ C, int K, int depth, int depth_used, void *__restrict__ out,
@@ -239,19 +243,9 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
     U.rsi[0] = U.rsi[1] = 0.f;
     if (rope_once) rope_load2(rp, n_, (tpp > 1 ? p / tpp : p) * 32 + q * 4, U.rco, U.rsi);
   };
-  int64_t nb = wave_global * tpp;
-  int gb = 0;
-  Unit nxt;
-  if (nb < N) fetch(nb, 0, nxt);
-  while (nb < N) {
-    const Unit cur = nxt;
-    int64_t nbn = nb;
-    int gbn = gb + 8 * NP;
-    if (gbn >= G) {
-      gbn = 0;
-      nbn = nb + wave_count * tpp;
-    }
-    fetch(nbn, gbn, nxt);
+  // one unit: passes gb / 8 .. of token(s) nb; `last` = the token's last unit (strided rows are
+  // then streamed out of LDS)
+  auto do_unit = [&](const int64_t nb, const int gb, const bool last, const Unit &cur) {
     const int64_t n = min(nb + ts, N - 1);
     const bool tok_ok = nb + ts < N;
     const float sd = cur.sd;
@@ -390,7 +384,7 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
       }
     }
     }
-    if (STRIDED && !(DEPTH8 && xpose4) && gbn == 0) {
+    if (STRIDED && !(DEPTH8 && xpose4) && last) {
       // the wavefront's own LDS writes are visible to its later reads (same wave, in order)
       __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
       for (int t = 0; t < tpp && nb + t < N; ++t) {
@@ -430,6 +424,71 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
       }
       __builtin_amdgcn_s_waitcnt(0xc07f);
     }
+  };
+
+  if (WIDE) {
+    constexpr int WL = 4;               // 1 KiB loads per fetch: 2 WL units of 32 groups
+    const int csh = __ffs(G >> 5) - 1;  // log2 of the units per token (G = 32 * 2^csh)
+    const int64_t units = N << csh;
+    auto fetchw = [&](int64_t f_, i32x4 (&wide_)[WL], float (&sd_)[2 * WL]) {
+#pragma unroll
+      for (int l = 0; l < WL; ++l) {
+        // this lane's (token, group) of load l: units 2 (WL f + l) and 2 (WL f + l) + 1
+        const int64_t gi = min((f_ * WL + l) * 64 + lane, N * G - 1);
+        wide_[l] = load_codes8<0, false>(codes_v, gi);
+      }
+#pragma unroll
+      for (int e = 0; e < 2 * WL; ++e)
+        sd_[e] = load_std(std_in, std_dtype, min(2 * WL * f_ + e, units - 1) >> csh);
+    };
+    i32x4 wide_n[WL];
+    float sd_n[2 * WL];
+    int64_t f = wave_global;  // units 2 WL f .. 2 WL f + 2 WL - 1
+    if (2 * WL * f < units) fetchw(f, wide_n, sd_n);
+    for (; 2 * WL * f < units; f += wave_count) {
+      i32x4 wide_c[WL];
+      float sd_c[2 * WL];
+#pragma unroll
+      for (int l = 0; l < WL; ++l) wide_c[l] = wide_n[l];
+#pragma unroll
+      for (int e = 0; e < 2 * WL; ++e) sd_c[e] = sd_n[e];
+      fetchw(f + wave_count, wide_n, sd_n);
+#pragma unroll
+      for (int e = 0; e < 2 * WL; ++e) {
+        const int64_t U = 2 * WL * f + e;
+        if (U >= units) break;
+        Unit cur;
+        cur.sd = sd_c[e];
+        cur.rco[0] = cur.rco[1] = 1.f;
+        cur.rsi[0] = cur.rsi[1] = 0.f;
+#pragma unroll
+        for (int u = 0; u < NP; ++u) {
+          const int src = ((e & 1) * 32 + 8 * u + p) << 2;  // byte index of the lane that holds the group
+#pragma unroll
+          for (int w4 = 0; w4 < 4; ++w4)
+            cur.wq[u][w4] = __builtin_amdgcn_ds_bpermute(src, wide_c[e >> 1][w4]);
+        }
+        const int gb = (int)(U & ((1 << csh) - 1)) << 5;
+        do_unit(U >> csh, gb, gb + 32 >= G, cur);
+      }
+    }
+    return;
+  }
+
+  int64_t nb = wave_global * tpp;
+  int gb = 0;
+  Unit nxt;
+  if (nb < N) fetch(nb, 0, nxt);
+  while (nb < N) {
+    const Unit cur = nxt;
+    int64_t nbn = nb;
+    int gbn = gb + 8 * NP;
+    if (gbn >= G) {
+      gbn = 0;
+      nbn = nb + wave_count * tpp;
+    }
+    fetch(nbn, gbn, nxt);
+    do_unit(nb, gb, gbn == 0, cur);
     nb = nbn;
     gb = gbn;
   }
@@ -748,14 +807,18 @@ hipError_t rvq_launch_decode(const rvq_ctx *ctx, const void *dCodes, int packed,
     if (blocks > cap) blocks = cap;
     const dim3 grid((unsigned)blocks), block(64 * DEC_WAVES);
     const bool d8 = c.depth == 8;
-#define RVQ_LAUNCH_ROWS_NP(F16, STR, D8, PK, RO, NP)                                             \
-  hipLaunchKernelGGL((decode_rows32_kernel<F16, STR, D8, PK, RO, NP>), grid, block, lds_bytes,   \
-                     s, dCodes, dStd, c.std_dtype, N, G, ctx->C, c.K, c.depth, depth_used, dOut, \
-                     ldo, lds_row, rp)
+    // 32 or 64 groups: two units of 32 groups are 1 KiB of codes, one load per lane, and are two
+    // tokens or one (with more groups a token's units would land in different wavefronts)
+    const bool wide_ok = G == 32 || G == 64;
+#define RVQ_LAUNCH_ROWS_NP(F16, STR, D8, PK, RO, NP, WD)                                         \
+  hipLaunchKernelGGL((decode_rows32_kernel<F16, STR, D8, PK, RO, NP, WD>), grid, block,          \
+                     lds_bytes, s, dCodes, dStd, c.std_dtype, N, G, ctx->C, c.K, c.depth,        \
+                     depth_used, dOut, ldo, lds_row, rp)
 #define RVQ_LAUNCH_ROWS(F16, STR, D8, PK, RO)                                                    \
   do {                                                                                           \
-    if (D8 && G > 8) RVQ_LAUNCH_ROWS_NP(F16, STR, D8, PK, RO, 4);                                \
-    else RVQ_LAUNCH_ROWS_NP(F16, STR, D8, PK, RO, 1);                                            \
+    if (D8 && PK == 0 && !RO && wide_ok) RVQ_LAUNCH_ROWS_NP(F16, STR, D8, 0, false, 4, true);    \
+    else if (D8 && G > 8) RVQ_LAUNCH_ROWS_NP(F16, STR, D8, PK, RO, 4, false);                    \
+    else RVQ_LAUNCH_ROWS_NP(F16, STR, D8, PK, RO, 1, false);                                     \
   } while (0)
 #define RVQ_LAUNCH_ROWS_FS(F16, STR)                                                             \
   do {                                                                                           \

@@ -413,6 +413,11 @@ def test_long_context_shape_mse_per_depth(gpu_device):
     (70, 128, 32, 16, 40, oracle.STRIDED, "fp16", 11),         # the largest number of stages
     (203, 1280, 32, 8, 300, oracle.CONTIGUOUS, "fp16", None),  # 40 groups: units of four passes and of one
     (203, 2304, 32, 8, 300, oracle.STRIDED, "fp16", 7),        # 72 groups through the row-gather kernel
+    (1003, 1024, 32, 8, 2048, oracle.CONTIGUOUS, "fp16", None),  # codes of eight units per fetch: a ragged
+    (1003, 1024, 32, 8, 2048, oracle.STRIDED, "fp32", 3),        # last fetch, 32 groups (one token a unit)
+    (501, 2048, 32, 8, 500, oracle.CONTIGUOUS, "fp16", None),    # and 64 groups (two units a token)
+    (501, 2048, 32, 8, 500, oracle.STRIDED, "fp16", None),
+    (3, 1024, 32, 8, 2048, oracle.CONTIGUOUS, "fp16", None),     # fewer units than one fetch
 ])
 def test_decode_small_and_ragged(gpu_device, case):
     N, d, dhat, depth, K, grouping, sdt, used = case
