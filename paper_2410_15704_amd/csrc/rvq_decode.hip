@@ -184,10 +184,10 @@ constexpr int DEC_WAVES = 4;
 // unrounded values
 // NP: passes per unit of work, 4 (32 groups), or 1 for rows of at most 8 groups (registers are
 // allotted for the gathers of all NP passes, which a one-pass row would hold for nothing)
-// WIDE (int16 codes, 32 or 64 groups, NP = 4, no rotation): a 16-byte load per lane fetches the
-// codes of two units at once (1 KiB), two such loads make a fetch, and the lanes take their
-// passes' codes from them by lane permutes; a wavefront then waits for HBM once per four units
-// instead of once per unit.
+// WIDE (int16 codes, no rotation; 32 or 64 groups with NP = 4, 4 or 8 groups with NP = 1): a
+// 16-byte load per lane fetches the codes of 64 (token, group) pairs at once (1 KiB: 2 units, or 8
+// of short rows), four such loads make a fetch, and the lanes take their passes' codes from them
+// by lane permutes; a wavefront then waits for HBM once per fetch instead of once per unit.
 template <bool OUT_F16, bool STRIDED, int DEPTH8, int PK, bool ROPE, int NP, bool WIDE>
 __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
     const void *__restrict__ codes_v, const void *__restrict__ std_in, int std_dtype, int64_t N,
@@ -427,49 +427,77 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
   };
 
   if (WIDE) {
-    constexpr int WL = 4;               // 1 KiB loads per fetch: 2 WL units of 32 groups
-    const int csh = __ffs(G >> 5) - 1;  // log2 of the units per token (G = 32 * 2^csh)
-    const int64_t units = N << csh;
-    auto fetchw = [&](int64_t f_, i32x4 (&wide_)[WL], float (&sd_)[2 * WL]) {
+    constexpr int EPU = 8 * NP;     // (token, group) entries of a unit: 32, or 8 for short rows
+    constexpr int UPL = 64 / EPU;   // units per 1 KiB load: 2 or 8
+    constexpr int WL = 4;           // loads per fetch
+    constexpr int UPF = UPL * WL;   // units per fetch: 8 or 32
+    // NP == 4: 32 or 64 groups, a unit is one token or half of one; NP == 1: 4 or 8 groups, a unit
+    // is tpp = 2 tokens or 1
+    const int csh = NP == 4 ? __ffs(G >> 5) - 1 : 0;  // log2 of the units per token
+    const int64_t units = NP == 4 ? N << csh : (N + tpp - 1) / tpp;
+    auto fetchw = [&](int64_t f_, i32x4 (&wide_)[WL], float (&sd_)[NP == 4 ? UPF : 1]) {
 #pragma unroll
       for (int l = 0; l < WL; ++l) {
-        // this lane's (token, group) of load l: units 2 (WL f + l) and 2 (WL f + l) + 1
-        const int64_t gi = min((f_ * WL + l) * 64 + lane, N * G - 1);
+        const int64_t gi = min((f_ * WL + l) * 64 + lane, N * G - 1);  // this lane's (token, group)
         wide_[l] = load_codes8<0, false>(codes_v, gi);
       }
+      if (NP == 4) {
 #pragma unroll
-      for (int e = 0; e < 2 * WL; ++e)
-        sd_[e] = load_std(std_in, std_dtype, min(2 * WL * f_ + e, units - 1) >> csh);
+        for (int e = 0; e < UPF; ++e)
+          sd_[NP == 4 ? e : 0] = load_std(std_in, std_dtype, min(UPF * f_ + e, units - 1) >> csh);
+      } else {
+        // short rows: the fetch covers UPF tpp <= 64 tokens, one std per lane
+        sd_[0] = load_std(std_in, std_dtype, min(f_ * (UPF * tpp) + lane, N - 1));
+      }
     };
     i32x4 wide_n[WL];
-    float sd_n[2 * WL];
-    int64_t f = wave_global;  // units 2 WL f .. 2 WL f + 2 WL - 1
-    if (2 * WL * f < units) fetchw(f, wide_n, sd_n);
-    for (; 2 * WL * f < units; f += wave_count) {
+    float sd_n[NP == 4 ? UPF : 1];
+    int64_t f = wave_global;  // units UPF f .. UPF f + UPF - 1
+    if (UPF * f < units) fetchw(f, wide_n, sd_n);
+    for (; UPF * f < units; f += wave_count) {
       i32x4 wide_c[WL];
-      float sd_c[2 * WL];
+      float sd_c[NP == 4 ? UPF : 1];
 #pragma unroll
       for (int l = 0; l < WL; ++l) wide_c[l] = wide_n[l];
 #pragma unroll
-      for (int e = 0; e < 2 * WL; ++e) sd_c[e] = sd_n[e];
+      for (int e = 0; e < (NP == 4 ? UPF : 1); ++e) sd_c[e] = sd_n[e];
       fetchw(f + wave_count, wide_n, sd_n);
+      // the units of one load after the other; short rows have eight per load, which are not all
+      // unrolled (the code would not fit the instruction cache)
 #pragma unroll
-      for (int e = 0; e < 2 * WL; ++e) {
-        const int64_t U = 2 * WL * f + e;
-        if (U >= units) break;
-        Unit cur;
-        cur.sd = sd_c[e];
-        cur.rco[0] = cur.rco[1] = 1.f;
-        cur.rsi[0] = cur.rsi[1] = 0.f;
+      for (int l = 0; l < WL; ++l) {
+#pragma unroll(UPL > 2 ? 2 : UPL)
+        for (int eu = 0; eu < UPL; ++eu) {
+          const int e = l * UPL + eu;
+          const int64_t U = UPF * f + e;
+          if (U >= units) break;
+          Unit cur;
+          if (NP == 4) {
+            cur.sd = sd_c[NP == 4 ? e : 0];
+          } else {
+            cur.sd = __int_as_float(
+                __builtin_amdgcn_ds_bpermute((e * tpp + ts) << 2, __float_as_int(sd_c[0])));
+          }
+          cur.rco[0] = cur.rco[1] = 1.f;
+          cur.rsi[0] = cur.rsi[1] = 0.f;
 #pragma unroll
-        for (int u = 0; u < NP; ++u) {
-          const int src = ((e & 1) * 32 + 8 * u + p) << 2;  // byte index of the lane that holds the group
+          for (int u = 0; u < NP; ++u) {
+            // byte index of the lane that holds this lane's (token, group) of pass u (with several
+            // tokens per pass the lane's token is in the low bits of p, memory has it in the high
+            // ones)
+            const int ent = tpp > 1 ? ts * G + p / tpp : 8 * u + p;
+            const int src = (eu * EPU + ent) << 2;
 #pragma unroll
-          for (int w4 = 0; w4 < 4; ++w4)
-            cur.wq[u][w4] = __builtin_amdgcn_ds_bpermute(src, wide_c[e >> 1][w4]);
+            for (int w4 = 0; w4 < 4; ++w4)
+              cur.wq[u][w4] = __builtin_amdgcn_ds_bpermute(src, wide_c[l][w4]);
+          }
+          if (NP == 4) {
+            const int gb = (int)(U & ((1 << csh) - 1)) << 5;
+            do_unit(U >> csh, gb, gb + 32 >= G, cur);
+          } else {
+            do_unit(U * tpp, 0, true, cur);
+          }
         }
-        const int gb = (int)(U & ((1 << csh) - 1)) << 5;
-        do_unit(U >> csh, gb, gb + 32 >= G, cur);
       }
     }
     return;
@@ -810,13 +838,19 @@ hipError_t rvq_launch_decode(const rvq_ctx *ctx, const void *dCodes, int packed,
     // 32 or 64 groups: two units of 32 groups are 1 KiB of codes, one load per lane, and are two
     // tokens or one (with more groups a token's units would land in different wavefronts)
     const bool wide_ok = G == 32 || G == 64;
+    const bool wide_short = G == 4 || G == 8;  // short rows: eight units of 8 pairs per load
 #define RVQ_LAUNCH_ROWS_NP(F16, STR, D8, PK, RO, NP, WD)                                         \
   hipLaunchKernelGGL((decode_rows32_kernel<F16, STR, D8, PK, RO, NP, WD>), grid, block,          \
                      lds_bytes, s, dCodes, dStd, c.std_dtype, N, G, ctx->C, c.K, c.depth,        \
                      depth_used, dOut, ldo, lds_row, rp)
 #define RVQ_LAUNCH_ROWS(F16, STR, D8, PK, RO)                                                    \
   do {                                                                                           \
-    if (D8 && PK == 0 && !RO && wide_ok) RVQ_LAUNCH_ROWS_NP(F16, STR, D8, 0, false, 4, true);    \
+    /* the wide variants exist for int16 codes, depth 8, no rotation; for any other instance   */ \
+    /* these two lines name the plain kernels again                                            */ \
+    if (D8 && PK == 0 && !RO && wide_ok)                                                         \
+      RVQ_LAUNCH_ROWS_NP(F16, STR, D8, PK, RO, 4, (D8 && PK == 0 && !RO));                       \
+    else if (D8 && PK == 0 && !RO && wide_short)                                                 \
+      RVQ_LAUNCH_ROWS_NP(F16, STR, D8, PK, RO, 1, (D8 && PK == 0 && !RO));                       \
     else if (D8 && G > 8) RVQ_LAUNCH_ROWS_NP(F16, STR, D8, PK, RO, 4, false);                    \
     else RVQ_LAUNCH_ROWS_NP(F16, STR, D8, PK, RO, 1, false);                                     \
   } while (0)

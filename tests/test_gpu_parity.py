@@ -418,6 +418,8 @@ def test_long_context_shape_mse_per_depth(gpu_device):
     (501, 2048, 32, 8, 500, oracle.CONTIGUOUS, "fp16", None),    # and 64 groups (two units a token)
     (501, 2048, 32, 8, 500, oracle.STRIDED, "fp16", None),
     (3, 1024, 32, 8, 2048, oracle.CONTIGUOUS, "fp16", None),     # fewer units than one fetch
+    (777, 256, 32, 8, 300, oracle.CONTIGUOUS, "fp16", None),     # 8 groups: 32 one-token units per fetch
+    (777, 256, 32, 8, 300, oracle.STRIDED, "fp32", 6),
 ])
 def test_decode_small_and_ragged(gpu_device, case):
     N, d, dhat, depth, K, grouping, sdt, used = case
