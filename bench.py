@@ -32,7 +32,7 @@ PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `--profile encode` and
 # `--profile decode`, scaled by the readings of a plain 1 GiB copy (profiles/*.txt hold the runs)
 TRAFFIC_ENCODE_W2 = 3.3345e5 * 2048 + 6.7991e5 * 1024            # encode_screen_kernel, workload 2
-TRAFFIC_DECODE_SLICE = 0.5 * ((1.4004e5 + 1.4342e5) * 2048) + 1.0486e6 * 1024  # mean of both kernels
+TRAFFIC_DECODE_SLICE = 0.5 * ((1.4004e5 + 1.4063e5) * 2048) + 1.0486e6 * 1024  # mean of both kernels
 
 W2 = dict(N=32768, d=1024, dhat=32, depth=8, K=2048)
 
