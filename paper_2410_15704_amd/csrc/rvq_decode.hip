@@ -428,18 +428,28 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
 
   if (WIDE) {
     constexpr int EPU = 8 * NP;     // (token, group) entries of a unit: 32, or 8 for short rows
-    constexpr int UPL = 64 / EPU;   // units per 1 KiB load: 2 or 8
-    constexpr int WL = 4;           // loads per fetch
-    constexpr int UPF = UPL * WL;   // units per fetch: 8 or 32
+    constexpr int UPL = 64 / EPU;   // units per 64 entries: 2 or 8
+    constexpr int VL = 4;           // a fetch is 4 x 64 = 256 entries
+    constexpr int UPF = UPL * VL;   // units per fetch: 8 or 32
+    // int16 codes: 256 entries are four 1 KiB loads; packed records (PK bytes): 256 PK bytes =
+    // three loads.  The wavefront puts them into its own LDS area and a lane then reads its entry
+    // (the aligned window of its record) there.
+    constexpr int FCH = PK ? 16 * PK : 256;       // 16-byte chunks of a fetch
+    constexpr int WL = (FCH + 63) / 64;           // loads per fetch: 4, or 3
+    constexpr int WAREA = PK ? 3088 : 4096;       // LDS bytes per wavefront
+    uint32_t *wlds = reinterpret_cast<uint32_t *>(
+        smem + (size_t)DEC_WAVES * lds_row * 32 * tpp * sizeof(stage_t) + (size_t)wave * WAREA);
     // NP == 4: 32 or 64 groups, a unit is one token or half of one; NP == 1: 4 or 8 groups, a unit
     // is tpp = 2 tokens or 1
     const int csh = NP == 4 ? __ffs(G >> 5) - 1 : 0;  // log2 of the units per token
     const int64_t units = NP == 4 ? N << csh : (N + tpp - 1) / tpp;
+    // the host has checked that the codes are a whole number of 16-byte chunks
+    const int64_t last_chunk = PK ? (N * G * PK) / 16 - 1 : N * G - 1;
     auto fetchw = [&](int64_t f_, i32x4 (&wide_)[WL], float (&sd_)[NP == 4 ? UPF : 1]) {
 #pragma unroll
       for (int l = 0; l < WL; ++l) {
-        const int64_t gi = min((f_ * WL + l) * 64 + lane, N * G - 1);  // this lane's (token, group)
-        wide_[l] = load_codes8<0, false>(codes_v, gi);
+        const int64_t ch = min(f_ * FCH + l * 64 + lane, last_chunk);
+        wide_[l] = load_codes8<0, false>(codes_v, ch);  // chunk = entry for int16 codes
       }
       if (NP == 4) {
 #pragma unroll
@@ -462,10 +472,19 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
 #pragma unroll
       for (int e = 0; e < (NP == 4 ? UPF : 1); ++e) sd_c[e] = sd_n[e];
       fetchw(f + wave_count, wide_n, sd_n);
-      // the units of one load after the other; short rows have eight per load, which are not all
+      {
+        // the previous fetch's records have all been read (program order within the wavefront)
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int l = 0; l < WL; ++l)
+          if (l * 64 + lane < FCH)
+            *reinterpret_cast<i32x4 *>(wlds + (l * 64 + lane) * 4) = wide_c[l];
+        __builtin_amdgcn_wave_barrier();
+      }
+      // the units of 64 entries after the other; short rows have eight per 64, which are not all
       // unrolled (the code would not fit the instruction cache)
 #pragma unroll
-      for (int l = 0; l < WL; ++l) {
+      for (int l = 0; l < VL; ++l) {
 #pragma unroll(UPL > 2 ? 2 : UPL)
         for (int eu = 0; eu < UPL; ++eu) {
           const int e = l * UPL + eu;
@@ -482,14 +501,24 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
           cur.rsi[0] = cur.rsi[1] = 0.f;
 #pragma unroll
           for (int u = 0; u < NP; ++u) {
-            // byte index of the lane that holds this lane's (token, group) of pass u (with several
-            // tokens per pass the lane's token is in the low bits of p, memory has it in the high
-            // ones)
-            const int ent = tpp > 1 ? ts * G + p / tpp : 8 * u + p;
-            const int src = (eu * EPU + ent) << 2;
-#pragma unroll
-            for (int w4 = 0; w4 < 4; ++w4)
-              cur.wq[u][w4] = __builtin_amdgcn_ds_bpermute(src, wide_c[l][w4]);
+            // this lane's (token, group) of pass u among the 64 entries (with several tokens per
+            // pass the lane's token is in the low bits of p, memory has it in the high ones)
+            const int ent = eu * EPU + (tpp > 1 ? ts * G + p / tpp : 8 * u + p);
+            if (PK) {
+              // the record's bytes [o, o + PK) lie in four aligned words of the LDS copy
+              const int o = (l * 64 + ent) * PK;
+              const uint32_t *wp = wlds + (o >> 2);
+              const uint32_t d0 = wp[0], d1 = wp[1], d2 = wp[2], d3 = wp[3];
+              const int sh = (o & 3) * 8;
+              const uint32_t W0 = __builtin_amdgcn_alignbit(d1, d0, sh);
+              const uint32_t W1 = __builtin_amdgcn_alignbit(d2, d1, sh);
+              const uint32_t W2 = __builtin_amdgcn_alignbit(d3, d2, sh);
+              // in the form code_of reads: first eight bytes, and the last four in the top of w
+              const i32x4 w = {(int)W0, (int)W1, 0, (int)(W2 << (8 * (12 - (PK ? PK : 12))))};
+              cur.wq[u] = w;
+            } else {
+              cur.wq[u] = *reinterpret_cast<const i32x4 *>(wlds + (l * 64 + ent) * 4);
+            }
           }
           if (NP == 4) {
             const int gb = (int)(U & ((1 << csh) - 1)) << 5;
@@ -839,18 +868,25 @@ hipError_t rvq_launch_decode(const rvq_ctx *ctx, const void *dCodes, int packed,
     // tokens or one (with more groups a token's units would land in different wavefronts)
     const bool wide_ok = G == 32 || G == 64;
     const bool wide_short = G == 4 || G == 8;  // short rows: eight units of 8 pairs per load
+    // the fetched codes are staged in LDS, 4096 bytes per wavefront (3088 for packed records,
+    // which are fetched as whole 16-byte chunks)
+    const size_t wide_lds = (size_t)DEC_WAVES * (pk ? 3088 : 4096);
+    const bool wide_fit = (wide_ok || wide_short) && !rope && d8 && lds_bytes + wide_lds <= 64 * 1024;
+    const bool wide_pk = pk != 0 && wide_fit && ((N * G * (int64_t)pk) % 16) == 0;
+    const bool wide_i16 = pk == 0 && wide_fit;
+    if (wide_pk || wide_i16) lds_bytes += wide_lds;
 #define RVQ_LAUNCH_ROWS_NP(F16, STR, D8, PK, RO, NP, WD)                                         \
   hipLaunchKernelGGL((decode_rows32_kernel<F16, STR, D8, PK, RO, NP, WD>), grid, block,          \
                      lds_bytes, s, dCodes, dStd, c.std_dtype, N, G, ctx->C, c.K, c.depth,        \
                      depth_used, dOut, ldo, lds_row, rp)
 #define RVQ_LAUNCH_ROWS(F16, STR, D8, PK, RO)                                                    \
   do {                                                                                           \
-    /* the wide variants exist for int16 codes, depth 8, no rotation; for any other instance   */ \
+    /* the wide variants exist for depth 8 without rotation; for any other instance            */ \
     /* these two lines name the plain kernels again                                            */ \
-    if (D8 && PK == 0 && !RO && wide_ok)                                                         \
-      RVQ_LAUNCH_ROWS_NP(F16, STR, D8, PK, RO, 4, (D8 && PK == 0 && !RO));                       \
-    else if (D8 && PK == 0 && !RO && wide_short)                                                 \
-      RVQ_LAUNCH_ROWS_NP(F16, STR, D8, PK, RO, 1, (D8 && PK == 0 && !RO));                       \
+    if (D8 && !RO && wide_ok && (PK == 0 ? wide_i16 : wide_pk))                                  \
+      RVQ_LAUNCH_ROWS_NP(F16, STR, D8, PK, RO, 4, (D8 && !RO));                                  \
+    else if (D8 && !RO && wide_short && (PK == 0 ? wide_i16 : wide_pk))                          \
+      RVQ_LAUNCH_ROWS_NP(F16, STR, D8, PK, RO, 1, (D8 && !RO));                                  \
     else if (D8 && G > 8) RVQ_LAUNCH_ROWS_NP(F16, STR, D8, PK, RO, 4, false);                    \
     else RVQ_LAUNCH_ROWS_NP(F16, STR, D8, PK, RO, 1, false);                                     \
   } while (0)

@@ -592,6 +592,11 @@ def test_ema_mixture_workload_one_pass(gpu_device):
     (300, 256, 8, 4096, oracle.CONTIGUOUS),   # 12-bit records
     (257, 96, 5, 100, oracle.STRIDED),        # 7 bits, records of 5 bytes: generic kernel
     (64, 64, 16, 3, oracle.CONTIGUOUS),       # 2 bits, depth 16
+    (603, 1024, 8, 2048, oracle.CONTIGUOUS),  # 11-bit records fetched 256 at a time, staged in LDS
+    (603, 2048, 8, 4096, oracle.STRIDED),     # 12-bit records, 64 groups
+    (1004, 128, 8, 2048, oracle.CONTIGUOUS),  # one head per row
+    (1004, 128, 8, 2048, oracle.STRIDED),
+    (1001, 128, 8, 2048, oracle.STRIDED),     # records that end off a 16-byte boundary: fetched per unit
 ])
 def test_packed_codes_and_decode_packed(gpu_device, case):
     """rvq_pack_codes equals the oracle's packing bit for bit, rvq_unpack_codes inverts it, and
