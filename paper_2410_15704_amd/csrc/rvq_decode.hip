@@ -431,6 +431,7 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
     constexpr int UPL = 64 / EPU;   // units per 64 entries: 2 or 8
     constexpr int VL = 4;           // a fetch is 4 x 64 = 256 entries
     constexpr int UPF = UPL * VL;   // units per fetch: 8 or 32
+    constexpr int UNR = UPL > 2 ? 2 : UPL;  // units of one 64-entry block that are unrolled
     // int16 codes: 256 entries are four 1 KiB loads; packed records (PK bytes): 256 PK bytes =
     // three loads.  The wavefront puts them into its own LDS area and a lane then reads its entry
     // (the aligned window of its record) there.
@@ -485,7 +486,7 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
       // unrolled (the code would not fit the instruction cache)
 #pragma unroll
       for (int l = 0; l < VL; ++l) {
-#pragma unroll(UPL > 2 ? 2 : UPL)
+#pragma unroll UNR
         for (int eu = 0; eu < UPL; ++eu) {
           const int e = l * UPL + eu;
           const int64_t U = UPF * f + e;
