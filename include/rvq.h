@@ -20,10 +20,17 @@
  *     16-byte aligned; the CALLER owns them; the library keeps no reference after the work it
  *     enqueued has run;
  *   - work is enqueued on the caller's stream (a hipStream_t passed as void*; NULL = the
- *     default stream); no entry point synchronizes the device except rvq_create/rvq_destroy
- *     and a growth of the context's internal workspace (see rvq_encode);
- *   - the context owns its pre-processed codebook copies and workspace and frees them in
- *     rvq_destroy; one context must not be used from two host threads at once;
+ *     default stream).  The enqueue calls (rvq_set_codebooks, rvq_get_codebooks, rvq_encode,
+ *     rvq_decode*, rvq_pack_codes, rvq_unpack_codes, rvq_ema_update) never allocate, free or
+ *     synchronize; the set-up and diagnostic calls (rvq_create, rvq_destroy, rvq_reserve,
+ *     rvq_get_counters, rvq_check_kernels) may do all three;
+ *   - the context owns its pre-processed codebook copies and its workspace (all of it allocated
+ *     by rvq_create / rvq_reserve) and frees them in rvq_destroy.  The workspace is per context:
+ *     a context must be used by one host thread and on ONE stream at a time (calls on two
+ *     streams would share the workspace and the codebook copies without any ordering); use one
+ *     context per stream, or order the streams with events;
+ *   - inputs must be finite.  A row with a NaN or an infinity gets unspecified codes (every
+ *     code still lies in [0, K) and every access stays in bounds); other rows are unaffected;
  *   - N == 0 / M == 0 is a successful no-op.
  */
 #ifndef RVQ_H
@@ -40,9 +47,13 @@ extern "C" {
 #define RVQ_ENOCODEBOOK (-2) /* encode / decode / ema before rvq_set_codebooks */
 #define RVQ_EHIP (-3)        /* a HIP runtime call failed; see rvq_last_hip_error */
 #define RVQ_ENOMEM (-4)      /* host or device allocation failed */
+#define RVQ_EWORKSPACE (-5)  /* more rows than the context's workspace holds: rvq_reserve first */
+#define RVQ_EKERNEL (-6)     /* a kernel gave up one of its bounded internal waits (never seen in
+                                a correct build); outputs of that launch are not valid */
 
 #define RVQ_MAX_DEPTH 16
 #define RVQ_MAX_K 32768 /* codes are stored as int16 */
+#define RVQ_DEFAULT_ROWS 131072 /* rows per rvq_encode call a new context is ready for */
 
 enum rvq_dtype { RVQ_F32 = 0, RVQ_BF16 = 1, RVQ_F16 = 2 };
 enum rvq_grouping {
@@ -81,6 +92,16 @@ typedef struct {
 int rvq_create(rvq_ctx **out, const rvq_config *cfg);
 int rvq_destroy(rvq_ctx *ctx);
 
+/* Workspace.  rvq_create allocates everything the enqueue calls need: 4 bytes per row for
+ * RVQ_DEFAULT_ROWS rows of an rvq_encode call (when cfg.scale == 1) and the scratch of
+ * rvq_ema_update (counts, sums and per-workgroup partial histograms, at most about
+ * 129 * K * (dhat + 1) * 4 bytes: 35 MB at K = 2048, dhat = 32).  rvq_reserve makes the context
+ * ready for rvq_encode calls of up to max_rows rows; it never shrinks.  It is a set-up call: it
+ * allocates, and when it has to grow the workspace it synchronizes the device first.
+ * rvq_reserved_rows returns the current limit (INT64_MAX when cfg.scale == 0: no limit). */
+int rvq_reserve(rvq_ctx *ctx, int64_t max_rows);
+int64_t rvq_reserved_rows(const rvq_ctx *ctx);
+
 /* Upload the codebooks {C_i} of Algorithm 1: dC is device memory, float [depth][K][dhat].  The
  * context copies them and derives what its kernels need (squared norms, half-precision operand
  * copies, rounding-error bounds); dC may be reused once the stream has passed this call.
@@ -102,8 +123,8 @@ int rvq_get_codebooks(rvq_ctx *ctx, float *dC, void *stream);
  *             (z_{i+1} of Algorithm 1, in group order); NULL to skip
  * Nearest = smallest squared Euclidean distance; ties go to the smallest index.  A row whose std
  * is below 1e-30 is scaled by 1.
- * The context keeps an internal workspace of 4 bytes per row; when N exceeds every earlier N it
- * is re-allocated (hipFree synchronizes the device).
+ * With cfg.scale == 1, N must not exceed rvq_reserved_rows(): RVQ_EWORKSPACE otherwise (nothing
+ * is enqueued).
  */
 int rvq_encode(rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx, int32_t stage_begin,
                int32_t stage_end, int16_t *dCodes, void *dStd, float *dResidual, void *stream);
@@ -111,8 +132,9 @@ int rvq_encode(rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx, int32_t sta
 /*
  * Decode (Section 2.2, last sentence): out[n][c(g,j)] = std[n] * sum_{i < depth_used}
  * C_i[codes[n][g][i]][j], summed in stage order in fp32, rounded once to cfg.out_dtype.
- *   dCodes  device, int16 [N][G][depth]; every code must lie in [0, K) (not checked on device
- *           beyond a clamp that keeps reads in bounds)
+ *   dCodes  device, int16 [N][G][depth]; every code must lie in [0, K).  This is not checked; a
+ *           code outside the range is replaced by some code inside it (clamped, or reduced
+ *           modulo K when K is a power of two, depending on the kernel), so reads stay in bounds
  *   dStd    device, [N] of cfg.std_dtype; NULL means std = 1
  *   depth_used 1..depth
  *   dOut    device, [N] rows of d channels of cfg.out_dtype, row stride ldo elements (>= d)
@@ -166,9 +188,7 @@ int rvq_decode_packed(rvq_ctx *ctx, const uint8_t *dPacked, const void *dStd, in
  *   dClusterSize device, float [K], in/out (N_k)
  *   dEmbedSum    device, float [K][dhat], in/out (M_k)
  * The new codebook replaces codebook `stage` inside the context (and its derived copies);
- * read it back with rvq_get_codebooks.  The first call on a context allocates its scratch
- * (per-code counts and sums plus the per-workgroup partial histograms, about
- * 129 * K * (dhat + 1) * 4 bytes) with hipMalloc.
+ * read it back with rvq_get_codebooks.  The scratch it uses was allocated by rvq_create.
  */
 int rvq_ema_update(rvq_ctx *ctx, int32_t stage, const float *dR, const int16_t *dCodes,
                    int64_t code_stride, int64_t M, float decay, float eps, float *dClusterSize,
@@ -184,6 +204,17 @@ int rvq_ema_update(rvq_ctx *ctx, int32_t stage, const float *dR, const int16_t *
  *       settled by scoring every codeword of their candidate groups exactly.
  */
 int rvq_get_counters(rvq_ctx *ctx, int64_t *host_out);
+
+/*
+ * Kernels of this library that make wavefronts wait for each other bound every such wait; a wait
+ * that expires sets an error word in the context and the kernel still runs to its end.
+ * rvq_check_kernels synchronizes the device, returns RVQ_EKERNEL if a launch since the last
+ * check set the word (and clears it), RVQ_OK otherwise.  rvq_debug_set_wait_polls sets the bound
+ * (polls per wait, 0 .. 2^31 - 1; the default allows about a second); it exists so that the
+ * error path can be exercised: with a bound of 0 every wait gives up at once.
+ */
+int rvq_check_kernels(rvq_ctx *ctx);
+int rvq_debug_set_wait_polls(rvq_ctx *ctx, int64_t polls);
 
 /* Text for an RVQ_E* code; the HIP error code of the last RVQ_EHIP on this context (0 if none). */
 const char *rvq_strerror(int code);

@@ -235,7 +235,7 @@ def kmeans_init_codebooks(Z, depth: int, K: int, iters: int, picks):
 
 
 def ema_train(R0, depth: int, K: int, iters: int, decay: float, eps: float, picks,
-              schedule: str = "sequential", batches=None):
+              schedule: str = "sequential", batches=None, progress=None):
     """Codebook learning by exponential moving average (Sections 2.1 and 3: decay 0.99) on a fixed
     set of vectors R0 [M][dhat], with moving-average state N_k = 1, M_k = C_k at the start.
       "sequential": stage by stage: codebook s starts from rows picks[s] of the vectors entering
@@ -247,6 +247,8 @@ def ema_train(R0, depth: int, K: int, iters: int, decay: float, eps: float, pick
           codebook, update the codebook.  With `batches` (a list of `iters` arrays [M_t][dhat])
           step t works on batches[t] instead of R0, as the paper's training does with a fresh
           batch of tokens in every step; R0 then only serves the initialisation.
+    `progress`, if given, is called with a short text after every stage ("sequential") or step
+    ("online"); it sees no data and changes nothing.
     Returns C [depth][K][dhat] float64."""
     R0 = _f64(R0)
     M, dhat = R0.shape
@@ -266,6 +268,8 @@ def ema_train(R0, depth: int, K: int, iters: int, decay: float, eps: float, pick
                 cs, es, Cs = ema_update(R, codes, K, decay, eps, cs, es)
             _, R = assign(R, Cs)
             C[s] = Cs
+            if progress:
+                progress(f"oracle: stage {s} trained")
         return C
     if schedule != "online":
         raise ValueError(schedule)
@@ -281,6 +285,8 @@ def ema_train(R0, depth: int, K: int, iters: int, decay: float, eps: float, pick
             codes, Rn = assign(R, C[s])
             cs[s], es[s], C[s] = ema_update(R, codes, K, decay, eps, cs[s], es[s])
             R = Rn
+        if progress:
+            progress(f"oracle: step {t} done")
     return C
 
 

@@ -18,6 +18,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "librvq.so")
 
 RVQ_OK, RVQ_EINVAL, RVQ_ENOCODEBOOK, RVQ_EHIP, RVQ_ENOMEM = 0, -1, -2, -3, -4
+RVQ_EWORKSPACE, RVQ_EKERNEL = -5, -6
+DEFAULT_ROWS = 131072
 F32, BF16, F16 = 0, 1, 2
 CONTIGUOUS, STRIDED = 0, 1
 PATH_AUTO, PATH_EXACT, PATH_SCREEN = 0, 1, 2
@@ -26,7 +28,8 @@ DTYPES = {"fp32": F32, "bf16": BF16, "fp16": F16}
 EXPORTS = ("rvq_create", "rvq_destroy", "rvq_set_codebooks", "rvq_get_codebooks", "rvq_encode",
            "rvq_decode", "rvq_ema_update", "rvq_strerror", "rvq_last_hip_error", "rvq_version",
            "rvq_get_counters", "rvq_packed_record_bytes", "rvq_pack_codes", "rvq_unpack_codes",
-           "rvq_decode_packed", "rvq_decode_rope")
+           "rvq_decode_packed", "rvq_decode_rope", "rvq_reserve", "rvq_reserved_rows",
+           "rvq_check_kernels", "rvq_debug_set_wait_polls")
 
 
 class rvq_config(ctypes.Structure):
@@ -56,13 +59,19 @@ def _load():
     lib.rvq_unpack_codes.argtypes = [vp, vp, i64, vp, vp]
     lib.rvq_decode_packed.argtypes = [vp, vp, vp, i64, i32, vp, i64, vp]
     lib.rvq_decode_rope.argtypes = [vp, vp, vp, i64, i32, vp, vp, i32, vp, i64, vp]
+    lib.rvq_reserve.argtypes = [vp, i64]
+    lib.rvq_reserved_rows.argtypes = [vp]
+    lib.rvq_reserved_rows.restype = ctypes.c_int64
+    lib.rvq_check_kernels.argtypes = [vp]
+    lib.rvq_debug_set_wait_polls.argtypes = [vp, i64]
     lib.rvq_strerror.argtypes = [ctypes.c_int]
     lib.rvq_strerror.restype = ctypes.c_char_p
     lib.rvq_last_hip_error.argtypes = [vp]
     lib.rvq_version.restype = ctypes.c_int
     for name in EXPORTS:
         getattr(lib, name)
-        if name not in ("rvq_strerror", "rvq_version", "rvq_packed_record_bytes"):
+        if name not in ("rvq_strerror", "rvq_version", "rvq_packed_record_bytes",
+                        "rvq_reserved_rows"):
             getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -127,6 +136,23 @@ def _chk(rc, ctx):
     if rc != RVQ_OK:
         raise RvqError(rc, ctx)
     return rc
+
+
+def rvq_reserve(ctx, max_rows):
+    return _chk(lib.rvq_reserve(ctx, max_rows), ctx)
+
+
+def rvq_reserved_rows(ctx) -> int:
+    return int(lib.rvq_reserved_rows(ctx))
+
+
+def rvq_check_kernels(ctx, check=True):
+    rc = lib.rvq_check_kernels(ctx)
+    return _chk(rc, ctx) if check else rc
+
+
+def rvq_debug_set_wait_polls(ctx, polls):
+    return _chk(lib.rvq_debug_set_wait_polls(ctx, polls), ctx)
 
 
 def rvq_set_codebooks(ctx, dC, stream=None):
@@ -232,6 +258,8 @@ class Quantizer:
                if self.cfg["scale"] else None)
         res = (torch.empty((N, self.G, self.cfg["dhat"]), dtype=torch.float32, device=X.device)
                if want_residual else None)
+        if N > rvq_reserved_rows(self.ctx):
+            rvq_reserve(self.ctx, N)  # set-up call: grows the context's workspace
         rvq_encode(self.ctx, X, N, X.stride(0) if N else self.cfg["d"], sb, se, codes, std, res)
         return codes, std, res
 

@@ -29,6 +29,22 @@ int validate_config(const rvq_config *c) {
   return RVQ_OK;
 }
 
+// the two kernels of an encode call: per-row std into std32 (and the caller's buffer), then
+// Algorithm 1 over the stage range
+int encode_enqueue(rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx, int stage_begin,
+                   int stage_end, int16_t *dCodes, void *dStd, float *dResidual, float *std32,
+                   hipStream_t s) {
+  const rvq_config &c = ctx->cfg;
+  if (c.scale) RVQ_HIP(ctx, rvq_launch_row_std(ctx, dX, N, ldx, dStd, std32, s));
+  if (c.dhat == 32 && c.encode_path != RVQ_PATH_EXACT)
+    RVQ_HIP(ctx, rvq_launch_encode_screen(ctx, dX, N, ldx, stage_begin, stage_end, dCodes,
+                                          dResidual, std32, s));
+  else
+    RVQ_HIP(ctx, rvq_launch_encode_exact(ctx, dX, N, ldx, stage_begin, stage_end, dCodes,
+                                         dResidual, std32, s));
+  return RVQ_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -42,6 +58,8 @@ const char *rvq_strerror(int code) {
     case RVQ_ENOCODEBOOK: return "codebooks have not been set";
     case RVQ_EHIP: return "HIP runtime error";
     case RVQ_ENOMEM: return "out of memory";
+    case RVQ_EWORKSPACE: return "more rows than the context's workspace holds (rvq_reserve)";
+    case RVQ_EKERNEL: return "a kernel gave up a bounded wait; its outputs are not valid";
     default: return "unknown error";
   }
 }
@@ -80,6 +98,7 @@ int rvq_create(rvq_ctx **out, const rvq_config *cfg) {
   ctx->ws_rows = 0;
   ctx->ws_ema = nullptr;
   ctx->ws_ema_bytes = 0;
+  ctx->wait_polls = RVQ_WAIT_POLLS_DEFAULT;
   hipError_t e = hipGetDevice(&ctx->device);
   ctx->num_cus = 256;
   if (e == hipSuccess) {
@@ -106,6 +125,15 @@ int rvq_create(rvq_ctx **out, const rvq_config *cfg) {
     if (e == hipSuccess && cb <= RVQ_SPLIT_MAX_LDS * 16)
       e = hipMalloc((void **)&ctx->Csplit, cb);
   }
+  // workspace of the enqueue calls: they never allocate
+  if (e == hipSuccess && cfg->scale) {
+    e = hipMalloc((void **)&ctx->ws_std, (size_t)RVQ_DEFAULT_ROWS * sizeof(float));
+    if (e == hipSuccess) ctx->ws_rows = RVQ_DEFAULT_ROWS;
+  }
+  if (e == hipSuccess) {
+    ctx->ws_ema_bytes = rvq_ema_workspace_bytes(ctx);
+    e = hipMalloc((void **)&ctx->ws_ema, ctx->ws_ema_bytes);
+  }
   if (e != hipSuccess) {
     if (ctx->C) (void)hipFree(ctx->C);
     if (ctx->norms) (void)hipFree(ctx->norms);
@@ -119,6 +147,7 @@ int rvq_create(rvq_ctx **out, const rvq_config *cfg) {
     if (ctx->perm16) (void)hipFree(ctx->perm16);
     if (ctx->counters) (void)hipFree(ctx->counters);
     if (ctx->Csplit) (void)hipFree(ctx->Csplit);
+    if (ctx->ws_std) (void)hipFree(ctx->ws_std);
     if (ctx->ws_ema) (void)hipFree(ctx->ws_ema);
     delete ctx;
     return e == hipErrorOutOfMemory ? RVQ_ENOMEM : RVQ_EHIP;
@@ -145,6 +174,47 @@ int rvq_destroy(rvq_ctx *ctx) {
   if (ctx->ws_std) (void)hipFree(ctx->ws_std);
   if (ctx->ws_ema) (void)hipFree(ctx->ws_ema);
   delete ctx;
+  return RVQ_OK;
+}
+
+int rvq_reserve(rvq_ctx *ctx, int64_t max_rows) {
+  if (!ctx || max_rows < 0) return RVQ_EINVAL;
+  if (!ctx->cfg.scale || max_rows <= ctx->ws_rows) return RVQ_OK;
+  if (max_rows > (int64_t)1 << 40) return RVQ_EINVAL;
+  float *grown = nullptr;
+  RVQ_HIP(ctx, hipMalloc((void **)&grown, (size_t)max_rows * sizeof(float)));
+  // earlier calls on any stream may still read the old workspace
+  hipError_t e = hipDeviceSynchronize();
+  if (e == hipSuccess && ctx->ws_std) e = hipFree(ctx->ws_std);
+  if (e != hipSuccess) {
+    (void)hipFree(grown);
+    ctx->last_hip = (int)e;
+    return RVQ_EHIP;
+  }
+  ctx->ws_std = grown;
+  ctx->ws_rows = max_rows;
+  return RVQ_OK;
+}
+
+int64_t rvq_reserved_rows(const rvq_ctx *ctx) {
+  if (!ctx) return RVQ_EINVAL;
+  return ctx->cfg.scale ? ctx->ws_rows : INT64_MAX;
+}
+
+int rvq_check_kernels(rvq_ctx *ctx) {
+  if (!ctx) return RVQ_EINVAL;
+  if (!ctx->counters) return RVQ_OK;
+  unsigned long long word = 0;
+  RVQ_HIP(ctx, hipDeviceSynchronize());
+  RVQ_HIP(ctx, hipMemcpy(&word, ctx->counters + 15, sizeof(word), hipMemcpyDeviceToHost));
+  if (!word) return RVQ_OK;
+  RVQ_HIP(ctx, hipMemset(ctx->counters + 15, 0, sizeof(word)));
+  return RVQ_EKERNEL;
+}
+
+int rvq_debug_set_wait_polls(rvq_ctx *ctx, int64_t polls) {
+  if (!ctx || polls < 0 || polls > 0x7fffffffLL) return RVQ_EINVAL;
+  ctx->wait_polls = (uint32_t)polls;
   return RVQ_OK;
 }
 
@@ -193,23 +263,9 @@ int rvq_encode(rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx, int32_t sta
   if (dResidual && !aligned16(dResidual)) return RVQ_EINVAL;
   if (N > (INT64_MAX / 4) / ((int64_t)c.d > ldx ? c.d : ldx)) return RVQ_EINVAL;
   if (!ctx->have_codebooks) return RVQ_ENOCODEBOOK;
-  hipStream_t s = (hipStream_t)stream;
-  if (c.scale) {
-    if (N > ctx->ws_rows) {
-      if (ctx->ws_std) RVQ_HIP(ctx, hipFree(ctx->ws_std));
-      ctx->ws_std = nullptr;
-      ctx->ws_rows = 0;
-      RVQ_HIP(ctx, hipMalloc((void **)&ctx->ws_std, (size_t)N * sizeof(float)));
-      ctx->ws_rows = N;
-    }
-    RVQ_HIP(ctx, rvq_launch_row_std(ctx, dX, N, ldx, dStd, s));
-  }
-  const bool screen = c.dhat == 32 && c.encode_path != RVQ_PATH_EXACT;
-  if (screen)
-    RVQ_HIP(ctx, rvq_launch_encode_screen(ctx, dX, N, ldx, stage_begin, stage_end, dCodes, dResidual, s));
-  else
-    RVQ_HIP(ctx, rvq_launch_encode_exact(ctx, dX, N, ldx, stage_begin, stage_end, dCodes, dResidual, s));
-  return RVQ_OK;
+  if (c.scale && N > ctx->ws_rows) return RVQ_EWORKSPACE;
+  return encode_enqueue(ctx, dX, N, ldx, stage_begin, stage_end, dCodes, dStd, dResidual,
+                        ctx->ws_std, (hipStream_t)stream);
 }
 
 int rvq_decode(rvq_ctx *ctx, const int16_t *dCodes, const void *dStd, int64_t N,
@@ -300,10 +356,6 @@ int rvq_ema_update(rvq_ctx *ctx, int32_t stage, const float *dR, const int16_t *
   if (!ctx->have_codebooks) return RVQ_ENOCODEBOOK;
   if (M == 0) return RVQ_OK;
   hipStream_t s = (hipStream_t)stream;
-  if (!ctx->ws_ema) {  // scratch of the scatter step, allocated on first use
-    ctx->ws_ema_bytes = rvq_ema_workspace_bytes(ctx);
-    RVQ_HIP(ctx, hipMalloc((void **)&ctx->ws_ema, ctx->ws_ema_bytes));
-  }
   RVQ_HIP(ctx, rvq_launch_ema(ctx, stage, dR, dCodes, code_stride, M, decay, eps, dClusterSize,
                               dEmbedSum, s));
   RVQ_HIP(ctx, rvq_launch_prepare_codebook(ctx, stage, stage + 1, s));

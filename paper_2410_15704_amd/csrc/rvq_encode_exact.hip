@@ -70,14 +70,14 @@ __global__ __launch_bounds__(256) void encode_exact_kernel(
 
 hipError_t rvq_launch_encode_exact(const rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx,
                                    int stage_begin, int stage_end, int16_t *dCodes,
-                                   float *dResidual, hipStream_t s) {
+                                   float *dResidual, const float *std32_in, hipStream_t s) {
   const rvq_config &c = ctx->cfg;
   const int64_t V = N * ctx->G;
   const int block = 256;
   const int64_t grid64 = (V + block - 1) / block;
   if (grid64 > 0x7fffffffLL) return hipErrorInvalidValue;
   const dim3 grid((unsigned)grid64);
-  const float *std32 = c.scale ? ctx->ws_std : nullptr;
+  const float *std32 = c.scale ? std32_in : nullptr;
 #define RVQ_LAUNCH_EXACT(DH)                                                                     \
   hipLaunchKernelGGL(encode_exact_kernel<DH>, grid, dim3(block), 0, s, dX, c.in_dtype, N, ldx,   \
                      ctx->G, c.dhat, c.grouping, std32, ctx->C, c.K, c.depth, stage_begin,       \

@@ -70,9 +70,11 @@ struct ScreenArgs {
   int16_t *codes;
   float *residual;
   unsigned long long *counters;  // [0] token-stages searched by the wavefront, [1] codewords
-                                 // scored exactly, [2] groups re-scored, [3] token-stages
+                                 // scored exactly, [2] groups re-scored, [3] token-stages,
+                                 // [15] error word: bit 0 = a wait between wavefronts gave up
   int64_t N, ldx, V;
   int in_dtype, G, grouping, K, Kpad, depth, stage_begin, stage_end, tag_bits;
+  unsigned wait_polls;  // polls after which a wait between wavefronts gives up (see spin_ge)
   float kappa;
 };
 
@@ -483,6 +485,53 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
     PHASE_MARK(1);  // operand conversion
   };
 
+  // ---- resolve, step 2 (global): exact fp32 score of every candidate found in the operands that
+  // are in LDS, sum (r - c)^2 with the fp32 codeword; slot s of all four tokens is loaded in one
+  // batch, and slots beyond the first only when some token of the wavefront has them.  When the
+  // whole codebook is in LDS, a token whose only candidate this is (97 % of them) has found its
+  // codeword: the row is subtracted from the residual right away, so it is fetched once, not twice.
+  auto exact_candidates = [&](int stage) {
+#pragma unroll 1
+    for (int slot = 0; slot < SCR_CAND; ++slot) {
+      bool need = false;
+#pragma unroll
+      for (int tt = 0; tt < SCR_TT; ++tt) need = need || (nc[tt] > slot && !slow[tt]);
+      if (!__any(need)) break;
+      f32x4 cw[SCR_TT][4];
+      int kk[SCR_TT];
+#pragma unroll
+      for (int tt = 0; tt < SCR_TT; ++tt) {
+        const int cand = lds_c[(wtok + tt * 32 + p) * SCR_CAND + slot];
+        kk[tt] = (nc[tt] > slot && cand < a.K) ? cand : 0;
+        const f32x4 *crow = reinterpret_cast<const f32x4 *>(
+            a.C32 + ((int64_t)stage * a.K + kk[tt]) * 32 + 16 * h);
+#pragma unroll
+        for (int c4 = 0; c4 < 4; ++c4) cw[tt][c4] = crow[c4];
+      }
+#pragma unroll
+      for (int tt = 0; tt < SCR_TT; ++tt) {
+        const bool valid = nc[tt] > slot && !slow[tt];
+        const bool commit = single_chunk && slot == 0 && valid && nc[tt] == 1;
+        const float sel = commit ? 1.0f : 0.0f;
+        float dist = 0.f;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const float c = cw[tt][j >> 2][j & 3];
+          const float dlt = r[tt][j] - c;
+          dist = fmaf(dlt, dlt, dist);
+          r[tt][j] = fmaf(-sel, c, r[tt][j]);  // exact: sel is 0 or 1
+        }
+        dist = sum32(dist);
+        n_exact += __popcll(__ballot(valid && h == 0));
+        if (valid && (dist < bestd[tt] || (dist == bestd[tt] && kk[tt] < bestk[tt]))) {
+          bestd[tt] = dist;
+          bestk[tt] = kk[tt];
+        }
+        if (commit) done[tt] = 1;
+      }
+    }
+  };
+
   // ---- phase L of a stage: everything that reads the stage's operands in LDS
   auto lds_phase = [&](int stage) {
     for (int cbase = 0; cbase < a.Kpad; cbase += SCR_KC) {
@@ -749,51 +798,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
       PHASE_MARK(7);  // resolve: group-wide exact passes
 
       if (!single_chunk) {
-        // ---- resolve, step 2 (global): exact fp32 score of every candidate of the chunk,
-        // sum (r - c)^2 with the fp32 codeword; slot s of all four tokens is loaded in one batch,
-        // and slots beyond the first only when some token of the wavefront has them.  A token
-        // whose only candidate this is (97 % of them) has found its codeword: the row is
-        // subtracted from the residual right away, so it is fetched once, not twice.
-  #pragma unroll 1
-        for (int slot = 0; slot < SCR_CAND; ++slot) {
-          bool need = false;
-  #pragma unroll
-          for (int tt = 0; tt < SCR_TT; ++tt) need = need || (nc[tt] > slot && !slow[tt]);
-          if (!__any(need)) break;
-          f32x4 cw[SCR_TT][4];
-          int kk[SCR_TT];
-  #pragma unroll
-          for (int tt = 0; tt < SCR_TT; ++tt) {
-            const int cand = lds_c[(wtok + tt * 32 + p) * SCR_CAND + slot];
-            kk[tt] = (nc[tt] > slot && cand < a.K) ? cand : 0;
-            const f32x4 *crow = reinterpret_cast<const f32x4 *>(
-                a.C32 + ((int64_t)stage * a.K + kk[tt]) * 32 + 16 * h);
-  #pragma unroll
-            for (int c4 = 0; c4 < 4; ++c4) cw[tt][c4] = crow[c4];
-          }
-  #pragma unroll
-          for (int tt = 0; tt < SCR_TT; ++tt) {
-            const bool valid = nc[tt] > slot && !slow[tt];
-            const bool commit = single_chunk && slot == 0 && valid && nc[tt] == 1;
-            const float sel = commit ? 1.0f : 0.0f;
-            float dist = 0.f;
-  #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-              const float c = cw[tt][j >> 2][j & 3];
-              const float dlt = r[tt][j] - c;
-              dist = fmaf(dlt, dlt, dist);
-              r[tt][j] = fmaf(-sel, c, r[tt][j]);  // exact: sel is 0 or 1
-            }
-            dist = sum32(dist);
-            n_exact += __popcll(__ballot(valid && h == 0));
-            if (valid && (dist < bestd[tt] || (dist == bestd[tt] && kk[tt] < bestk[tt]))) {
-              bestd[tt] = dist;
-              bestk[tt] = kk[tt];
-            }
-            if (commit) done[tt] = 1;
-          }
-        }
-
+        exact_candidates(stage);
         if (lane < SCR_TT * 16) lds_cnt[(wtok >> 1) + lane] = 0u;  // new lists per chunk
       }
     }
@@ -803,54 +808,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
   int64_t load_next = blockIdx.x;  // chunk to load at the top of the next half-step (-1: none)
   // `next_chunk`: the chunk this wavefront takes up after the last stage (-1: none)
   auto tail_phase = [&](int stage, int64_t next_chunk) {
-    if (single_chunk) {
-      const int kc = a.Kpad;
-      (void)kc;
-      // ---- resolve, step 2 (global): exact fp32 score of every candidate of the chunk,
-      // sum (r - c)^2 with the fp32 codeword; slot s of all four tokens is loaded in one batch,
-      // and slots beyond the first only when some token of the wavefront has them.  A token
-      // whose only candidate this is (97 % of them) has found its codeword: the row is
-      // subtracted from the residual right away, so it is fetched once, not twice.
-#pragma unroll 1
-      for (int slot = 0; slot < SCR_CAND; ++slot) {
-        bool need = false;
-#pragma unroll
-        for (int tt = 0; tt < SCR_TT; ++tt) need = need || (nc[tt] > slot && !slow[tt]);
-        if (!__any(need)) break;
-        f32x4 cw[SCR_TT][4];
-        int kk[SCR_TT];
-#pragma unroll
-        for (int tt = 0; tt < SCR_TT; ++tt) {
-          const int cand = lds_c[(wtok + tt * 32 + p) * SCR_CAND + slot];
-          kk[tt] = (nc[tt] > slot && cand < a.K) ? cand : 0;
-          const f32x4 *crow = reinterpret_cast<const f32x4 *>(
-              a.C32 + ((int64_t)stage * a.K + kk[tt]) * 32 + 16 * h);
-#pragma unroll
-          for (int c4 = 0; c4 < 4; ++c4) cw[tt][c4] = crow[c4];
-        }
-#pragma unroll
-        for (int tt = 0; tt < SCR_TT; ++tt) {
-          const bool valid = nc[tt] > slot && !slow[tt];
-          const bool commit = single_chunk && slot == 0 && valid && nc[tt] == 1;
-          const float sel = commit ? 1.0f : 0.0f;
-          float dist = 0.f;
-#pragma unroll
-          for (int j = 0; j < 16; ++j) {
-            const float c = cw[tt][j >> 2][j & 3];
-            const float dlt = r[tt][j] - c;
-            dist = fmaf(dlt, dlt, dist);
-            r[tt][j] = fmaf(-sel, c, r[tt][j]);  // exact: sel is 0 or 1
-          }
-          dist = sum32(dist);
-          n_exact += __popcll(__ballot(valid && h == 0));
-          if (valid && (dist < bestd[tt] || (dist == bestd[tt] && kk[tt] < bestk[tt]))) {
-            bestd[tt] = dist;
-            bestk[tt] = kk[tt];
-          }
-          if (commit) done[tt] = 1;
-        }
-      }
-    }
+    if (single_chunk) exact_candidates(stage);
     // ---- exact search by the whole wavefront for the tokens the screen could not settle
     {
       bool any_slow = false;
@@ -934,9 +892,22 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
   // stages (tokens beyond the end are padding), so every count is reached.
   unsigned *lds_f = reinterpret_cast<unsigned *>(reinterpret_cast<char *>(smem) + SCR_LDS_BYTES - 16);
   typedef __attribute__((address_space(3))) unsigned lds_u32;
+  // A wait polls at most a.wait_polls times.  Every wavefront runs every stage, so the counts
+  // are always reached; should a future change break that, the wavefront sets the launch's error
+  // word, stops waiting for good and still runs to the end of the kernel (all of its accesses
+  // stay in bounds whatever the operands in LDS hold), instead of hanging the GPU.
+  bool gave_up = false;  // wave-uniform
   auto spin_ge = [&](int idx, unsigned target) {
     volatile lds_u32 *f = (volatile lds_u32 *)(lds_f + idx);
-    while (*f < target) __builtin_amdgcn_s_sleep(2);
+    unsigned polls = 0;
+    while (!gave_up && *f < target) {
+      if (++polls > a.wait_polls) {
+        gave_up = true;
+        if (lane == 0) atomicOr(&a.counters[15], 1ull);
+      } else {
+        __builtin_amdgcn_s_sleep(2);
+      }
+    }
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
   };
   auto signal = [&](int idx) {
@@ -1023,11 +994,11 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
 
 hipError_t rvq_launch_encode_screen(const rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx,
                                     int stage_begin, int stage_end, int16_t *dCodes,
-                                    float *dResidual, hipStream_t s) {
+                                    float *dResidual, const float *std32, hipStream_t s) {
   const rvq_config &c = ctx->cfg;
   ScreenArgs a;
   a.X = dX;
-  a.std32 = c.scale ? ctx->ws_std : nullptr;
+  a.std32 = c.scale ? std32 : nullptr;
   a.C32 = ctx->C;
   a.C16 = reinterpret_cast<const uint4 *>(ctx->C16);
   a.normp = ctx->normp;
@@ -1050,6 +1021,7 @@ hipError_t rvq_launch_encode_screen(const rvq_ctx *ctx, const void *dX, int64_t 
   a.stage_begin = stage_begin;
   a.stage_end = stage_end;
   a.tag_bits = ctx->tag_bits;
+  a.wait_polls = ctx->wait_polls;
   // one workgroup fills a CU (LDS): as many workgroups as CUs, each walking its share of the chunks
   const int64_t nchunks = (a.V + SCR_TOKENS - 1) / SCR_TOKENS;
   const int64_t grid64 = nchunks < ctx->num_cus ? nchunks : ctx->num_cus;

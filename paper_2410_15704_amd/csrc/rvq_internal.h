@@ -7,6 +7,9 @@
 
 #include "rvq.h"
 
+// polls of a wait between wavefronts before it gives up (a poll takes some 300 clocks)
+constexpr uint32_t RVQ_WAIT_POLLS_DEFAULT = 1u << 22;
+
 // largest channel-pair table (bytes) the LDS decode path keeps resident: depth * K * 8
 constexpr size_t RVQ_SPLIT_MAX_LDS = 144 * 1024;
 
@@ -41,12 +44,15 @@ struct rvq_ctx {
   // Csplit[a][i][k] = (C_i[k][2a], C_i[k][2a+1]), so the table of one channel pair is contiguous
   float *Csplit;       // [16][depth][K][2]
 
-  unsigned long long *counters;  // [4] statistics of the screen path since rvq_create
+  unsigned long long *counters;  // [16]: [0..3], [10] statistics of the screen path since
+                                 // rvq_create; [15] error word (a bounded wait gave up)
 
+  // Workspace: allocated by rvq_create / rvq_reserve only; the enqueue calls never allocate.
   float *ws_std;       // per-row fp32 std of the rows being encoded
-  int64_t ws_rows;
+  int64_t ws_rows;     // rows it holds
   float *ws_ema;       // moving-average scratch: counts [K] + sums [K][dhat] (+ partials)
   size_t ws_ema_bytes;
+  uint32_t wait_polls; // polls after which a wait between wavefronts inside a kernel gives up
 };
 
 // bits per packed code: the smallest b >= 1 with 2^b >= K; bytes of the record of one (token, group)
@@ -59,13 +65,13 @@ inline __host__ __device__ int rvq_record_bytes(int depth, int K) {
   return (depth * rvq_code_bits(K) + 7) / 8;
 }
 
-#define RVQ_HIP(ctx, call)                       \
-  do {                                           \
-    hipError_t e_ = (call);                      \
-    if (e_ != hipSuccess) {                      \
-      if (ctx) (ctx)->last_hip = (int)e_;        \
-      return RVQ_EHIP;                           \
-    }                                            \
+#define RVQ_HIP(ctx, call)                                        \
+  do {                                                            \
+    hipError_t e_ = (call);                                       \
+    if (e_ != hipSuccess) {                                       \
+      if (ctx) (ctx)->last_hip = (int)e_;                         \
+      return e_ == hipErrorOutOfMemory ? RVQ_ENOMEM : RVQ_EHIP;   \
+    }                                                             \
   } while (0)
 
 // ---- storage conversions (device) -------------------------------------------------------------
@@ -95,14 +101,16 @@ __device__ __forceinline__ uint16_t rvq_f32_to_f16_bits_sat(float v) {
 // ---- kernel launchers (each returns a hipError_t from the launch) -----------------------------
 hipError_t rvq_launch_prepare_codebook(const rvq_ctx *ctx, int stage_begin, int stage_end,
                                        hipStream_t s);
+// std32: device, float [N]: the unrounded per-row std (written by row_std, read by the encode
+// kernels); nullptr in the encode launchers means "rows are already scaled"
 hipError_t rvq_launch_row_std(const rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx,
-                              void *dStd, hipStream_t s);
+                              void *dStd, float *std32, hipStream_t s);
 hipError_t rvq_launch_encode_exact(const rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx,
                                    int stage_begin, int stage_end, int16_t *dCodes,
-                                   float *dResidual, hipStream_t s);
+                                   float *dResidual, const float *std32, hipStream_t s);
 hipError_t rvq_launch_encode_screen(const rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx,
                                     int stage_begin, int stage_end, int16_t *dCodes,
-                                    float *dResidual, hipStream_t s);
+                                    float *dResidual, const float *std32, hipStream_t s);
 // dCodes: int16 [N][G][depth] (packed == 0) or packed records [N][G][rvq_record_bytes] (packed == 1)
 // dCos / dSin: rotary tables [N][head_dim / 2] fp32, or nullptr for a plain decode
 hipError_t rvq_launch_decode(const rvq_ctx *ctx, const void *dCodes, int packed, const void *dStd,

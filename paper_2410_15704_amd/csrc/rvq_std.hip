@@ -1,4 +1,4 @@
-// Per-row standard deviation (Section 2.2: "we scale x by its standard deviation").
+// Per-row standard deviation: Section 2.2 scales every vector by its own std before grouping.
 #include "rvq_internal.h"
 
 namespace {
@@ -85,7 +85,7 @@ __global__ __launch_bounds__(256) void row_std_kernel(const void *__restrict__ X
 }  // namespace
 
 hipError_t rvq_launch_row_std(const rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx,
-                              void *dStd, hipStream_t s) {
+                              void *dStd, float *std32, hipStream_t s) {
   const rvq_config &c = ctx->cfg;
   const int rows_per_block = 4;
   const unsigned grid = (unsigned)((N + rows_per_block - 1) / rows_per_block);
@@ -96,10 +96,10 @@ hipError_t rvq_launch_row_std(const rvq_ctx *ctx, const void *dX, int64_t N, int
 #define RVQ_STD(DT)                                                                               \
   if (vec)                                                                                        \
     hipLaunchKernelGGL((row_std_kernel<DT, true>), dim3(grid), block, 0, s, dX, N, ldx, c.d,      \
-                       c.std_ddof, ctx->ws_std, dStd, c.std_dtype);                               \
+                       c.std_ddof, std32, dStd, c.std_dtype);                               \
   else                                                                                            \
     hipLaunchKernelGGL((row_std_kernel<DT, false>), dim3(grid), block, 0, s, dX, N, ldx, c.d,     \
-                       c.std_ddof, ctx->ws_std, dStd, c.std_dtype)
+                       c.std_ddof, std32, dStd, c.std_dtype)
   switch (c.in_dtype) {
     case RVQ_F32: RVQ_STD(RVQ_F32); break;
     case RVQ_BF16: RVQ_STD(RVQ_BF16); break;

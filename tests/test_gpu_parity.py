@@ -57,30 +57,39 @@ def _half_ulp_distance(a_bits, b_bits):
 
 
 def check_encode(Xs, in_dtype, d, dhat, depth, K, grouping, C32, *, path=0, sample_rows=None,
-                 std_dtype="fp32", min_equal=0.9999, mismatch_cap=None):
-    """Run rvq_encode on the GPU for all rows, the oracle on `sample_rows` (all if None)."""
+                 std_dtype="fp32", min_equal=0.9999, mismatch_cap=None, ddof=0, ldx=None,
+                 keep=False):
+    """Run rvq_encode on the GPU for all rows, the oracle on `sample_rows` (all if None).
+    `ldx` > d puts the rows into a wider device buffer (row stride ldx elements); `keep` returns
+    the quantizer and the device outputs as well (the caller closes the quantizer)."""
     torch, b = _torch(), _b()
     N = Xs.shape[0]
     q = b.Quantizer(d=d, dhat=dhat, depth=depth, K=K, grouping=grouping, in_dtype=b.DTYPES[in_dtype],
-                    out_dtype=b.F32, std_dtype=b.DTYPES[std_dtype], encode_path=path)
+                    out_dtype=b.F32, std_dtype=b.DTYPES[std_dtype], encode_path=path, std_ddof=ddof)
     q.set_codebooks(torch.from_numpy(C32).cuda())
     dX = _to_dev(Xs, in_dtype)
+    if ldx is not None:
+        wide = torch.full((N, ldx), 7.0, dtype=dX.dtype, device="cuda")  # the padding is never read
+        wide[:, :d] = dX
+        dX = wide[:, :d]
+        assert dX.stride(0) == ldx
     codes, std, res = q.encode(dX, want_residual=True)
     torch.cuda.synchronize()
     rows = np.arange(N) if sample_rows is None else np.asarray(sample_rows)
-    g_codes = codes.cpu().numpy()[rows].astype(np.int32)
-    g_std = std.float().cpu().numpy()[rows].astype(np.float64)
-    g_res = res.cpu().numpy()[rows].astype(np.float64)
+    rt = torch.from_numpy(rows).cuda()
+    g_codes = codes[rt].cpu().numpy().astype(np.int32)
+    g_std = std[rt].float().cpu().numpy().astype(np.float64)
+    g_res = res[rt].cpu().numpy().astype(np.float64)
     Xw = synth.widen(Xs[rows], in_dtype)
     C64 = C32.astype(np.float64)
-    ref = oracle.encode(Xw, C64, dhat, grouping, want_residual=True, want_gap=True)
+    ref = oracle.encode(Xw, C64, dhat, grouping, want_residual=True, want_gap=True, ddof=ddof)
 
     # std
     if std_dtype == "fp32":
         np.testing.assert_allclose(g_std, ref["std"], rtol=2e-6)
     else:
         want = ref["std"].astype(np.float16).view(np.uint16)
-        got = std.cpu().numpy()[rows].view(np.uint16)
+        got = std[rt].cpu().numpy().view(np.uint16)
         assert _half_ulp_distance(got, want).max() <= 1
 
     # (i) agreement with the free-running oracle codes
@@ -93,7 +102,7 @@ def check_encode(Xs, in_dtype, d, dhat, depth, K, grouping, C32, *, path=0, samp
     else:
         assert neq.sum() <= max(2, int(entries * 1e-4))
     # (ii) every GPU code is (nearly) nearest for the prefix it follows
-    excess, rn2 = oracle.prefix_excess(Xw, C64, dhat, g_codes, grouping)
+    excess, rn2 = oracle.prefix_excess(Xw, C64, dhat, g_codes, grouping, ddof=ddof)
     bad = excess > NEAR_TIE * rn2 + 1e-300
     assert not bad.any(), f"{bad.sum()} GPU codes are not near-nearest (max excess/r2 " \
                           f"{(excess / np.maximum(rn2, 1e-300)).max():.3e})"
@@ -114,8 +123,12 @@ def check_encode(Xs, in_dtype, d, dhat, depth, K, grouping, C32, *, path=0, samp
     scale = np.sqrt(np.maximum(ref["rnorm2"][:, :, 0], 1e-300))[:, :, None]
     assert np.max(np.abs(g_res - ref["residual"])[same] / np.broadcast_to(scale, g_res.shape)[same],
                   initial=0.0) < 2e-5
+    r = dict(mismatch=int(neq.sum()), entries=int(entries), mse=float(mse_gpu))
+    if keep:
+        r.update(q=q, codes=codes, std=std, dX=dX, ref=ref, rows=rows)
+        return r
     q.close()
-    return dict(mismatch=int(neq.sum()), entries=int(entries), mse=float(mse_gpu))
+    return r
 
 
 def check_decode(codes_np, std_np, std_dtype, C32, d, dhat, grouping, *, depth_used=None,
@@ -203,15 +216,9 @@ def test_encode_std_in_half_precision_and_bessel(gpu_device):
     X = synth.gaussian_rows(257, 128, seed=99, dtype="fp32", outliers=3)
     C = _codebooks_from_samples(X.astype(np.float64), 32, oracle.STRIDED, 4, 128, seed=3)
     check_encode(X, "fp32", 128, 32, 4, 128, oracle.STRIDED, C, std_dtype="fp16")
-    # ddof = 1
-    q = b.Quantizer(d=128, dhat=32, depth=4, K=128, grouping=b.STRIDED, std_ddof=1,
-                    std_dtype=b.F32)
-    q.set_codebooks(torch.from_numpy(C).cuda())
-    codes, std, _ = q.encode(torch.from_numpy(X).cuda())
-    ref = oracle.encode(X.astype(np.float64), C.astype(np.float64), 32, oracle.STRIDED, ddof=1)
-    np.testing.assert_allclose(std.cpu().numpy(), ref["std"], rtol=2e-6)
-    assert (codes.cpu().numpy() != ref["codes"]).mean() < 1e-3
-    q.close()
+    # the std with divisor d - 1, held to the same bar (codes, near-tie proof, error, std)
+    check_encode(X, "fp32", 128, 32, 4, 128, oracle.STRIDED, C, ddof=1)
+    check_encode(X, "fp32", 128, 32, 4, 128, oracle.STRIDED, C, ddof=1, std_dtype="fp16")
 
 
 def test_encode_degenerate_rows(gpu_device):
