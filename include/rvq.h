@@ -54,6 +54,7 @@ extern "C" {
 #define RVQ_MAX_DEPTH 16
 #define RVQ_MAX_K 32768 /* codes are stored as int16 */
 #define RVQ_DEFAULT_ROWS 131072 /* rows per rvq_encode call a new context is ready for */
+#define RVQ_STATIC_MAX_ROWS 1048576 /* rows per rvq_encode_static call */
 
 enum rvq_dtype { RVQ_F32 = 0, RVQ_BF16 = 1, RVQ_F16 = 2 };
 enum rvq_grouping {
@@ -128,6 +129,22 @@ int rvq_get_codebooks(rvq_ctx *ctx, float *dC, void *stream);
  */
 int rvq_encode(rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx, int32_t stage_begin,
                int32_t stage_end, int16_t *dCodes, void *dStd, float *dResidual, void *stream);
+
+/*
+ * rvq_encode for callers that cannot allocate device memory and cannot rely on a context's
+ * allocated workspace either: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, outputs (bit for bit) and errors as rvq_encode; the 4 bytes
+ * per row of scratch that rvq_encode keeps in the context's workspace live here in a device array
+ * of fixed size that is part of the library image (4 MiB per GPU, held until the process ends),
+ * so the call allocates nothing.  Limits: with cfg.scale == 1, N <= RVQ_STATIC_MAX_ROWS, else
+ * RVQ_EWORKSPACE and nothing is enqueued.  All contexts on one GPU share that array: calls that
+ * may overlap on one GPU (two streams, or two contexts) race on it and must be ordered by the
+ * caller.  The array needs no clearing between calls: every entry a call reads it has written
+ * itself.
+ */
+int rvq_encode_static(rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx, int32_t stage_begin,
+                      int32_t stage_end, int16_t *dCodes, void *dStd, float *dResidual,
+                      void *stream);
 
 /*
  * Decode (Section 2.2, last sentence): out[n][c(g,j)] = std[n] * sum_{i < depth_used}

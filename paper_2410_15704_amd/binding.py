@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(HERE, "librvq.so")
 RVQ_OK, RVQ_EINVAL, RVQ_ENOCODEBOOK, RVQ_EHIP, RVQ_ENOMEM = 0, -1, -2, -3, -4
 RVQ_EWORKSPACE, RVQ_EKERNEL = -5, -6
 DEFAULT_ROWS = 131072
+STATIC_MAX_ROWS = 1048576
 F32, BF16, F16 = 0, 1, 2
 CONTIGUOUS, STRIDED = 0, 1
 PATH_AUTO, PATH_EXACT, PATH_SCREEN = 0, 1, 2
@@ -29,7 +30,7 @@ EXPORTS = ("rvq_create", "rvq_destroy", "rvq_set_codebooks", "rvq_get_codebooks"
            "rvq_decode", "rvq_ema_update", "rvq_strerror", "rvq_last_hip_error", "rvq_version",
            "rvq_get_counters", "rvq_packed_record_bytes", "rvq_pack_codes", "rvq_unpack_codes",
            "rvq_decode_packed", "rvq_decode_rope", "rvq_reserve", "rvq_reserved_rows",
-           "rvq_check_kernels", "rvq_debug_set_wait_polls")
+           "rvq_check_kernels", "rvq_debug_set_wait_polls", "rvq_encode_static")
 
 
 class rvq_config(ctypes.Structure):
@@ -50,6 +51,7 @@ def _load():
     lib.rvq_set_codebooks.argtypes = [vp, vp, vp]
     lib.rvq_get_codebooks.argtypes = [vp, vp, vp]
     lib.rvq_encode.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp, vp, vp]
+    lib.rvq_encode_static.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp, vp, vp]
     lib.rvq_decode.argtypes = [vp, vp, vp, i64, i32, vp, i64, vp]
     lib.rvq_ema_update.argtypes = [vp, i32, vp, vp, i64, i64, f32, f32, vp, vp, vp]
     lib.rvq_get_counters.argtypes = [vp, ctypes.POINTER(ctypes.c_int64)]
@@ -166,6 +168,12 @@ def rvq_get_codebooks(ctx, dC, stream=None):
 def rvq_encode(ctx, dX, N, ldx, stage_begin, stage_end, dCodes, dStd, dResidual=None, stream=None):
     return _chk(lib.rvq_encode(ctx, _ptr(dX), N, ldx, stage_begin, stage_end, _ptr(dCodes),
                                _ptr(dStd), _ptr(dResidual), _stream(stream)), ctx)
+
+
+def rvq_encode_static(ctx, dX, N, ldx, stage_begin, stage_end, dCodes, dStd, dResidual=None,
+                      stream=None):
+    return _chk(lib.rvq_encode_static(ctx, _ptr(dX), N, ldx, stage_begin, stage_end, _ptr(dCodes),
+                                      _ptr(dStd), _ptr(dResidual), _stream(stream)), ctx)
 
 
 def rvq_decode(ctx, dCodes, dStd, N, depth_used, dOut, ldo, stream=None):

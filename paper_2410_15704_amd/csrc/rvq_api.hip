@@ -5,7 +5,34 @@
 
 #include "rvq_internal.h"
 
+// Scratch of rvq_encode_static: the unrounded fp32 std of every row of one call.  A file-scope
+// device array, so the entry point needs no allocation; every GPU the library runs on holds its
+// own copy until the process ends.  In host code the name below is only a handle for
+// hipGetSymbolAddress: kernels and copies are given the per-device address that call returns.
+static __device__ __align__(256) float scratch[RVQ_STATIC_MAX_ROWS];
+
 namespace {
+
+constexpr int MAX_DEVICES = 64;
+float *g_scratch_ptr[MAX_DEVICES];  // device address of `scratch` on each device, once looked up
+
+// Looks up, once per device and with that device current, where `scratch` lives there.
+hipError_t scratch_address(int device, float **out) {
+  if (device < 0 || device >= MAX_DEVICES) return hipErrorInvalidDevice;
+  if (!g_scratch_ptr[device]) {
+    int cur = -1;
+    hipError_t e = hipGetDevice(&cur);
+    if (e != hipSuccess) return e;
+    if (cur != device) return hipErrorInvalidDevice;
+    float *ptr = nullptr;
+    e = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[device] = ptr;
+  }
+  *out = g_scratch_ptr[device];
+  return hipSuccess;
+}
 
 bool valid_dtype(int32_t t) { return t == RVQ_F32 || t == RVQ_BF16 || t == RVQ_F16; }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -125,6 +152,8 @@ int rvq_create(rvq_ctx **out, const rvq_config *cfg) {
     if (e == hipSuccess && cb <= RVQ_SPLIT_MAX_LDS * 16)
       e = hipMalloc((void **)&ctx->Csplit, cb);
   }
+  ctx->static_std = nullptr;
+  if (e == hipSuccess) e = scratch_address(ctx->device, &ctx->static_std);
   // workspace of the enqueue calls: they never allocate
   if (e == hipSuccess && cfg->scale) {
     e = hipMalloc((void **)&ctx->ws_std, (size_t)RVQ_DEFAULT_ROWS * sizeof(float));
@@ -266,6 +295,27 @@ int rvq_encode(rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx, int32_t sta
   if (c.scale && N > ctx->ws_rows) return RVQ_EWORKSPACE;
   return encode_enqueue(ctx, dX, N, ldx, stage_begin, stage_end, dCodes, dStd, dResidual,
                         ctx->ws_std, (hipStream_t)stream);
+}
+
+int rvq_encode_static(rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx, int32_t stage_begin,
+                      int32_t stage_end, int16_t *dCodes, void *dStd, float *dResidual,
+                      void *stream) {
+  if (!ctx || N < 0) return RVQ_EINVAL;
+  const rvq_config &c = ctx->cfg;
+  if (stage_begin < 0 || stage_end > c.depth || stage_begin >= stage_end) return RVQ_EINVAL;
+  if (ldx < c.d) return RVQ_EINVAL;
+  if (N == 0) return ctx->have_codebooks ? RVQ_OK : RVQ_ENOCODEBOOK;
+  if (!dX || !dCodes || !aligned16(dX) || !aligned16(dCodes)) return RVQ_EINVAL;
+  if (c.scale && (!dStd || !aligned16(dStd))) return RVQ_EINVAL;
+  if (dResidual && !aligned16(dResidual)) return RVQ_EINVAL;
+  if (N > (INT64_MAX / 4) / ((int64_t)c.d > ldx ? c.d : ldx)) return RVQ_EINVAL;
+  if (!ctx->have_codebooks) return RVQ_ENOCODEBOOK;
+  if (c.scale && N > RVQ_STATIC_MAX_ROWS) return RVQ_EWORKSPACE;
+  if (c.scale && !ctx->static_std) return RVQ_EHIP;
+  // every row's std is written by the first kernel before the second reads it: nothing of an
+  // earlier call is carried over and nothing has to be cleared
+  return encode_enqueue(ctx, dX, N, ldx, stage_begin, stage_end, dCodes, dStd, dResidual,
+                        ctx->static_std, (hipStream_t)stream);
 }
 
 int rvq_decode(rvq_ctx *ctx, const int16_t *dCodes, const void *dStd, int64_t N,

@@ -52,6 +52,7 @@ struct rvq_ctx {
   int64_t ws_rows;     // rows it holds
   float *ws_ema;       // moving-average scratch: counts [K] + sums [K][dhat] (+ partials)
   size_t ws_ema_bytes;
+  float *static_std;   // this device's address of the file-scope scratch of rvq_encode_static
   uint32_t wait_polls; // polls after which a wait between wavefronts inside a kernel gives up
 };
 
