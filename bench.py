@@ -44,6 +44,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-decode-stream", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-extra-workloads", action="store_true",
+                    help="skip the workload 4 and workload 5 legs")
     ap.add_argument("--decode-slices", type=int, default=64)
     ap.add_argument("--cpu-rows", type=int, default=32768)
     ap.add_argument("--encode-path", type=int, default=0)
@@ -235,6 +237,115 @@ def run_decode_stream(args):
                               avg_launch_ms=ms / S))
 
 
+def run_workload5(args):
+    """Workload 5 (long-context MHA): N = 131072 rows x 4096 channels fp16, strided groups (128 per
+    row), depth 8, K = 4096: encode, decode, reconstruction error after 1..8 stages.  The rows are
+    drawn on the device (torch's seeded generator) with the workload's recipe, N(0,1) times a
+    per-channel scale min(100, Pareto(1.5))."""
+    import numpy as np
+    import torch
+
+    from paper_2410_15704_amd import binding as b
+    from paper_2410_15704_amd import synth, train
+
+    N, d, dhat, depth, K = 131072, 4096, 32, 8, 4096
+    G, V = d // dhat, N * (d // dhat)
+    _, sigma = synth.heavy_tailed_keys(rows=slice(0, 1))  # the workload's seeded channel scales
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.BASE_SEED + 5)
+    dX = torch.empty((N, d), dtype=torch.float16, device="cuda")
+    sg = torch.from_numpy(sigma).cuda()
+    for a in range(0, N, 16384):
+        dX[a:a + 16384] = (torch.randn((16384, d), device="cuda", generator=gen) * sg).half()
+    Zhead = train.scaled_groups(dX[:512], d=d, dhat=dhat, grouping=b.STRIDED, in_dtype=b.F16)
+    C = train.sample_init_codebooks(Zhead, depth, K, seed=synth.BASE_SEED + 5)
+    del Zhead
+    q = b.Quantizer(d=d, dhat=dhat, depth=depth, K=K, grouping=b.STRIDED, in_dtype=b.F16,
+                    out_dtype=b.F16, std_dtype=b.F16)
+    q.set_codebooks(C)
+    codes = torch.empty((N, G, depth), dtype=torch.int16, device="cuda")
+    std = torch.empty((N,), dtype=torch.float16, device="cuda")
+    out = torch.empty((N, d), dtype=torch.float16, device="cuda")
+    a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            fn()
+        z.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(z) / reps
+
+    enc_ms = timed(lambda: b.rvq_encode(q.ctx, dX, N, d, 0, depth, codes, std, None), 3)
+    dec_ms = timed(lambda: b.rvq_decode(q.ctx, codes, std, N, depth, out, d), 5)
+    mse = []
+    for k in range(1, depth + 1):
+        b.rvq_decode(q.ctx, codes, std, N, k, out, d)
+        acc = 0.0
+        for r0 in range(0, N, 16384):
+            acc += float(((dX[r0:r0 + 16384].float() - out[r0:r0 + 16384].float()) ** 2).sum(dtype=torch.float64))
+        mse.append(acc / (N * d))
+    flops = 2.0 * dhat * K * depth * V
+    dec_bytes = N * (G * depth * 2 + 2 + d * 2)
+    q.close()
+    return dict(workload="workload 5: N=131072 x 4096 ch fp16, strided, 128 groups, depth 8, K=4096",
+                vectors=V, encode_ms=enc_ms, encode_Mvec_s=V / (enc_ms * 1e-3) / 1e6,
+                encode_tflops=flops / (enc_ms * 1e-3) / 1e12,
+                encode_frac_of_mfma_peak=flops / (enc_ms * 1e-3) / 1e12 / PEAK_MFMA_16BIT_TFLOPS,
+                decode_ms=dec_ms, decode_GBs=dec_bytes / (dec_ms * 1e-3) / 1e9,
+                decode_frac_of_hbm_peak=dec_bytes / (dec_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                mse_per_depth=mse, mean_square_of_input=float((dX[:16384].float() ** 2).mean()))
+
+
+def run_workload4(args):
+    """Workload 4 (codebook learning): 1,048,576 mixture vectors, depth 8, K = 2048, stage by stage,
+    10 (assign, update) rounds per stage + the assignment that forms the residuals; time per pass
+    split into the assignment (rvq_encode over one stage) and the update (rvq_ema_update: scatter,
+    reduction of the partial histograms, blend, refresh of the stage's derived copies)."""
+    import torch
+
+    from paper_2410_15704_amd import synth, train
+
+    M, depth, K, iters = 1048576, 8, 2048, 10
+    dR = torch.from_numpy(synth.gaussian_mixture(M)).cuda()
+
+    class Timers:
+        def __init__(self):
+            self.ev, self.open = {}, {}
+
+        def start(self, name):
+            e = torch.cuda.Event(enable_timing=True)
+            e.record()
+            self.open[name] = e
+
+        def stop(self, name):
+            e = torch.cuda.Event(enable_timing=True)
+            e.record()
+            self.ev.setdefault(name, []).append((self.open.pop(name), e))
+
+        def mean_ms(self, name):
+            return sum(x.elapsed_time(y) for x, y in self.ev[name]) / len(self.ev[name])
+
+    train.ema_train_sequential(dR, depth, K, 1, 0.99, 1e-5, seed=synth.BASE_SEED + 4)  # warm-up
+    tm = Timers()
+    a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    a.record()
+    train.ema_train_sequential(dR, depth, K, iters, 0.99, 1e-5, seed=synth.BASE_SEED + 4, timers=tm)
+    z.record()
+    torch.cuda.synchronize()
+    assign_ms, update_ms = tm.mean_ms("assign"), tm.mean_ms("update")
+    return dict(workload="workload 4: 1,048,576 vectors of 32, depth 8, K=2048, 10 rounds per stage, "
+                         "decay 0.99, eps 1e-5, stage by stage",
+                passes=depth * iters, schedule_ms=a.elapsed_time(z), assign_ms_per_pass=assign_ms,
+                update_ms_per_pass=update_ms,
+                assign_Mvec_s=M / (assign_ms * 1e-3) / 1e6,
+                assign_frac_of_mfma_peak=2.0 * 32 * K * M / (assign_ms * 1e-3) / 1e12 / PEAK_MFMA_16BIT_TFLOPS,
+                update_GBs=M * 130 / (update_ms * 1e-3) / 1e9)
+
+
 def run_cpu_baseline(args):
     """The fp64 oracle, as it stands, on a bounded sample of workload 2 (encode + decode)."""
     import numpy as np
@@ -351,6 +462,9 @@ def main():
     }
     if not args.no_decode_stream:
         line["decode_stream"] = run_decode_stream(args)
+    if not args.no_extra_workloads:
+        line["workload5"] = run_workload5(args)
+        line["workload4"] = run_workload4(args)
     line["cpu_baseline"] = None if args.no_cpu else run_cpu_baseline(args)
     print(json.dumps(line))
 
