@@ -31,11 +31,17 @@
 // codeword, so stages never round-trip through memory (the fusion Section 3 of the paper
 // describes for its own kernel).
 //
-// Work decomposition: a chunk = 8 wavefronts x 4 token tiles x 32 tokens = 1024 group vectors;
-// one workgroup per CU (LDS admits no second) walks the chunks blockIdx.x, blockIdx.x +
-// gridDim.x, ...; LDS holds one stage (up to 2048 codewords = 128 KiB of fp16 operands + 8 KiB
-// of norms); larger codebooks are swept in pieces of 2048 with the resolve step run per piece.
-// A token is split over the lane pair (p, p + 32): each lane owns 16 of its 32 channels.
+// Work decomposition: a chunk = 8 wavefronts x 128 tokens = 1024 group vectors; one workgroup
+// per CU (LDS admits no second) walks the chunks blockIdx.x, blockIdx.x + gridDim.x, ...; LDS
+// holds one stage (up to 2048 codewords = 128 KiB of fp16 operands + 8 KiB of norms); larger
+// codebooks are swept in pieces of 2048 with the resolve step run per piece.
+// Every lane OWNS two tokens (one in each half of the wavefront's 128): their 32 fp32 residual
+// channels and their fp16 copy live in that lane for all stages, so everything of the resolve
+// step is lane-local.  Only the matrix-core sweep wants another arrangement (a token tile of 32
+// tokens spread over lane pairs (p, p + 32), 16 channels each); v_permlane32_swap, which trades
+// the upper half of one register for the lower half of another, turns the fp16 copy into that
+// arrangement before the sweep (one instruction per register pair) and the tracked minima back
+// into the owner's lane after it.
 #include "rvq_internal.h"
 
 namespace {
@@ -138,16 +144,6 @@ __device__ __forceinline__ float dot8(const uint4 w, const half8 b, float acc) {
 #define PHASE_MARK(i) do { } while (0)
 #endif
 
-// rotate a per-token-tile array by one entry: lets a compact, non-unrolled loop work on entry 0
-// SCR_TT times instead of unrolling its body (the unrolled resolve code did not fit the
-// instruction cache)
-#define ROT4(x)                                                   \
-  do {                                                            \
-    auto t_ = x[0];                                               \
-    _Pragma("unroll") for (int i_ = 0; i_ + 1 < SCR_TT; ++i_) x[i_] = x[i_ + 1]; \
-    x[SCR_TT - 1] = t_;                                           \
-  } while (0)
-
 // Exact nearest codeword of one vector among the K codewords of a stage, by the whole wavefront
 // (every lane passes the same vector; two codewords per lane in flight; ties to the smallest
 // index).  Kept out of line: it is needed for 0.02 % of the searches, and inlined its 100
@@ -230,7 +226,7 @@ __device__ __noinline__ int exact_best_of_lanes(const float *__restrict__ Cs, co
   tau##d = min3f(tau##d, tau##e, acc[15]);
 #define SWEEP_R2(tau, TT, tile_id, Agv)                      \
   tau = fminf(tau, tau##d);                                  \
-  tau = fmaf(-g1[TT], Agv, tau); /* lower bound on the exact scores of the group */ \
+  tau = fmaf(-g1t[TT], Agv, tau); /* lower bound on the exact scores of the group */ \
   tau = __uint_as_float((__float_as_uint(tau) & tag_mask_v) | (tile_id)); \
   m3[TT] = med3f(m2[TT], m3[TT], tau);                       \
   m2[TT] = med3f(m1[TT], m2[TT], tau);                       \
@@ -307,6 +303,25 @@ __device__ __noinline__ int exact_best_of_lanes(const float *__restrict__ Cs, co
     Agp = Agc;                                                                                  \
   }
 
+// trade the upper half (lanes 32..63) of a for the lower half (lanes 0..31) of b
+__device__ __forceinline__ void swap_halves(unsigned &a, unsigned &b) {
+  const auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+  a = r[0];
+  b = r[1];
+}
+__device__ __forceinline__ void swap_halves(float &a, float &b) {
+  unsigned ua = __float_as_uint(a), ub = __float_as_uint(b);
+  swap_halves(ua, ub);
+  a = __uint_as_float(ua);
+  b = __uint_as_float(ub);
+}
+__device__ __forceinline__ float dot2w(unsigned w, unsigned b, float acc) {
+  return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, w), __builtin_bit_cast(half2v, b), acc, false);
+}
+
+constexpr int SCR_DT = 2;          // double tiles (64 tokens, one per lane) per wavefront
+constexpr int SCR_WTOK = 64 * SCR_DT;  // tokens per wavefront
+
 template <int DT>
 __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const ScreenArgs a) {
 #ifdef RVQ_PHASE_CLOCKS
@@ -319,17 +334,17 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
   float *lds_g = lds_n + SCR_KC;                                    // SCR_KC / 16 group bounds
   uint16_t *lds_p = reinterpret_cast<uint16_t *>(lds_g + SCR_KC / 16);  // position -> codeword
   uint16_t *lds_c = lds_p + SCR_KC;  // [token of the workgroup][SCR_CAND] candidate codewords
-  // candidates found per token: two 16-bit counts per word, bumped with LDS atomics
+  // candidates found per token: two 16-bit counts per word; the owner keeps its count in a
+  // register and publishes it here only when other lanes have to append (queued groups)
   unsigned *lds_cnt = reinterpret_cast<unsigned *>(lds_c + SCR_TOKENS * SCR_CAND);
   // per-wavefront queue of (token, group) pairs waiting for a re-score: 64 bytes of fp16
-  // residual (two lanes x 32 bytes) and 8 bytes of bookkeeping per entry
+  // residual and 8 bytes of bookkeeping per entry
   uint4 *lds_qB = reinterpret_cast<uint4 *>(lds_cnt + SCR_TOKENS / 2);
   uint2 *lds_qM = reinterpret_cast<uint2 *>(lds_qB + SCR_WAVES * SCR_QCAP * 4);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int p = lane & 31;
   const int h = lane >> 5;
   // A workgroup walks the chunks of SCR_TOKENS vectors blockIdx.x, blockIdx.x + gridDim.x, ...;
   // vbase is the first vector of this wavefront in the chunk it is working on (the two teams may
@@ -337,35 +352,34 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
   const int64_t nchunks_all = (a.V + SCR_TOKENS - 1) / SCR_TOKENS;
   const int nmy = (int)((nchunks_all - blockIdx.x + gridDim.x - 1) / gridDim.x);  // chunks of this workgroup
   int64_t vbase = 0;
-  const int wtok = wave * (SCR_TT * 32);  // first token slot of this wavefront in the workgroup
+  const int wtok = wave * SCR_WTOK;  // first token slot of this wavefront in the workgroup
   uint4 *qB = lds_qB + wave * SCR_QCAP * 4;
   uint2 *qM = lds_qM + wave * SCR_QCAP;
 
-  // ---- load this lane's 16 channels of its 4 tokens, scaled by the row std (Section 2.2)
-  float r[SCR_TT][16];
+  // ---- the 32 channels of this lane's two tokens, scaled by the row std (Section 2.2)
+  float r[SCR_DT][32];
   auto load_chunk = [&](int64_t chunk) {
-    vbase = chunk * SCR_TOKENS + wave * (SCR_TT * 32);
+    vbase = chunk * SCR_TOKENS + wtok;
 #pragma unroll
-    for (int tt = 0; tt < SCR_TT; ++tt) {
-      // no branch around the loads, so that all 16 of a token are in flight together: a vector
+    for (int k = 0; k < SCR_DT; ++k) {
+      // no branch around the loads, so that all 32 of a token are in flight together: a vector
       // beyond the end reads the last vector (V >= 1) and is set to zero afterwards
-      const int64_t v = vbase + tt * 32 + p;
+      const int64_t v = vbase + k * 64 + lane;
       const bool valid = v < a.V;
       const int64_t vc = valid ? v : a.V - 1;
       const int64_t n = vc / a.G;
       const int g = (int)(vc - n * a.G);
       const float sd = a.std32 ? a.std32[n] : 1.0f;
-      float x[16];
+      float x[32];
 #pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        const int dim = 16 * h + j;
-        const int64_t ch = a.grouping == RVQ_CONTIGUOUS ? (int64_t)g * 32 + dim : (int64_t)dim * a.G + g;
+      for (int j = 0; j < 32; ++j) {
+        const int64_t ch = a.grouping == RVQ_CONTIGUOUS ? (int64_t)g * 32 + j : (int64_t)j * a.G + g;
         x[j] = rvq_load_in<DT>(a.X, n * a.ldx + ch);
       }
 #pragma unroll
-      for (int j = 0; j < 16; ++j) {
+      for (int j = 0; j < 32; ++j) {
         const float xv = valid ? x[j] : 0.f;
-        r[tt][j] = a.std32 ? xv / sd : xv;
+        r[k][j] = a.std32 ? xv / sd : xv;
       }
     }
   };
@@ -373,13 +387,13 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
   auto store_chunk = [&]() {
     if (a.residual) {
 #pragma unroll
-      for (int tt = 0; tt < SCR_TT; ++tt) {
-        const int64_t v = vbase + tt * 32 + p;
+      for (int k = 0; k < SCR_DT; ++k) {
+        const int64_t v = vbase + k * 64 + lane;
         if (v < a.V) {
-          f32x4 *dst = reinterpret_cast<f32x4 *>(a.residual + v * 32 + 16 * h);
+          f32x4 *dst = reinterpret_cast<f32x4 *>(a.residual + v * 32);
 #pragma unroll
-          for (int c4 = 0; c4 < 4; ++c4) {
-            const f32x4 w = {r[tt][c4 * 4 + 0], r[tt][c4 * 4 + 1], r[tt][c4 * 4 + 2], r[tt][c4 * 4 + 3]};
+          for (int c4 = 0; c4 < 8; ++c4) {
+            const f32x4 w = {r[k][c4 * 4 + 0], r[k][c4 * 4 + 1], r[k][c4 * 4 + 2], r[k][c4 * 4 + 3]};
             dst[c4] = w;
           }
         }
@@ -431,15 +445,19 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
   // there every wavefront is in team 0.
   const int team = (single_chunk && wave >= SCR_WAVES / 2) ? 1 : 0;
 
-  // ---- per-stage state of this wavefront's tokens
-  half8 B0[SCR_TT], B1[SCR_TT];  // fp16 residual (matrix-core B operands)
-  float g1[SCR_TT];     // token part of the error bound: e_k = g1 ||2c|| + k4 ||2c||^2 + g0
-  float g0[SCR_TT];     // ||fp16(r)|| * (largest norm of codeword elements dropped to zero)
-  int slow[SCR_TT];     // token goes to the exact wavefront search
-  float bestd[SCR_TT];  // exact distance and index of the best candidate scored so far
-  int bestk[SCR_TT];
-  int done[SCR_TT];     // the codeword has already been subtracted from the residual
-  int nc[SCR_TT];       // candidates found for the token (the list itself is in LDS)
+  // ---- per-stage state of this lane's two tokens
+  // fp16 residual as packed pairs: [0..7] channels 0..15, [8..15] channels 16..31 of the lane's own
+  // token.  During the sweep (and only then) the upper half of [j] and the lower half of [8 + j]
+  // have changed places, which makes [0..7] the matrix-core B operands of token tile 2k (tokens
+  // owned by lanes 0..31) and [8..15] those of token tile 2k + 1.
+  unsigned Bw[SCR_DT][16];
+  float g1[SCR_DT];     // token part of the error bound: e_k = g1 ||2c|| + k4 ||2c||^2 + g0
+  float g0[SCR_DT];     // ||fp16(r)|| * (largest norm of codeword elements dropped to zero)
+  int slow[SCR_DT];     // token goes to the exact wavefront search
+  float bestd[SCR_DT];  // exact distance and index of the best candidate scored so far
+  int bestk[SCR_DT];
+  int done[SCR_DT];     // the codeword has already been subtracted from the residual
+  int nc[SCR_DT];       // candidates found for the token (the list itself is in LDS)
 
   // fp16 operands and error bounds of `stage` from the current residuals
   auto convert = [&](int stage) {
@@ -448,45 +466,44 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
     const float Fdrop = a.stats[stage * 8 + 2];
     const float Tscale = a.stats[stage * 8 + 4];  // power of two applied to the residuals
     const float tiny = 6.103515625e-5f / Tscale;  // below this the scaled value is no normal half
-
-    // ---- fp16 B operands and the per-token error bound
 #pragma unroll
-    for (int tt = 0; tt < SCR_TT; ++tt) {
-      bestd[tt] = INFINITY;
-      bestk[tt] = 0;
-      done[tt] = 0;
+    for (int k = 0; k < SCR_DT; ++k) {
+      bestd[k] = INFINITY;
+      bestk[k] = 0;
+      done[k] = 0;
+      nc[k] = 0;
       float s_q = 0.f, s_d = 0.f;
 #pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        const float x = r[tt][j] * Tscale;  // exact
-        const _Float16 hx = fabsf(r[tt][j]) < tiny ? (_Float16)0.f : (_Float16)x;
-        if (j < 8) B0[tt][j] = hx;
-        else B1[tt][j - 8] = hx;
-        const float xr = (float)hx;
-        const float dx = x - xr;  // exact
-        s_q = fmaf(xr, xr, s_q);
-        s_d = fmaf(dx, dx, s_d);
+      for (int j = 0; j < 32; j += 2) {
+        _Float16 hx[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const float x = r[k][j + e] * Tscale;  // exact
+          hx[e] = fabsf(r[k][j + e]) < tiny ? (_Float16)0.f : (_Float16)x;
+          const float xr = (float)hx[e];
+          const float dx = x - xr;  // exact
+          s_q = fmaf(xr, xr, s_q);
+          s_d = fmaf(dx, dx, s_d);
+        }
+        const half2v pr = {hx[0], hx[1]};
+        Bw[k][j >> 1] = __builtin_bit_cast(unsigned, pr);
       }
-      s_q = sum32(s_q);
-      s_d = sum32(s_d);
       const float nq = sqrtf(s_q) * 1.000001f;
       const float nd = sqrtf(s_d) * 1.000001f;
-      g1[tt] = (nd + (rho + a.kappa * (1.0f + rho)) * nq) * 1.000001f;
-      g0[tt] = nq * Fdrop * 1.000001f;
-      // an element beyond the half range turns s_q into infinity
+      g1[k] = (nd + (rho + a.kappa * (1.0f + rho)) * nq) * 1.000001f;
+      g0[k] = nq * Fdrop * 1.000001f;
+      // an element beyond the half range turns s_q into infinity (or the sum into a NaN)
 #ifdef RVQ_FORCE_SLOW
-      slow[tt] = 1;
+      slow[k] = 1;
 #else
-      slow[tt] = (!usable || !(s_q < 3.6e9f)) ? 1 : 0;
+      slow[k] = (!usable || (__float_as_uint(s_q) & 0x7fffffffu) >= 0x4f5693a4u /* 3.6e9f */) ? 1 : 0;
 #endif
     }
-    if (lane < SCR_TT * 16) lds_cnt[(wtok >> 1) + lane] = 0u;  // this wavefront's candidate counts
-
     PHASE_MARK(1);  // operand conversion
   };
 
   // ---- resolve, step 2 (global): exact fp32 score of every candidate found in the operands that
-  // are in LDS, sum (r - c)^2 with the fp32 codeword; slot s of all four tokens is loaded in one
+  // are in LDS, sum (r - c)^2 with the fp32 codeword; slot s of both tokens is loaded in one
   // batch, and slots beyond the first only when some token of the wavefront has them.  When the
   // whole codebook is in LDS, a token whose only candidate this is (97 % of them) has found its
   // codeword: the row is subtracted from the residual right away, so it is fetched once, not twice.
@@ -495,40 +512,49 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
     for (int slot = 0; slot < SCR_CAND; ++slot) {
       bool need = false;
 #pragma unroll
-      for (int tt = 0; tt < SCR_TT; ++tt) need = need || (nc[tt] > slot && !slow[tt]);
+      for (int k = 0; k < SCR_DT; ++k) need = need || (nc[k] > slot && !slow[k]);
       if (!__any(need)) break;
-      f32x4 cw[SCR_TT][4];
-      int kk[SCR_TT];
+      f32x4 cw[SCR_DT][8];
+      int kk[SCR_DT];
 #pragma unroll
-      for (int tt = 0; tt < SCR_TT; ++tt) {
-        const int cand = lds_c[(wtok + tt * 32 + p) * SCR_CAND + slot];
-        kk[tt] = (nc[tt] > slot && cand < a.K) ? cand : 0;
-        const f32x4 *crow = reinterpret_cast<const f32x4 *>(
-            a.C32 + ((int64_t)stage * a.K + kk[tt]) * 32 + 16 * h);
+      for (int k = 0; k < SCR_DT; ++k) {
+        const int cand = lds_c[(wtok + k * 64 + lane) * SCR_CAND + slot];
+        kk[k] = (nc[k] > slot && cand < a.K) ? cand : 0;
+        const f32x4 *crow = reinterpret_cast<const f32x4 *>(a.C32 + ((int64_t)stage * a.K + kk[k]) * 32);
 #pragma unroll
-        for (int c4 = 0; c4 < 4; ++c4) cw[tt][c4] = crow[c4];
+        for (int c4 = 0; c4 < 8; ++c4) cw[k][c4] = crow[c4];
       }
 #pragma unroll
-      for (int tt = 0; tt < SCR_TT; ++tt) {
-        const bool valid = nc[tt] > slot && !slow[tt];
-        const bool commit = single_chunk && slot == 0 && valid && nc[tt] == 1;
+      for (int k = 0; k < SCR_DT; ++k) {
+        const bool valid = nc[k] > slot && !slow[k];
+        const bool commit = single_chunk && slot == 0 && valid && nc[k] == 1;
         const float sel = commit ? 1.0f : 0.0f;
         float dist = 0.f;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          const float c = cw[tt][j >> 2][j & 3];
-          const float dlt = r[tt][j] - c;
+        for (int j = 0; j < 32; ++j) {
+          const float c = cw[k][j >> 2][j & 3];
+          const float dlt = r[k][j] - c;
           dist = fmaf(dlt, dlt, dist);
-          r[tt][j] = fmaf(-sel, c, r[tt][j]);  // exact: sel is 0 or 1
+          r[k][j] = fmaf(-sel, c, r[k][j]);  // exact: sel is 0 or 1
         }
-        dist = sum32(dist);
-        n_exact += __popcll(__ballot(valid && h == 0));
-        if (valid && (dist < bestd[tt] || (dist == bestd[tt] && kk[tt] < bestk[tt]))) {
-          bestd[tt] = dist;
-          bestk[tt] = kk[tt];
+        n_exact += __popcll(__ballot(valid));
+        if (valid && (dist < bestd[k] || (dist == bestd[k] && kk[k] < bestk[k]))) {
+          bestd[k] = dist;
+          bestk[k] = kk[k];
         }
-        if (commit) done[tt] = 1;
+        if (commit) done[k] = 1;
       }
+    }
+  };
+
+  // the residual of the token that lane `src` owns in double tile k, handed to every lane
+  auto broadcast_token = [&](int k, int src, float (&vec)[32]) {
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+      float rj = r[0][j];
+#pragma unroll
+      for (int k2 = 1; k2 < SCR_DT; ++k2) rj = k == k2 ? r[k2][j] : rj;
+      vec[j] = __shfl(rj, src, 64);
     }
   };
 
@@ -555,7 +581,23 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
       for (int tt = 0; tt < SCR_TT; ++tt) m1[tt] = m2[tt] = m3[tt] = BIG;
       const int tile0 = cbase >> 5;
       {
-        static_assert(SCR_TT == 4, "the sweep pipeline is written for four token tiles");
+        static_assert(SCR_TT == 4 && SCR_DT == 2, "the sweep pipeline is written for four token tiles");
+        // the matrix-core arrangement of the fp16 residuals and of the tokens' bound terms
+        half8 B0[SCR_TT], B1[SCR_TT];
+        float g1t[SCR_TT];
+#pragma unroll
+        for (int k = 0; k < SCR_DT; ++k) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) swap_halves(Bw[k][j], Bw[k][8 + j]);
+#pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            B0[2 * k + e] = __builtin_bit_cast(
+                half8, make_uint4(Bw[k][8 * e + 0], Bw[k][8 * e + 1], Bw[k][8 * e + 2], Bw[k][8 * e + 3]));
+            B1[2 * k + e] = __builtin_bit_cast(
+                half8, make_uint4(Bw[k][8 * e + 4], Bw[k][8 * e + 5], Bw[k][8 * e + 6], Bw[k][8 * e + 7]));
+          }
+          halves32f(g1[k], g1t[2 * k], g1t[2 * k + 1]);
+        }
         f32x16 accA, accB, cn;
 #pragma unroll
         for (int e = 0; e < 16; ++e) { accA[e] = BIG; accB[e] = BIG; }
@@ -572,68 +614,170 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
         const unsigned tid_l = (unsigned)(tile0 + ntiles - 1);
         { float v = u2, vd = u2d; SWEEP_R2(v, 2, tid_l, Agp) }
         { SWEEP_R1(accB, u3) SWEEP_R2(u3, 3, tid_l, Agp) }
+        // back to the owner's arrangement
+#pragma unroll
+        for (int k = 0; k < SCR_DT; ++k)
+#pragma unroll
+          for (int j = 0; j < 8; ++j) swap_halves(Bw[k][j], Bw[k][8 + j]);
+      }
+      // the tracked groups of every token go to the lane that owns it: ta = the three smallest
+      // lower bounds among the groups of tile rows with lane half 0, tb = those of lane half 1
+      float ta[SCR_DT][3], tb[SCR_DT][3];
+#pragma unroll
+      for (int k = 0; k < SCR_DT; ++k) {
+        ta[k][0] = m1[2 * k]; tb[k][0] = m1[2 * k + 1];
+        ta[k][1] = m2[2 * k]; tb[k][1] = m2[2 * k + 1];
+        ta[k][2] = m3[2 * k]; tb[k][2] = m3[2 * k + 1];
+#pragma unroll
+        for (int i = 0; i < 3; ++i) swap_halves(ta[k][i], tb[k][i]);
       }
 
       PHASE_MARK(3);  // sweep
       // ---- resolve, step 1 (LDS only): the candidate codewords of every token of the chunk.
       //
-      // fp16 re-score of the 16 rows of group (tl, hh) for the token whose fp16 residual halves
-      // the lane pair holds in (Bx0, Bx1).  A row survives when its score minus the group's error
-      // bound is within the token's window: score <= tadj = thr + g1 A_g (the second-order part
-      // of the bound is already inside the stored norms).  Returns the survivors of the pair as
-      // a 16-bit row mask, the same in both lanes.
-      auto rescore = [&](int tl, int hh, const half8 &Bx0, const half8 &Bx1, float tadj,
-                         bool act) -> unsigned {
-        const uint2 *rows = reinterpret_cast<const uint2 *>(lds_A) + tl * 256 + h * 32;
+      // fp16 re-score of the 16 rows of group (tl, hh) for the token whose fp16 residual (owner's
+      // arrangement) is Bx.  A row survives when its score minus the group's error bound is
+      // within the token's window: score <= tadj = thr + g1 A_g (the second-order part of the
+      // bound is already inside the stored norms).  Returns the survivors as a 16-bit mask:
+      // bit 4 b + i stands for tile row 8 b + 4 hh + i.
+      auto rescore = [&](int tl, int hh, const unsigned (&Bx)[16], float tadj, bool act) -> unsigned {
+        const uint2 *tile = reinterpret_cast<const uint2 *>(lds_A) + tl * 256;
         const int swz = tl & 31;  // row m of tile tl is stored in slot m ^ swz
-        // Both lanes of the pair take the partial dot products (over their half of the channels)
-        // of all 16 rows: px of the group's rows in the lower half of the tile, py of those in
-        // the upper half.  One half-swap per row pair then leaves, added up, the full product of
-        // an upper row in lane half 0 and of a lower row in lane half 1.
-        const float *nrow = lds_n + (tl * 2 + hh) * 16 + 8 * (1 - h);
-        // all reads of one quarter of the rows are issued before their dot products: few
-        // dependent LDS round trips
-        float px[8], py[8];
-#pragma unroll
-        for (int qt = 0; qt < 4; ++qt) {  // two rows of either half per step
-          uint4 xa0[2], xa1[2], xb0[2], xb1[2];
-#pragma unroll
-          for (int q = 0; q < 2; ++q) {
-            const int u = 2 * qt + q;
-            const int mo = 8 * (u >> 2) + (u & 3);  // tile row of group row u, within 16 rows
-            const uint2 *ra = rows + ((4 * hh + mo) ^ swz);
-            const uint2 *rb = rows + ((16 + 4 * hh + mo) ^ swz);
-            xa0[q] = make_uint4(ra[0].x, ra[0].y, ra[64].x, ra[64].y);
-            xa1[q] = make_uint4(ra[128].x, ra[128].y, ra[192].x, ra[192].y);
-            xb0[q] = make_uint4(rb[0].x, rb[0].y, rb[64].x, rb[64].y);
-            xb1[q] = make_uint4(rb[128].x, rb[128].y, rb[192].x, rb[192].y);
-          }
-#pragma unroll
-          for (int q = 0; q < 2; ++q) {
-            px[2 * qt + q] = dot8(xa1[q], Bx1, dot8(xa0[q], Bx0, 0.f));
-            py[2 * qt + q] = dot8(xb1[q], Bx1, dot8(xb0[q], Bx0, 0.f));
-          }
-        }
-        const f32x4 nlo = *reinterpret_cast<const f32x4 *>(nrow);
-        const f32x4 nhi = *reinterpret_cast<const f32x4 *>(nrow + 4);
+        const float *nrow = lds_n + (tl * 2 + hh) * 16;
         unsigned mask = 0;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(py[u]),
-                                                          __float_as_uint(px[u]), false, false);
-          const float sc = (__uint_as_float(r[0]) + __uint_as_float(r[1])) + (u < 4 ? nlo[u & 3] : nhi[u & 3]);
-          mask |= (sc <= tadj ? 1u : 0u) << u;
+        for (int b4 = 0; b4 < 4; ++b4) {  // four rows per step: their reads are issued together
+          uint2 w[4][8];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const uint2 *row = tile + ((8 * b4 + 4 * hh + i) ^ swz);
+            // piece (q, pc) of lane half hx holds channels 16 hx + 8 q + 4 pc .. + 3
+#pragma unroll
+            for (int pc8 = 0; pc8 < 8; ++pc8) w[i][pc8] = row[(pc8 & 3) * 64 + (pc8 >> 2) * 32];
+          }
+          const f32x4 nv = *reinterpret_cast<const f32x4 *>(nrow + 4 * b4);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            float acc0 = 0.f, acc1 = 0.f;
+#pragma unroll
+            for (int pc4 = 0; pc4 < 4; ++pc4) {  // channels 4 pc4 .. of the lower 16, then of the upper
+              acc0 = dot2w(w[i][pc4].x, Bx[2 * pc4], acc0);
+              acc0 = dot2w(w[i][pc4].y, Bx[2 * pc4 + 1], acc0);
+              acc1 = dot2w(w[i][4 + pc4].x, Bx[8 + 2 * pc4], acc1);
+              acc1 = dot2w(w[i][4 + pc4].y, Bx[8 + 2 * pc4 + 1], acc1);
+            }
+            const float sc = (acc0 + acc1) + nv[i];
+            mask |= (sc <= tadj ? 1u : 0u) << (4 * b4 + i);
+          }
         }
-        mask = act ? mask << (8 * (1 - h)) : 0u;  // bits 0..7: lower rows, 8..15: upper rows
-        n_groups += __popcll(__ballot(act && h == 0));
-        unsigned k0, k1;
-        halves32(mask, k0, k1);
-        return k0 | k1;
+        mask = act ? mask : 0u;
+        n_groups += __popcll(__ballot(act));
+        return mask;
       };
-      // append the surviving rows of group (tl, hh), as codeword indices, to the candidate list
-      // of token slot `tok` of this wavefront; a count beyond the list marks the token for the
-      // group-wide exact pass below
-      auto append = [&](unsigned todo, int tl, int hh, int tok) {
+      // group (tile, lane half) of a tagged lower bound, tile relative to the chunk
+      auto tile_of = [&](float val) -> int {
+        int tl = (int)(__float_as_uint(val) & ~tag_mask) - tile0;
+        return tl < 0 ? 0 : (tl >= ntiles ? ntiles - 1 : tl);
+      };
+      // the window of the lane's token in double tile k: thr = upper bound on the exact minimum,
+      // from the best group of either lane half (LB + 2 e_g, 25 % spare); e0..e3 = the token's four
+      // tracked groups, the best one first (the two best of half 0 and of half 1); pend = which of
+      // them lie within the window
+      struct Window { float thr, e0, e1, e2, e3; unsigned pend; bool afirst; };
+      auto window = [&](int k) -> Window {
+        Window w;
+        const float a1 = ta[k][0], a2 = ta[k][1], a3 = ta[k][2];
+        const float b1 = tb[k][0], b2 = tb[k][1], b3 = tb[k][2];
+        const float Aa = lds_g[tile_of(a1) * 2 + 0], Ab = lds_g[tile_of(b1) * 2 + 1];
+        const float ua = a1 + 2.5f * (g1[k] * Aa + k4 * Aa * Aa + g0[k]);
+        const float ub = b1 + 2.5f * (g1[k] * Ab + k4 * Ab * Ab + g0[k]);
+        w.thr = fminf(ua, ub);
+        // a third group of one lane half inside the window: more groups than are tracked
+        if (a3 <= w.thr || b3 <= w.thr) slow[k] = 1;
+        w.afirst = a1 <= b1;
+        w.e0 = w.afirst ? a1 : b1; w.e1 = w.afirst ? b1 : a1;
+        w.e2 = w.afirst ? a2 : b2; w.e3 = w.afirst ? b2 : a2;
+        w.pend = 0;
+        if (!slow[k])
+          w.pend = (w.e0 <= w.thr && w.e0 < 1e37f ? 1u : 0u) | (w.e1 <= w.thr && w.e1 < 1e37f ? 2u : 0u) |
+                   (w.e2 <= w.thr && w.e2 < 1e37f ? 4u : 0u) | (w.e3 <= w.thr && w.e3 < 1e37f ? 8u : 0u);
+        return w;
+      };
+
+      // Pass A, per double tile: the best group of every token is re-scored by its owner and the
+      // surviving rows go to the token's candidate list; its other groups inside the window (3 %
+      // of the tokens have one) are queued, so that they are re-scored together afterwards
+      // instead of one extra pass per double tile.
+      int qn = 0;  // queue entries of this wavefront (wave-uniform)
+#pragma unroll
+      for (int k = 0; k < SCR_DT; ++k) {
+        const int tok = k * 64 + lane;
+        const Window w = window(k);
+        {
+          const int tl = tile_of(w.e0);
+          const int hh = (w.afirst ? 0 : 1);
+          const float tadj = w.thr + g1[k] * lds_g[tl * 2 + hh];
+          unsigned todo = rescore(tl, hh, Bw[k], tadj, (w.pend & 1u) != 0);
+          // the surviving rows, as codeword indices, into the owner's list; a count beyond the
+          // list marks the token for the group-wide exact pass below
+          while (__any(todo != 0)) {
+            const bool has = todo != 0;
+            const int rr = has ? __ffs(todo) - 1 : 0;
+            todo &= todo - 1;
+            const int m = 8 * (rr >> 2) + 4 * hh + (rr & 3);
+            const unsigned kk = lds_p[tl * 32 + m];
+            if (has && kk < (unsigned)a.K) {
+              if (nc[k] < SCR_CAND) lds_c[(wtok + tok) * SCR_CAND + nc[k]] = (uint16_t)kk;
+              nc[k] += 1;
+            }
+          }
+        }
+#pragma unroll
+        for (int it = 1; it < 4; ++it) {
+          const bool has = ((w.pend >> it) & 1u) != 0;
+          const unsigned long long bal = __ballot(has);
+          if (bal) {  // wave-uniform, seldom taken
+            const int idx = qn + __popcll(bal & ((1ull << lane) - 1ull));
+            const float val = it == 1 ? w.e1 : (it == 2 ? w.e2 : w.e3);
+            const int tl = tile_of(val);
+            const int hh = (w.afirst ? it : it + 1) & 1;
+            if (has) {
+              if (idx < SCR_QCAP) {
+#pragma unroll
+                for (int c4 = 0; c4 < 4; ++c4)
+                  qB[idx * 4 + c4] = make_uint4(Bw[k][4 * c4], Bw[k][4 * c4 + 1], Bw[k][4 * c4 + 2], Bw[k][4 * c4 + 3]);
+                qM[idx] = make_uint2(__float_as_uint(w.thr + g1[k] * lds_g[tl * 2 + hh]),
+                                     (unsigned)tok | ((unsigned)tl << 8) | ((unsigned)hh << 16));
+              } else {
+                nc[k] |= 0x100;  // queue full: the group-wide exact pass takes the token
+              }
+            }
+            qn = min(SCR_QCAP, qn + (int)__popcll(bal));
+          }
+        }
+      }
+      PHASE_MARK(4);  // resolve: best groups by their owners
+      // Pass B: the queued (token, group) pairs, one per lane.  The lists are then appended to by
+      // lanes that do not own them: the owners publish their counts first and read them back after.
+      if (qn > 0) {
+#pragma unroll
+        for (int k = 0; k < SCR_DT; ++k)
+          reinterpret_cast<uint16_t *>(lds_cnt)[wtok + k * 64 + lane] = (uint16_t)nc[k];
+        __builtin_amdgcn_wave_barrier();
+        const bool valid = lane < qn;
+        const int qi = valid ? lane : 0;
+        const uint2 meta = qM[qi];
+        unsigned Bq[16];
+#pragma unroll
+        for (int c4 = 0; c4 < 4; ++c4) {
+          const uint4 t4 = qB[qi * 4 + c4];
+          Bq[4 * c4] = t4.x; Bq[4 * c4 + 1] = t4.y; Bq[4 * c4 + 2] = t4.z; Bq[4 * c4 + 3] = t4.w;
+        }
+        const int tok = (int)(meta.y & 0xffu) & (SCR_WTOK - 1);
+        int tl = (int)((meta.y >> 8) & 0xffu);
+        tl = tl >= ntiles ? ntiles - 1 : tl;
+        const int hh = (int)((meta.y >> 16) & 1u);
+        unsigned todo = rescore(tl, hh, Bq, __uint_as_float(meta.x), valid);
         const int sh = 16 * (tok & 1);
         while (__any(todo != 0)) {
           const bool has = todo != 0;
@@ -641,165 +785,75 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
           todo &= todo - 1;
           const int m = 8 * (rr >> 2) + 4 * hh + (rr & 3);
           const unsigned kk = lds_p[tl * 32 + m];
-          if (has && h == 0 && kk < (unsigned)a.K) {
+          if (has && kk < (unsigned)a.K) {
             const unsigned pos = (atomicAdd(&lds_cnt[(wtok + tok) >> 1], 1u << sh) >> sh) & 0xffffu;
             if (pos < (unsigned)SCR_CAND) lds_c[(wtok + tok) * SCR_CAND + pos] = (uint16_t)kk;
           }
         }
-      };
-      // group (tile, lane half) of a tagged lower bound, tile relative to the chunk
-      auto tile_of = [&](float val) -> int {
-        int tl = (int)(__float_as_uint(val) & ~tag_mask) - tile0;
-        return tl < 0 ? 0 : (tl >= ntiles ? ntiles - 1 : tl);
-      };
-      // the window of entry 0 of the (rotated) per-tile arrays: thr = upper bound on the exact
-      // minimum, from the best group of either lane (LB + 2 e_g, 25 % spare); e0..e3 = the
-      // token's four tracked groups, the best one first (both lanes of the pair build the same
-      // list: the two best of half 0 and of half 1); pend = which of them lie within the window
-      struct Window { float thr, e0, e1, e2, e3; unsigned pend; bool afirst; };
-      auto window = [&]() -> Window {
-        Window w;
-        // a = the tracked groups of lane half 0, b = those of lane half 1, the same in both lanes
-        float a1, b1, a2, b2, a3, b3;
-        halves32f(m1[0], a1, b1);
-        halves32f(m2[0], a2, b2);
-        halves32f(m3[0], a3, b3);
-        {
-          const float A1 = lds_g[tile_of(m1[0]) * 2 + h];
-          const float mine = m1[0] + 2.5f * (g1[0] * A1 + k4 * A1 * A1 + g0[0]);
-          float t0, t1;
-          halves32f(mine, t0, t1);
-          w.thr = fminf(t0, t1);
-        }
-        // a third group of one lane inside the window: more groups than are tracked
-        if (a3 <= w.thr || b3 <= w.thr) slow[0] = 1;
-        w.afirst = a1 <= b1;
-        w.e0 = w.afirst ? a1 : b1; w.e1 = w.afirst ? b1 : a1;
-        w.e2 = w.afirst ? a2 : b2; w.e3 = w.afirst ? b2 : a2;
-        w.pend = 0;
-        if (!slow[0])
-          w.pend = (w.e0 <= w.thr && w.e0 < 1e37f ? 1u : 0u) | (w.e1 <= w.thr && w.e1 < 1e37f ? 2u : 0u) |
-                   (w.e2 <= w.thr && w.e2 < 1e37f ? 4u : 0u) | (w.e3 <= w.thr && w.e3 < 1e37f ? 8u : 0u);
-        return w;
-      };
-
-      // Pass A, per token tile: the best group of every token is re-scored in place; its other
-      // groups inside the window (3 % of the tokens have one) are queued, so that they are
-      // re-scored 32 at a time afterwards instead of one extra pass per token tile.
-      // The loop body always works on entry 0 of the per-tile arrays, which are rotated.
-      int qn = 0;  // queue entries of this wavefront (wave-uniform)
-#pragma unroll 1
-      for (int rot = 0; rot < SCR_TT; ++rot) {
-        const int tok = rot * 32 + p;
-        const Window w = window();
-        {
-          const int tl = tile_of(w.e0);
-          const int hh = (w.afirst ? 0 : 1);
-          const float tadj = w.thr + g1[0] * lds_g[tl * 2 + hh];
-          const unsigned todo = rescore(tl, hh, B0[0], B1[0], tadj, (w.pend & 1u) != 0);
-          append(todo, tl, hh, tok);
-        }
-        bool over = false;
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int it = 1; it < 4; ++it) {
-          const bool has = ((w.pend >> it) & 1u) != 0;
-          const unsigned long long bal = __ballot(has && h == 0);
-          if (bal) {  // wave-uniform, seldom taken
-            const int idx = qn + __popcll(bal & ((1ull << p) - 1ull));
-            const float val = it == 1 ? w.e1 : (it == 2 ? w.e2 : w.e3);
-            const int tl = tile_of(val);
-            const int hh = (w.afirst ? it : it + 1) & 1;
-            if (has) {
-              if (idx < SCR_QCAP) {
-                qB[(idx * 2 + h) * 2 + 0] = __builtin_bit_cast(uint4, B0[0]);
-                qB[(idx * 2 + h) * 2 + 1] = __builtin_bit_cast(uint4, B1[0]);
-                if (h == 0)
-                  qM[idx] = make_uint2(__float_as_uint(w.thr + g1[0] * lds_g[tl * 2 + hh]),
-                                       (unsigned)tok | ((unsigned)tl << 8) | ((unsigned)hh << 16));
-              } else {
-                over = true;  // queue full: the group-wide exact pass takes the token
-              }
-            }
-            qn = min(SCR_QCAP, qn + (int)__popcll(bal));
-          }
-        }
-        if (over && h == 0) atomicOr(&lds_cnt[(wtok + tok) >> 1], 0x100u << (16 * (tok & 1)));
-        ROT4(m1); ROT4(m2); ROT4(m3); ROT4(g1); ROT4(g0); ROT4(slow);
-        ROT4(B0); ROT4(B1);
-      }
-      PHASE_MARK(4);  // resolve: best groups in place
-      // Pass B: the queued (token, group) pairs, one per lane pair
-      for (int base = 0; base < qn; base += 32) {
-        const bool valid = base + p < qn;
-        const int qi = valid ? base + p : 0;
-        const uint2 meta = qM[qi];
-        const half8 Bq0 = __builtin_bit_cast(half8, qB[(qi * 2 + h) * 2 + 0]);
-        const half8 Bq1 = __builtin_bit_cast(half8, qB[(qi * 2 + h) * 2 + 1]);
-        const int tok = (int)(meta.y & 0xffu) & (SCR_TT * 32 - 1);
-        int tl = (int)((meta.y >> 8) & 0xffu);
-        tl = tl >= ntiles ? ntiles - 1 : tl;
-        const int hh = (int)((meta.y >> 16) & 1u);
-        const unsigned todo = rescore(tl, hh, Bq0, Bq1, __uint_as_float(meta.x), valid);
-        append(todo, tl, hh, tok);
+        for (int k = 0; k < SCR_DT; ++k)
+          nc[k] = (int)reinterpret_cast<uint16_t *>(lds_cnt)[wtok + k * 64 + lane];
       }
 
       PHASE_MARK(6);  // resolve: queued groups
-      // candidates per token, as counted in LDS
-      bool any_over = false;
-#pragma unroll
-      for (int tt = 0; tt < SCR_TT; ++tt) {
-        nc[tt] = (int)((lds_cnt[(wtok + tt * 32 + p) >> 1] >> (16 * (p & 1))) & 0xffffu);
-        any_over = any_over || nc[tt] > SCR_CAND;
-      }
       // ---- a token with more candidates than the list holds (or whose groups did not fit the
       // queue): the wavefront scores ALL rows of its (at most four) groups in the window
       // exactly, one lane per row, and the token keeps the single winner.  Exact, because the
       // true winner of the chunk lies in one of these groups.
-      if (__any(any_over)) {
+      {
+        bool any_over = false;
+#pragma unroll
+        for (int k = 0; k < SCR_DT; ++k) any_over = any_over || (nc[k] > SCR_CAND && !slow[k]);
+        if (__any(any_over)) {
 #pragma unroll 1
-        for (int rot = 0; rot < SCR_TT; ++rot) {
-          unsigned long long ovm = __ballot(nc[0] > SCR_CAND && !slow[0] && h == 0);
-          if (ovm) {
-            const Window w = window();
-            while (ovm) {
-              const int src = __ffsll((long long)ovm) - 1;
-              ovm &= ovm - 1;
-              n_over += 1;
-              float rr32[32];
+          for (int k = 0; k < SCR_DT; ++k) {
+            int nck = nc[0], slowk = slow[0];
 #pragma unroll
-              for (int j = 0; j < 16; ++j) {
-                float rj = r[0][j];
+            for (int k2 = 1; k2 < SCR_DT; ++k2) { nck = k == k2 ? nc[k2] : nck; slowk = k == k2 ? slow[k2] : slowk; }
+            unsigned long long ovm = __ballot(nck > SCR_CAND && !slowk);
+            if (ovm) {
+              Window w = window(0);
 #pragma unroll
-                for (int t2 = 1; t2 < SCR_TT; ++t2) rj = rot == t2 ? r[t2][j] : rj;
-                rr32[j] = __shfl(rj, src, 64);
-                rr32[16 + j] = __shfl(rj, src + 32, 64);
+              for (int k2 = 1; k2 < SCR_DT; ++k2)
+                if (k == k2) w = window(k2);
+              while (ovm) {
+                const int src = __ffsll((long long)ovm) - 1;
+                ovm &= ovm - 1;
+                n_over += 1;
+                float rr32[32];
+                broadcast_token(k, src, rr32);
+                const int gi = lane >> 4, rw = lane & 15;  // lane -> (group of the window, row)
+                const float ge0 = __shfl(w.e0, src, 64), ge1 = __shfl(w.e1, src, 64);
+                const float ge2 = __shfl(w.e2, src, 64), ge3 = __shfl(w.e3, src, 64);
+                const unsigned gpend = (unsigned)__shfl((int)w.pend, src, 64);
+                const int gaf = __shfl((int)w.afirst, src, 64);
+                const float gval = gi == 0 ? ge0 : (gi == 1 ? ge1 : (gi == 2 ? ge2 : ge3));
+                const int ghh = (gaf ? gi : gi + 1) & 1;
+                const int gtl = tile_of(gval);
+                const int gm = 8 * (rw >> 2) + 4 * ghh + (rw & 3);
+                const unsigned gk = ((gpend >> gi) & 1u) ? (unsigned)lds_p[gtl * 32 + gm] : 0xffffu;
+                const bool gvalid = gk < (unsigned)a.K;
+                const int bk = exact_best_of_lanes(a.C32 + (int64_t)stage * a.K * 32, rr32, gk, gvalid);
+                // bk == 0x7fffffff cannot happen for a token with candidates; it would leave the
+                // token without one and send it to the wavefront search below
+                if (lane == src) {
+                  lds_c[(wtok + k * 64 + src) * SCR_CAND] = (uint16_t)(bk == 0x7fffffff ? 0 : bk);
+#pragma unroll
+                  for (int k2 = 0; k2 < SCR_DT; ++k2)
+                    if (k == k2) nc[k2] = bk == 0x7fffffff ? 0 : 1;
+                }
               }
-              const int gi = lane >> 4, rw = lane & 15;  // lane -> (group of the window, row)
-              const float ge0 = __shfl(w.e0, src, 64), ge1 = __shfl(w.e1, src, 64);
-              const float ge2 = __shfl(w.e2, src, 64), ge3 = __shfl(w.e3, src, 64);
-              const unsigned gpend = (unsigned)__shfl((int)w.pend, src, 64);
-              const int gaf = __shfl((int)w.afirst, src, 64);
-              const float gval = gi == 0 ? ge0 : (gi == 1 ? ge1 : (gi == 2 ? ge2 : ge3));
-              const int ghh = (gaf ? gi : gi + 1) & 1;
-              const int gtl = tile_of(gval);
-              const int gm = 8 * (rw >> 2) + 4 * ghh + (rw & 3);
-              const unsigned gk = ((gpend >> gi) & 1u) ? (unsigned)lds_p[gtl * 32 + gm] : 0xffffu;
-              const bool gvalid = gk < (unsigned)a.K;
-              const int bk = exact_best_of_lanes(a.C32 + (int64_t)stage * a.K * 32, rr32, gk, gvalid);
-              if (lane == src) lds_c[(wtok + rot * 32 + src) * SCR_CAND] = (uint16_t)(bk == 0x7fffffff ? 0 : bk);
-              // bk == 0x7fffffff cannot happen for a token with candidates; it would leave the
-              // token without one and send it to the wavefront search below
-              if (lane == src || lane == src + 32) nc[0] = bk == 0x7fffffff ? 0 : 1;
             }
           }
-          ROT4(m1); ROT4(m2); ROT4(m3); ROT4(g1); ROT4(g0); ROT4(slow); ROT4(nc);
         }
       }
       PHASE_MARK(7);  // resolve: group-wide exact passes
 
       if (!single_chunk) {
         exact_candidates(stage);
-        if (lane < SCR_TT * 16) lds_cnt[(wtok >> 1) + lane] = 0u;  // new lists per chunk
+#pragma unroll
+        for (int k = 0; k < SCR_DT; ++k) nc[k] = 0;  // new lists per chunk of the codebook
       }
     }
   };
@@ -813,63 +867,65 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
     {
       bool any_slow = false;
 #pragma unroll
-      for (int tt = 0; tt < SCR_TT; ++tt) {
-        if (!(bestd[tt] < INFINITY)) slow[tt] = 1;  // no candidate in any chunk
-        any_slow = any_slow || slow[tt];
+      for (int k = 0; k < SCR_DT; ++k) {
+        if (!(bestd[k] < INFINITY)) slow[k] = 1;  // no candidate in any chunk
+        any_slow = any_slow || slow[k];
       }
       if (__any(any_slow)) {  // seldom: 0.02 % of the searches
 #pragma unroll 1
-        for (int rot = 0; rot < SCR_TT; ++rot) {
-          // token tile `rot` is picked with selects, so that the common path never moves the
+        for (int k = 0; k < SCR_DT; ++k) {
+          // double tile k is picked with selects, so that the common path never moves the
           // register arrays around
-          int slow_r = slow[0];
+          int slow_k = slow[0];
 #pragma unroll
-          for (int t2 = 1; t2 < SCR_TT; ++t2) slow_r = rot == t2 ? slow[t2] : slow_r;
-          unsigned long long pending = __ballot(slow_r && h == 0);
+          for (int k2 = 1; k2 < SCR_DT; ++k2) slow_k = k == k2 ? slow[k2] : slow_k;
+          unsigned long long pending = __ballot(slow_k != 0);
           n_slow += __popcll(pending);
           while (pending) {
             const int src = __ffsll((long long)pending) - 1;
             pending &= pending - 1;
             float rr32[32];
-#pragma unroll
-            for (int j = 0; j < 16; ++j) {
-              float rj = r[0][j];
-#pragma unroll
-              for (int t2 = 1; t2 < SCR_TT; ++t2) rj = rot == t2 ? r[t2][j] : rj;
-              rr32[j] = __shfl(rj, src, 64);
-              rr32[16 + j] = __shfl(rj, src + 32, 64);
-            }
+            broadcast_token(k, src, rr32);
             const int bk = exact_scan(a.C32 + (int64_t)stage * a.K * 32, a.K, rr32, lane);
-            const bool mine = lane == src || lane == src + 32;
 #pragma unroll
-            for (int t2 = 0; t2 < SCR_TT; ++t2) bestk[t2] = (mine && rot == t2) ? bk : bestk[t2];
+            for (int k2 = 0; k2 < SCR_DT; ++k2) bestk[k2] = (lane == src && k == k2) ? bk : bestk[k2];
           }
         }
       }
     }
-    n_search += SCR_TT * 32;
+    n_search += SCR_WTOK;
 
     // ---- emit the code and subtract the fp32 codeword from the residual (Algorithm 1) where
-    // that has not happened yet; the four rows are fetched in one batch (row 0 stands in for
-    // the tokens that are done, so their lanes cost no memory traffic)
+    // that has not happened yet (the tokens with several candidates and those searched exactly)
     {
-      f32x4 cw[SCR_TT][4];
+      int kq[SCR_DT];
 #pragma unroll
-      for (int tt = 0; tt < SCR_TT; ++tt) {
-        const int64_t v = vbase + tt * 32 + p;
-        int k = bestk[tt];
-        k = k < 0 ? 0 : (k >= a.K ? a.K - 1 : k);
-        if (v < a.V && h == 0) a.codes[v * a.depth + stage] = (int16_t)k;
-        const f32x4 *crow = reinterpret_cast<const f32x4 *>(
-            a.C32 + ((int64_t)stage * a.K + (done[tt] ? 0 : k)) * 32 + 16 * h);
-#pragma unroll
-        for (int c4 = 0; c4 < 4; ++c4) cw[tt][c4] = crow[c4];
+      for (int k = 0; k < SCR_DT; ++k) {
+        const int64_t v = vbase + k * 64 + lane;
+        int kk = bestk[k];
+        kk = kk < 0 ? 0 : (kk >= a.K ? a.K - 1 : kk);
+        kq[k] = kk;
+        if (v < a.V) a.codes[v * a.depth + stage] = (int16_t)kk;
       }
+      bool any_left = false;
 #pragma unroll
-      for (int tt = 0; tt < SCR_TT; ++tt) {
-        const float sel = done[tt] ? 0.0f : 1.0f;
+      for (int k = 0; k < SCR_DT; ++k) any_left = any_left || !done[k];
+      if (__any(any_left)) {
+        f32x4 cw[SCR_DT][8];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) r[tt][j] = fmaf(-sel, cw[tt][j >> 2][j & 3], r[tt][j]);
+        for (int k = 0; k < SCR_DT; ++k) {
+          // row 0 stands in for the tokens that are done: one line for all of their lanes
+          const f32x4 *crow = reinterpret_cast<const f32x4 *>(
+              a.C32 + ((int64_t)stage * a.K + (done[k] ? 0 : kq[k])) * 32);
+#pragma unroll
+          for (int c4 = 0; c4 < 8; ++c4) cw[k][c4] = crow[c4];
+        }
+#pragma unroll
+        for (int k = 0; k < SCR_DT; ++k) {
+          const float sel = done[k] ? 0.0f : 1.0f;
+#pragma unroll
+          for (int j = 0; j < 32; ++j) r[k][j] = fmaf(-sel, cw[k][j >> 2][j & 3], r[k][j]);
+        }
       }
     }
     PHASE_MARK(5);  // exact scores + code emit
