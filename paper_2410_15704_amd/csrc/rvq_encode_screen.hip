@@ -757,37 +757,54 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
         }
       }
       PHASE_MARK(4);  // resolve: best groups by their owners
-      // Pass B: the queued (token, group) pairs, one per lane.  The lists are then appended to by
-      // lanes that do not own them: the owners publish their counts first and read them back after.
+      // Pass B: the queued (token, group) pairs, four per pass: 16 lanes share a pair and score
+      // one row of its group each.  The lists are then appended to by lanes that do not own them:
+      // the owners publish their counts first and read them back after.
       if (qn > 0) {
 #pragma unroll
         for (int k = 0; k < SCR_DT; ++k)
           reinterpret_cast<uint16_t *>(lds_cnt)[wtok + k * 64 + lane] = (uint16_t)nc[k];
         __builtin_amdgcn_wave_barrier();
-        const bool valid = lane < qn;
-        const int qi = valid ? lane : 0;
-        const uint2 meta = qM[qi];
-        unsigned Bq[16];
+        const int rq = lane & 15;  // accumulator position 4 b + i of this lane's row
+#pragma unroll 1
+        for (int base = 0; base < qn; base += 4) {
+          const int qi = base + (lane >> 4);
+          const bool valid = qi < qn;
+          const int qc = valid ? qi : 0;
+          const uint2 meta = qM[qc];
+          unsigned Bq[16];
 #pragma unroll
-        for (int c4 = 0; c4 < 4; ++c4) {
-          const uint4 t4 = qB[qi * 4 + c4];
-          Bq[4 * c4] = t4.x; Bq[4 * c4 + 1] = t4.y; Bq[4 * c4 + 2] = t4.z; Bq[4 * c4 + 3] = t4.w;
-        }
-        const int tok = (int)(meta.y & 0xffu) & (SCR_WTOK - 1);
-        int tl = (int)((meta.y >> 8) & 0xffu);
-        tl = tl >= ntiles ? ntiles - 1 : tl;
-        const int hh = (int)((meta.y >> 16) & 1u);
-        unsigned todo = rescore(tl, hh, Bq, __uint_as_float(meta.x), valid);
-        const int sh = 16 * (tok & 1);
-        while (__any(todo != 0)) {
-          const bool has = todo != 0;
-          const int rr = has ? __ffs(todo) - 1 : 0;
-          todo &= todo - 1;
-          const int m = 8 * (rr >> 2) + 4 * hh + (rr & 3);
-          const unsigned kk = lds_p[tl * 32 + m];
-          if (has && kk < (unsigned)a.K) {
-            const unsigned pos = (atomicAdd(&lds_cnt[(wtok + tok) >> 1], 1u << sh) >> sh) & 0xffffu;
-            if (pos < (unsigned)SCR_CAND) lds_c[(wtok + tok) * SCR_CAND + pos] = (uint16_t)kk;
+          for (int c4 = 0; c4 < 4; ++c4) {
+            const uint4 t4 = qB[qc * 4 + c4];
+            Bq[4 * c4] = t4.x; Bq[4 * c4 + 1] = t4.y; Bq[4 * c4 + 2] = t4.z; Bq[4 * c4 + 3] = t4.w;
+          }
+          const int tok = (int)(meta.y & 0xffu) & (SCR_WTOK - 1);
+          int tl = (int)((meta.y >> 8) & 0xffu);
+          tl = tl >= ntiles ? ntiles - 1 : tl;
+          const int hh = (int)((meta.y >> 16) & 1u);
+          const int m = 8 * (rq >> 2) + 4 * hh + (rq & 3);
+          const uint2 *row = reinterpret_cast<const uint2 *>(lds_A) + tl * 256 + (m ^ (tl & 31));
+          uint2 w[8];
+#pragma unroll
+          for (int pc8 = 0; pc8 < 8; ++pc8) w[pc8] = row[(pc8 & 3) * 64 + (pc8 >> 2) * 32];
+          const float nvq = lds_n[(tl * 2 + hh) * 16 + rq];
+          float acc0 = 0.f, acc1 = 0.f;
+#pragma unroll
+          for (int pc4 = 0; pc4 < 4; ++pc4) {
+            acc0 = dot2w(w[pc4].x, Bq[2 * pc4], acc0);
+            acc0 = dot2w(w[pc4].y, Bq[2 * pc4 + 1], acc0);
+            acc1 = dot2w(w[4 + pc4].x, Bq[8 + 2 * pc4], acc1);
+            acc1 = dot2w(w[4 + pc4].y, Bq[8 + 2 * pc4 + 1], acc1);
+          }
+          const float sc = (acc0 + acc1) + nvq;
+          n_groups += __popcll(__ballot(valid && rq == 0));
+          if (valid && sc <= __uint_as_float(meta.x)) {
+            const unsigned kk = lds_p[tl * 32 + m];
+            if (kk < (unsigned)a.K) {
+              const int sh = 16 * (tok & 1);
+              const unsigned pos = (atomicAdd(&lds_cnt[(wtok + tok) >> 1], 1u << sh) >> sh) & 0xffffu;
+              if (pos < (unsigned)SCR_CAND) lds_c[(wtok + tok) * SCR_CAND + pos] = (uint16_t)kk;
+            }
           }
         }
         __builtin_amdgcn_wave_barrier();
