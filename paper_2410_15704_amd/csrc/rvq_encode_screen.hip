@@ -80,6 +80,7 @@ struct ScreenArgs {
                                  // [15] error word: bit 0 = a wait between wavefronts gave up
   int64_t N, ldx, V;
   int in_dtype, G, grouping, K, Kpad, depth, stage_begin, stage_end, tag_bits;
+  int vec_rows;         // contiguous groups that can be read in 16-byte pieces
   unsigned wait_polls;  // polls after which a wait between wavefronts gives up (see spin_ge)
   float kappa;
 };
@@ -371,10 +372,37 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
       const int g = (int)(vc - n * a.G);
       const float sd = a.std32 ? a.std32[n] : 1.0f;
       float x[32];
+      if (a.vec_rows) {
+        // contiguous groups whose 32 channels start on a 16-byte boundary: whole 16-byte pieces
+        // (element by element the 64 lanes of a load would touch 64 lines for 4 bytes each)
+        constexpr int EPP = DT == RVQ_F32 ? 4 : 8;  // elements per piece
+        const uint4 *src = reinterpret_cast<const uint4 *>(
+            reinterpret_cast<const char *>(a.X) + (n * a.ldx + (int64_t)g * 32) * (DT == RVQ_F32 ? 4 : 2));
+        uint4 w[32 / EPP];
 #pragma unroll
-      for (int j = 0; j < 32; ++j) {
-        const int64_t ch = a.grouping == RVQ_CONTIGUOUS ? (int64_t)g * 32 + j : (int64_t)j * a.G + g;
-        x[j] = rvq_load_in<DT>(a.X, n * a.ldx + ch);
+        for (int c = 0; c < 32 / EPP; ++c) w[c] = src[c];
+#pragma unroll
+        for (int c = 0; c < 32 / EPP; ++c) {
+          const uint32_t u[4] = {w[c].x, w[c].y, w[c].z, w[c].w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            if constexpr (DT == RVQ_F32) {
+              x[c * 4 + i] = __uint_as_float(u[i]);
+            } else if constexpr (DT == RVQ_BF16) {
+              x[c * 8 + 2 * i] = rvq_bf16_bits_to_f32((uint16_t)(u[i] & 0xffffu));
+              x[c * 8 + 2 * i + 1] = rvq_bf16_bits_to_f32((uint16_t)(u[i] >> 16));
+            } else {
+              x[c * 8 + 2 * i] = rvq_f16_bits_to_f32((uint16_t)(u[i] & 0xffffu));
+              x[c * 8 + 2 * i + 1] = rvq_f16_bits_to_f32((uint16_t)(u[i] >> 16));
+            }
+          }
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {
+          const int64_t ch = a.grouping == RVQ_CONTIGUOUS ? (int64_t)g * 32 + j : (int64_t)j * a.G + g;
+          x[j] = rvq_load_in<DT>(a.X, n * a.ldx + ch);
+        }
       }
 #pragma unroll
       for (int j = 0; j < 32; ++j) {
@@ -1016,7 +1044,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
     }
     if (do_lds) {
       const int i = sg % nst;
-      if (single_chunk && sg > 0) {
+      if (single_chunk && sg > 0 && nst > 1) {  // (one stage per call: the operands stay)
         if (team == 0) {
           spin_ge(0, 4u * sg);
           spin_ge(1, 4u * sg);
@@ -1094,6 +1122,11 @@ hipError_t rvq_launch_encode_screen(const rvq_ctx *ctx, const void *dX, int64_t 
   a.stage_begin = stage_begin;
   a.stage_end = stage_end;
   a.tag_bits = ctx->tag_bits;
+  {
+    const int64_t esz = c.in_dtype == RVQ_F32 ? 4 : 2;
+    a.vec_rows = (c.grouping == RVQ_CONTIGUOUS || ctx->G == 1) && (ldx * esz) % 16 == 0 &&
+                 (reinterpret_cast<uintptr_t>(dX) % 16) == 0;
+  }
   a.wait_polls = ctx->wait_polls;
   // one workgroup fills a CU (LDS): as many workgroups as CUs, each walking its share of the chunks
   const int64_t nchunks = (a.V + SCR_TOKENS - 1) / SCR_TOKENS;
