@@ -228,9 +228,30 @@ def run_decode_stream(args):
     del dcos, dsin
     for q in qs:
         q.close()
+    # What bounds the decode is not HBM but the on-chip gather: 32 groups x 8 stages x 128 bytes of
+    # fp32 codeword rows = 32 KiB per token against 2562 bytes of HBM traffic.  The library's probes
+    # measure the rate at which this GPU gathers in the two kernels' access shapes; divided by the
+    # 32 KiB per token and multiplied by the 2562 HBM bytes per token they give the decode rate at
+    # which the gathers alone would saturate, to compare with what each kernel reaches.
+    pr = b.rvq_probe_gather_rates()
+    gather_bytes = G * depth * 32 * 4
+    row_bytes = G * depth * 2 + 2 + d * 2
+    slice_bytes = T * row_bytes
+    ceil_lds = pr["lds_random_GBs"] / gather_bytes * row_bytes
+    ceil_lds_free = pr["lds_consecutive_GBs"] / gather_bytes * row_bytes
+    ceil_l2 = pr["l2_rows_random_GBs"] / gather_bytes * row_bytes
+    ceiling = dict(gather_bytes_per_token=gather_bytes, hbm_bytes_per_token=row_bytes, probes_GBs=pr,
+                   lds_kernel=dict(grouping="strided", bound="LDS reads at random addresses",
+                                   ceiling_GBs=ceil_lds, ceiling_without_bank_conflicts_GBs=ceil_lds_free),
+                   row_gather_kernel=dict(grouping="contiguous", bound="L2 row gathers", ceiling_GBs=ceil_l2))
+    for key, name in (("lds_kernel", "strided"), ("row_gather_kernel", "contiguous")):
+        if name in packed:
+            gb = slice_bytes / (packed[name]["int16_ms_per_slice"] * 1e-3) / 1e9
+            ceiling[key].update(achieved_GBs=gb, frac_of_ceiling=gb / ceiling[key]["ceiling_GBs"],
+                                frac_of_hbm_peak=gb / PEAK_HBM_GBS)
     return dict(workload="decode-time reconstruction, %d slices x 524288 tokens x 1024 ch" % S,
                 slices=S, ms_per_pass=ms, bytes_per_pass=nbytes, tokens_per_s=S * T / (ms * 1e-3),
-                packed_codes_and_rope=packed,
+                packed_codes_and_rope=packed, ceiling=ceiling,
                 roofline=dict(bound="hbm", achieved=gbs, peak=PEAK_HBM_GBS, unit="GB/s",
                               frac=gbs / PEAK_HBM_GBS, traffic=TRAFFIC_DECODE_SLICE,
                               kernel="rvq_decode", bytes_per_launch=nbytes / S,

@@ -233,6 +233,18 @@ int rvq_get_counters(rvq_ctx *ctx, int64_t *host_out);
 int rvq_check_kernels(rvq_ctx *ctx);
 int rvq_debug_set_wait_polls(rvq_ctx *ctx, int64_t polls);
 
+/*
+ * Gather-rate probes (diagnostics; allocates, runs on the default stream and synchronizes).
+ * Decode (Section 2.2, last sentence) gathers 8 fp32 codeword rows per (token, group): 32 KiB per
+ * 1024-channel token against 2.5 KB of HBM traffic, so its ceiling is the on-chip gather rate.
+ * host_out is HOST memory, 3 values in GB/s of gathered bytes on the current device:
+ *   [0] 8-byte reads at random indices of a 128 KiB table in LDS (the access of the LDS decode
+ *       kernel), [1] the same at consecutive indices (no bank conflicts), [2] 128-byte rows read at
+ *       random from a 2 MiB table through L2, 16 bytes per lane (the access of the row-gather
+ *       decode kernel).
+ */
+int rvq_probe_gather_rates(double *host_out);
+
 /* Text for an RVQ_E* code; the HIP error code of the last RVQ_EHIP on this context (0 if none). */
 const char *rvq_strerror(int code);
 int rvq_last_hip_error(const rvq_ctx *ctx);

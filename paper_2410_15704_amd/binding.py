@@ -30,7 +30,8 @@ EXPORTS = ("rvq_create", "rvq_destroy", "rvq_set_codebooks", "rvq_get_codebooks"
            "rvq_decode", "rvq_ema_update", "rvq_strerror", "rvq_last_hip_error", "rvq_version",
            "rvq_get_counters", "rvq_packed_record_bytes", "rvq_pack_codes", "rvq_unpack_codes",
            "rvq_decode_packed", "rvq_decode_rope", "rvq_reserve", "rvq_reserved_rows",
-           "rvq_check_kernels", "rvq_debug_set_wait_polls", "rvq_encode_static")
+           "rvq_check_kernels", "rvq_debug_set_wait_polls", "rvq_encode_static",
+           "rvq_probe_gather_rates")
 
 
 class rvq_config(ctypes.Structure):
@@ -66,6 +67,7 @@ def _load():
     lib.rvq_reserved_rows.restype = ctypes.c_int64
     lib.rvq_check_kernels.argtypes = [vp]
     lib.rvq_debug_set_wait_polls.argtypes = [vp, i64]
+    lib.rvq_probe_gather_rates.argtypes = [ctypes.POINTER(ctypes.c_double)]
     lib.rvq_strerror.argtypes = [ctypes.c_int]
     lib.rvq_strerror.restype = ctypes.c_char_p
     lib.rvq_last_hip_error.argtypes = [vp]
@@ -155,6 +157,12 @@ def rvq_check_kernels(ctx, check=True):
 
 def rvq_debug_set_wait_polls(ctx, polls):
     return _chk(lib.rvq_debug_set_wait_polls(ctx, polls), ctx)
+
+
+def rvq_probe_gather_rates():
+    out = (ctypes.c_double * 3)()
+    _chk(lib.rvq_probe_gather_rates(out), None)
+    return dict(lds_random_GBs=out[0], lds_consecutive_GBs=out[1], l2_rows_random_GBs=out[2])
 
 
 def rvq_set_codebooks(ctx, dC, stream=None):
