@@ -673,19 +673,23 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
         const int swz = tl & 31;  // row m of tile tl is stored in slot m ^ swz
         const float *nrow = lds_n + (tl * 2 + hh) * 16;
         unsigned mask = 0;
+        constexpr int RB = 2;  // rows per step: their reads are issued together (more rows in
+                               // flight cost registers that the kernel does not have)
 #pragma unroll
-        for (int b4 = 0; b4 < 4; ++b4) {  // four rows per step: their reads are issued together
-          uint2 w[4][8];
+        for (int b4 = 0; b4 < 16 / RB; ++b4) {
+          uint2 w[RB][8];
+          float nvv[RB];
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const uint2 *row = tile + ((8 * b4 + 4 * hh + i) ^ swz);
+          for (int i = 0; i < RB; ++i) {
+            const int rr = RB * b4 + i;
+            const uint2 *row = tile + ((8 * (rr >> 2) + 4 * hh + (rr & 3)) ^ swz);
             // piece (q, pc) of lane half hx holds channels 16 hx + 8 q + 4 pc .. + 3
 #pragma unroll
             for (int pc8 = 0; pc8 < 8; ++pc8) w[i][pc8] = row[(pc8 & 3) * 64 + (pc8 >> 2) * 32];
+            nvv[i] = nrow[rr];
           }
-          const f32x4 nv = *reinterpret_cast<const f32x4 *>(nrow + 4 * b4);
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
+          for (int i = 0; i < RB; ++i) {
             float acc0 = 0.f, acc1 = 0.f;
 #pragma unroll
             for (int pc4 = 0; pc4 < 4; ++pc4) {  // channels 4 pc4 .. of the lower 16, then of the upper
@@ -694,8 +698,8 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
               acc1 = dot2w(w[i][4 + pc4].x, Bx[8 + 2 * pc4], acc1);
               acc1 = dot2w(w[i][4 + pc4].y, Bx[8 + 2 * pc4 + 1], acc1);
             }
-            const float sc = (acc0 + acc1) + nv[i];
-            mask |= (sc <= tadj ? 1u : 0u) << (4 * b4 + i);
+            const float sc = (acc0 + acc1) + nvv[i];
+            mask |= (sc <= tadj ? 1u : 0u) << (RB * b4 + i);
           }
         }
         mask = act ? mask : 0u;
