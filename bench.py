@@ -30,9 +30,11 @@ if ROOT not in sys.path:
 PEAK_MFMA_16BIT_TFLOPS = 2500.0  # MI355X dense bf16 / fp16 matrix-core peak
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `--profile encode` and
-# `--profile decode`, scaled by the readings of a plain 1 GiB copy (profiles/*.txt hold the runs)
-TRAFFIC_ENCODE_W2 = 3.3345e5 * 2048 + 6.7991e5 * 1024            # encode_screen_kernel, workload 2
-TRAFFIC_DECODE_SLICE = 0.5 * ((1.4004e5 + 1.4063e5) * 2048) + 1.0486e6 * 1024  # mean of both kernels
+# `--profile decode`, scaled by the readings of a plain 1 GiB copy: FETCH_SIZE counts 2 KiB units,
+# WRITE_SIZE 1 KiB units (the readings are in profiles/rvq_encode_workload2.txt and
+# profiles/rvq_decode_workload3_slice.txt)
+TRAFFIC_ENCODE_W2 = 1.7764e5 * 2048 + 4.2865e5 * 1024            # encode_screen_kernel, workload 2
+TRAFFIC_DECODE_SLICE = 0.5 * ((1.4005e5 + 1.4058e5) * 2048) + 1.0486e6 * 1024  # mean of both kernels
 
 W2 = dict(N=32768, d=1024, dhat=32, depth=8, K=2048)
 
