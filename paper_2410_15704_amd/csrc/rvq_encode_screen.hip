@@ -19,7 +19,8 @@
 //     LB_g = (smallest screened score of the group) - e_g.  The exact winner lies in a group
 //     with LB_g <= UB, UB = LB + 2 e of the group with the smallest LB.  Those few groups are
 //     re-scored from the same LDS copy with packed fp16 dot products (the best group of every
-//     token in place, the 3 % of further groups from a per-wavefront queue, 32 at a time), and
+//     token by its owner, the 3 % of further groups from a per-wavefront queue, four at a time
+//     with 16 lanes per group), and
 //     every codeword whose lower bound is <= UB is scored exactly (fp32, direct form
 //     sum (r - c)^2, fp32 codebook), ties going to the smallest index.  A token with a single
 //     candidate (97 %) needs no score at all: the row is fetched once and subtracted.  A token
