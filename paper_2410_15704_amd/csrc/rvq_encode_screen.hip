@@ -324,7 +324,8 @@ __device__ __forceinline__ float dot2w(unsigned w, unsigned b, float acc) {
 constexpr int SCR_DT = 2;          // double tiles (64 tokens, one per lane) per wavefront
 constexpr int SCR_WTOK = 64 * SCR_DT;  // tokens per wavefront
 
-template <int DT>
+// SC: the (padded) codebook fits the LDS copy whole; otherwise it is swept in pieces of SCR_KC
+template <int DT, bool SC>
 __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const ScreenArgs a) {
 #ifdef RVQ_PHASE_CLOCKS
   long long phase_acc[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
@@ -346,7 +347,9 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  // the wavefront's number as a scalar: what derives from it (its token slots, its queue, the
+  // first vector of its chunk) then lives in scalar registers
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int h = lane >> 5;
   // A workgroup walks the chunks of SCR_TOKENS vectors blockIdx.x, blockIdx.x + gridDim.x, ...;
   // vbase is the first vector of this wavefront in the chunk it is working on (the two teams may
@@ -462,7 +465,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
     dma(a.perm16 + (int64_t)st * a.Kpad + cb, lds_p, kcc * 2);
     dma(a.C16 + ((int64_t)st * a.Kpad + cb) * 4, lds_A, kcc * 64);
   };
-  const bool single_chunk = a.Kpad <= SCR_KC;
+  constexpr bool single_chunk = SC;
   // A stage has two phases.  Phase L works against the stage's operands in LDS (sweep on the
   // matrix cores, fp16 re-scores); phase T touches only registers, the token's candidate list
   // and the fp32 codebook in L2 (exact scores, code, residual update, operands of the next
@@ -589,6 +592,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
 
   // ---- phase L of a stage: everything that reads the stage's operands in LDS
   auto lds_phase = [&](int stage) {
+    // (a codebook that fits has one piece: the bound is a constant, and the loop goes away)
     for (int cbase = 0; cbase < a.Kpad; cbase += SCR_KC) {
       const int kc = min(SCR_KC, a.Kpad - cbase);
       const int ntiles = kc >> 5;
@@ -670,9 +674,19 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
       // bound is already inside the stored norms).  Returns the survivors as a 16-bit mask:
       // bit 4 b + i stands for tile row 8 b + 4 hh + i.
       auto rescore = [&](int tl, int hh, const unsigned (&Bx)[16], float tadj, bool act) -> unsigned {
-        const uint2 *tile = reinterpret_cast<const uint2 *>(lds_A) + tl * 256;
         const int swz = tl & 31;  // row m of tile tl is stored in slot m ^ swz
-        const float *nrow = lds_n + (tl * 2 + hh) * 16;
+        // All eight pieces of a row lie in one pair of LDS banks, the pair (slot mod 16), and every
+        // lane reads another tile: with the same row order in all lanes the 64 reads of an
+        // instruction fall on the 16 pairs at random (twice the cycles of an even spread).  So lane
+        // l takes the rows of its group in the order j ^ x: x is chosen so that the three bits of
+        // the pair that the row decides equal those of l ^ j, which spreads the lanes evenly
+        // whatever tiles they read (the fourth bit is the lane half of the group: not ours to pick).
+        const int x = (lane ^ ((tl & 3) | ((tl >> 1) & 12))) & 15;
+        // uint2 index of row x's first piece; rows j ^ x follow by XOR with a constant, because
+        // row -> slot is linear over XOR (bits 0, 1 stay, bits 2, 3 move to 3, 4)
+        const unsigned a0 = (unsigned)tl * 256u + (unsigned)(((8 * (x >> 2) + (x & 3)) | (4 * hh)) ^ swz);
+        const unsigned n0 = (unsigned)(tl * 2 + hh) * 16u + (unsigned)x;  // index of row x's norm
+        const uint2 *A2 = reinterpret_cast<const uint2 *>(lds_A);
         unsigned mask = 0;
         constexpr int RB = 2;  // rows per step: their reads are issued together (more rows in
                                // flight cost registers that the kernel does not have)
@@ -682,12 +696,12 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
           float nvv[RB];
 #pragma unroll
           for (int i = 0; i < RB; ++i) {
-            const int rr = RB * b4 + i;
-            const uint2 *row = tile + ((8 * (rr >> 2) + 4 * hh + (rr & 3)) ^ swz);
+            const int j = RB * b4 + i;
+            const uint2 *row = A2 + (a0 ^ (unsigned)(8 * (j >> 2) + (j & 3)));
             // piece (q, pc) of lane half hx holds channels 16 hx + 8 q + 4 pc .. + 3
 #pragma unroll
             for (int pc8 = 0; pc8 < 8; ++pc8) w[i][pc8] = row[(pc8 & 3) * 64 + (pc8 >> 2) * 32];
-            nvv[i] = nrow[rr];
+            nvv[i] = lds_n[n0 ^ (unsigned)j];
           }
 #pragma unroll
           for (int i = 0; i < RB; ++i) {
@@ -700,7 +714,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
               acc1 = dot2w(w[i][4 + pc4].y, Bx[8 + 2 * pc4 + 1], acc1);
             }
             const float sc = (acc0 + acc1) + nvv[i];
-            mask |= (sc <= tadj ? 1u : 0u) << (RB * b4 + i);
+            mask |= (sc <= tadj ? 1u : 0u) << ((RB * b4 + i) ^ x);  // bit = the row's number
           }
         }
         mask = act ? mask : 0u;
@@ -1030,47 +1044,37 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
     __syncthreads();
     PHASE_MARK(2);  // staging
   }
-  // sg counts the (chunk, stage) pairs of this workgroup: stage sg % nst of its chunk sg / nst.
-  // The teams carry straight on from the last stage of one chunk to the first of the next (the
-  // tail phase of a chunk's last stage stores its residuals and loads the next chunk), so the
-  // half-idle first and last half-steps are paid once per workgroup, not once per chunk.
+  // sg counts the (chunk, stage) steps of this workgroup: stage sg % nst of its chunk sg / nst.
+  // A wavefront carries straight on from the last stage of one chunk to the first of the next
+  // (the tail phase of a chunk's last stage stores its residuals; the next chunk is loaded at the
+  // top of the following step), so input load and first operand copy are not paid per chunk at a
+  // barrier.  Both teams run the same sequence L(0) T(0) L(1) T(1) ...; they differ in who copies.
   const int SG = nmy * nst;
-  for (int hs = 0; hs <= 2 * SG; ++hs) {
-    const int sg = hs >> 1;
-    const bool even = (hs & 1) == 0;
-    // one call site per phase: the two teams differ only in which half-step runs which
-    const bool do_lds = team == 0 ? (even && sg < SG) : !even;
-    const bool do_tail = team == 0 ? !even : (even && sg >= 1);
+  for (int sg = 0; sg < SG; ++sg) {
     if (load_next >= 0) {  // the first chunk, or the one after a chunk's last stage
       load_chunk(load_next);
       load_next = -1;
       PHASE_MARK(0);  // input load
       convert(a.stage_begin);
     }
-    if (do_lds) {
-      const int i = sg % nst;
-      if (single_chunk && sg > 0 && nst > 1) {  // (one stage per call: the operands stay)
-        if (team == 0) {
-          spin_ge(0, 4u * sg);
-          spin_ge(1, 4u * sg);
-          PHASE_MARK(8);  // waiting for the end of the previous stage's phase L
-          stage_to_lds(a.stage_begin + i, 0, a.Kpad, wave, SCR_WAVES / 2);
-          __builtin_amdgcn_s_waitcnt(0x0f70);
-          signal(2);
-        }
-        spin_ge(2, 4u * sg);
-        PHASE_MARK(2);  // staging
+    const int i = sg % nst;
+    if (single_chunk && sg > 0 && nst > 1) {  // (one stage per call: the operands stay)
+      if (team == 0) {
+        spin_ge(0, 4u * sg);
+        spin_ge(1, 4u * sg);
+        PHASE_MARK(8);  // waiting for the end of the previous stage's phase L
+        stage_to_lds(a.stage_begin + i, 0, a.Kpad, wave, SCR_WAVES / 2);
+        __builtin_amdgcn_s_waitcnt(0x0f70);
+        signal(2);
       }
-      lds_phase(a.stage_begin + i);
-      if (single_chunk) signal(team);
+      spin_ge(2, 4u * sg);
+      PHASE_MARK(2);  // staging
     }
-    if (do_tail) {
-      const int sgt = team == 0 ? sg : sg - 1;
-      const int i = sgt % nst;
-      const int64_t nextc = (sgt + 1 < SG && i == nst - 1)
-                                ? (int64_t)blockIdx.x + (int64_t)(sgt / nst + 1) * gridDim.x : -1;
-      tail_phase(a.stage_begin + i, nextc);
-    }
+    lds_phase(a.stage_begin + i);
+    if (single_chunk) signal(team);
+    const int64_t nextc = (sg + 1 < SG && i == nst - 1)
+                              ? (int64_t)blockIdx.x + (int64_t)(sg / nst + 1) * gridDim.x : -1;
+    tail_phase(a.stage_begin + i, nextc);
   }
 
   // statistics: one update per workgroup (the counters are shared by the whole grid)
@@ -1139,15 +1143,23 @@ hipError_t rvq_launch_encode_screen(const rvq_ctx *ctx, const void *dX, int64_t 
   if (grid64 < 1) return hipSuccess;
   const dim3 grid((unsigned)grid64), block(64 * SCR_WAVES);
   hipError_t e;
-#define RVQ_LAUNCH_SCREEN(DT)                                                                   \
-  e = hipFuncSetAttribute(reinterpret_cast<const void *>(&encode_screen_kernel<DT>),            \
+#define RVQ_LAUNCH_SCREEN(DT, SC)                                                               \
+  e = hipFuncSetAttribute(reinterpret_cast<const void *>(&encode_screen_kernel<DT, SC>),        \
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)SCR_LDS_BYTES);      \
   if (e != hipSuccess) return e;                                                                \
-  hipLaunchKernelGGL(encode_screen_kernel<DT>, grid, block, SCR_LDS_BYTES, s, a)
-  switch (c.in_dtype) {
-    case RVQ_F32: RVQ_LAUNCH_SCREEN(RVQ_F32); break;
-    case RVQ_BF16: RVQ_LAUNCH_SCREEN(RVQ_BF16); break;
-    default: RVQ_LAUNCH_SCREEN(RVQ_F16); break;
+  hipLaunchKernelGGL((encode_screen_kernel<DT, SC>), grid, block, SCR_LDS_BYTES, s, a)
+  if (a.Kpad <= SCR_KC) {
+    switch (c.in_dtype) {
+      case RVQ_F32: RVQ_LAUNCH_SCREEN(RVQ_F32, true); break;
+      case RVQ_BF16: RVQ_LAUNCH_SCREEN(RVQ_BF16, true); break;
+      default: RVQ_LAUNCH_SCREEN(RVQ_F16, true); break;
+    }
+  } else {
+    switch (c.in_dtype) {
+      case RVQ_F32: RVQ_LAUNCH_SCREEN(RVQ_F32, false); break;
+      case RVQ_BF16: RVQ_LAUNCH_SCREEN(RVQ_BF16, false); break;
+      default: RVQ_LAUNCH_SCREEN(RVQ_F16, false); break;
+    }
   }
 #undef RVQ_LAUNCH_SCREEN
   return hipGetLastError();
