@@ -186,34 +186,6 @@ __device__ __noinline__ int exact_scan(const float *__restrict__ Cs, int K, cons
   return bk == 0x7fffffff ? 0 : bk;
 }
 
-// Exact distances of one vector (the same in every lane) to one codeword per lane, and the
-// nearest of them over the wavefront (ties to the smallest index; 0x7fffffff if no lane has a
-// valid codeword).  Out of line for the same reason as exact_scan: 1.8 % of the tokens of the
-// first stage need it, none later.
-__device__ __noinline__ int exact_best_of_lanes(const float *__restrict__ Cs, const float *vec,
-                                                unsigned gk, bool gvalid) {
-  const f32x4 *crow = reinterpret_cast<const f32x4 *>(Cs + (int64_t)(gvalid ? gk : 0u) * 32);
-  float dist = 0.f;
-#pragma unroll
-  for (int c4 = 0; c4 < 8; ++c4) {
-    const f32x4 cw = crow[c4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const float dlt = vec[c4 * 4 + e] - cw[e];
-      dist = fmaf(dlt, dlt, dist);
-    }
-  }
-  float bd = gvalid ? dist : INFINITY;
-  int bk = gvalid ? (int)gk : 0x7fffffff;
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const float od = __shfl_xor(bd, o, 64);
-    const int ok2 = __shfl_xor(bk, o, 64);
-    if (od < bd || (od == bd && ok2 < bk)) { bd = od; bk = ok2; }
-  }
-  return bk;
-}
-
 // pieces of the sweep's reduction of one accumulator set: R1 folds the 16 scores of a lane into two
 // partial minima (reads the accumulators), R2 finishes the group's tagged lower bound and merges
 // it into the three smallest of token tile TT
@@ -885,8 +857,6 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
                 const int src = __ffsll((long long)ovm) - 1;
                 ovm &= ovm - 1;
                 n_over += 1;
-                float rr32[32];
-                broadcast_token(k, src, rr32);
                 const int gi = lane >> 4, rw = lane & 15;  // lane -> (group of the window, row)
                 const float ge0 = __shfl(w.e0, src, 64), ge1 = __shfl(w.e1, src, 64);
                 const float ge2 = __shfl(w.e2, src, 64), ge3 = __shfl(w.e3, src, 64);
@@ -898,7 +868,33 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
                 const int gm = 8 * (rw >> 2) + 4 * ghh + (rw & 3);
                 const unsigned gk = ((gpend >> gi) & 1u) ? (unsigned)lds_p[gtl * 32 + gm] : 0xffffu;
                 const bool gvalid = gk < (unsigned)a.K;
-                const int bk = exact_best_of_lanes(a.C32 + (int64_t)stage * a.K * 32, rr32, gk, gvalid);
+                // exact distance of the token to this lane's row.  The token's residual comes out
+                // of its owner's registers as scalars (src is uniform), so it costs no vector
+                // registers and no trip through memory.
+                const f32x4 *crow = reinterpret_cast<const f32x4 *>(
+                    a.C32 + ((int64_t)stage * a.K + (gvalid ? gk : 0u)) * 32);
+                float dist = 0.f;
+#pragma unroll
+                for (int c4 = 0; c4 < 8; ++c4) {
+                  const f32x4 cw = crow[c4];
+#pragma unroll
+                  for (int e = 0; e < 4; ++e) {
+                    const int j = c4 * 4 + e;
+                    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, r[0][j]), src));
+                    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, r[1][j]), src));
+                    const float dlt = (k == 0 ? r0 : r1) - cw[e];
+                    dist = fmaf(dlt, dlt, dist);
+                  }
+                }
+                static_assert(SCR_DT == 2, "the double tile is picked with one select");
+                float bd = gvalid ? dist : INFINITY;
+                int bk = gvalid ? (int)gk : 0x7fffffff;
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) {  // nearest over the wavefront, ties to the smallest index
+                  const float od = __shfl_xor(bd, o, 64);
+                  const int ok2 = __shfl_xor(bk, o, 64);
+                  if (od < bd || (od == bd && ok2 < bk)) { bd = od; bk = ok2; }
+                }
                 // bk == 0x7fffffff cannot happen for a token with candidates; it would leave the
                 // token without one and send it to the wavefront search below
                 if (lane == src) {
