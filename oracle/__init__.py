@@ -7,7 +7,9 @@ this module and this module never imports the product package.
 The arithmetic lives in ``rvq_oracle.c`` (plain C, double precision, compiled
 with gcc); this file only marshals numpy arrays into it.  Function names and
 argument order mirror the C file; see its header for the paper passages each
-function follows and for the readings taken where the paper is silent.
+function follows and for the readings taken where the paper is silent.  Two functions are
+written out here in numpy on top of the C routines: ``decode_rope`` (the rotation of decoded pairs)
+and ``attn_decode`` (softmax attention of one query over decoded keys and values).
 """
 from __future__ import annotations
 
@@ -318,6 +320,50 @@ def decode_rope(codes, std, C, d: int, grouping: int, cos, sin, head_dim: int,
     out[..., 0] = xr[..., 0] * c - xr[..., 1] * s_
     out[..., 1] = xr[..., 0] * s_ + xr[..., 1] * c
     return out.reshape(N, d)
+
+
+def attn_decode(q, kcodes, kstd, Ck, k_grouping: int, vcodes, vstd, Cv, v_grouping: int,
+                cos, sin, scale: float, n_kv_heads: int):
+    """Attention of one query position over a cache that holds RVQ codes instead of keys and
+    values (Section 3: one quantizer for the key and one for the value projection of an attention
+    block, applied before the rotary embedding; the Conclusion names the cost of decoding inside
+    attention as the open efficiency question).  Head vectors of hd = q.shape[1] channels are the
+    rows of both quantizers: row n * n_kv_heads + h is head h of token n.
+
+      k[n,h] = rotate(decode(kcodes, kstd)[n * Hkv + h], cos[n], sin[n])    (decode_rope)
+      v[n,h] = decode(vcodes, vstd)[n * Hkv + h]
+      s[a,n] = scale * q[a] . k[n, a // rep]          rep = Hq // Hkv query heads per kv head
+      p[a,:] = softmax over n of s[a,:]
+      out[a] = sum_n p[a,n] v[n, a // rep]
+
+    Plain definition in float64, no blocking, the softmax with its maximum subtracted.
+    q [Hq][hd]; codes [N * Hkv][hd / 32][depth]; std [N * Hkv]; cos, sin [N][hd / 2].
+    Returns [Hq][hd] float64."""
+    q = _f64(q)
+    Hq, hd = q.shape
+    Hkv = int(n_kv_heads)
+    if Hq % Hkv:
+        raise ValueError("query heads must be a multiple of kv heads")
+    rep = Hq // Hkv
+    rows = np.asarray(kcodes).shape[0]
+    if rows % Hkv or np.asarray(vcodes).shape[0] != rows:
+        raise ValueError("rows must be tokens x kv heads for both caches")
+    N = rows // Hkv
+    if N < 1:
+        raise ValueError("attention over an empty cache is undefined")
+    cos = _f64(cos)
+    sin = _f64(sin)
+    # every head of a token is turned by that token's angles
+    k = decode_rope(kcodes, kstd, Ck, hd, k_grouping, np.repeat(cos, Hkv, axis=0),
+                    np.repeat(sin, Hkv, axis=0), hd).reshape(N, Hkv, hd)
+    v = decode(vcodes, vstd, Cv, hd, v_grouping).reshape(N, Hkv, hd)
+    out = np.empty((Hq, hd), dtype=np.float64)
+    for a in range(Hq):
+        h = a // rep
+        s = float(scale) * (k[:, h, :] @ q[a])
+        w = np.exp(s - s.max())
+        out[a] = (w / w.sum()) @ v[:, h, :]
+    return out
 
 
 def code_bits(K: int) -> int:

@@ -514,3 +514,108 @@ def test_decode_rope_against_complex_multiplication_and_special_angles():
                       w[..., 0] * s2[:, None] + w[..., 1] * c2[:, None]], axis=-1).reshape(N, d)
     np.testing.assert_allclose(twice, oracle.decode_rope(codes, std, C, d, oracle.STRIDED, c3, s3, hd),
                                rtol=1e-9, atol=1e-9)
+
+
+# ---- Section 3 / Conclusion: attention over a cache of codes --------------------------------------
+def _attn_case(rng, N, Hkv, rep, hd=64, depth=3, K=20):
+    G = hd // 32
+    Ck = rng.standard_normal((depth, K, 32))
+    Cv = rng.standard_normal((depth, K, 32))
+    kc = rng.integers(0, K, (N * Hkv, G, depth))
+    vc = rng.integers(0, K, (N * Hkv, G, depth))
+    ks = np.exp(0.3 * rng.standard_normal(N * Hkv))
+    vs = np.exp(0.3 * rng.standard_normal(N * Hkv))
+    q = rng.standard_normal((Hkv * rep, hd))
+    cos, sin = oracle.rope_tables(rng.integers(0, 4000, N), hd)
+    return q, kc, ks, Ck, vc, vs, Cv, cos, sin
+
+
+def test_attn_decode_against_explicit_loops_and_library_softmax():
+    """The attention oracle against (1) scalar loops with math.exp over explicitly decoded and
+    rotated keys, (2) scipy's softmax + matmul when the rotation is the identity, and the cases
+    the definition fixes: one token returns its value vector, a zero query or scale 0 returns the
+    mean of the values, a key that dominates returns its value, and the result over a cache cut in
+    two equals the log-sum-exp merge of the two parts."""
+    import math
+    from scipy.special import logsumexp, softmax
+    rng = np.random.Generator(np.random.PCG64(2024))
+    N, Hkv, rep, hd = 13, 2, 3, 64
+    q, kc, ks, Ck, vc, vs, Cv, cos, sin = _attn_case(rng, N, Hkv, rep, hd)
+    scale = 1.0 / math.sqrt(hd)
+    out = oracle.attn_decode(q, kc, ks, Ck, oracle.STRIDED, vc, vs, Cv, oracle.CONTIGUOUS, cos, sin,
+                             scale, Hkv)
+    # (1) scalar loops over what decode and decode_rope return row by row
+    kx = oracle.decode(kc, ks, Ck, hd, oracle.STRIDED)
+    vx = oracle.decode(vc, vs, Cv, hd, oracle.CONTIGUOUS)
+    for a in range(Hkv * rep):
+        h = a // rep
+        sc = []
+        for n in range(N):
+            row = kx[n * Hkv + h]
+            dot = 0.0
+            for i in range(hd // 2):
+                x0, x1 = row[2 * i], row[2 * i + 1]
+                dot += q[a, 2 * i] * (x0 * cos[n, i] - x1 * sin[n, i])
+                dot += q[a, 2 * i + 1] * (x0 * sin[n, i] + x1 * cos[n, i])
+            sc.append(scale * dot)
+        mx = max(sc)
+        w = [math.exp(v - mx) for v in sc]
+        tot = sum(w)
+        want = np.zeros(hd)
+        for n in range(N):
+            want += (w[n] / tot) * vx[n * Hkv + h]
+        np.testing.assert_allclose(out[a], want, rtol=1e-11, atol=1e-12)
+    # (2) identity rotation: library softmax and matmul
+    one, zero = np.ones_like(cos), np.zeros_like(sin)
+    o2 = oracle.attn_decode(q, kc, ks, Ck, oracle.CONTIGUOUS, vc, vs, Cv, oracle.STRIDED, one, zero,
+                            scale, Hkv)
+    kk = oracle.decode(kc, ks, Ck, hd, oracle.CONTIGUOUS).reshape(N, Hkv, hd)
+    vv = oracle.decode(vc, vs, Cv, hd, oracle.STRIDED).reshape(N, Hkv, hd)
+    for a in range(Hkv * rep):
+        h = a // rep
+        np.testing.assert_allclose(o2[a], softmax(scale * kk[:, h] @ q[a]) @ vv[:, h], rtol=1e-11, atol=1e-12)
+    # one token: its value, whatever the query
+    sel = slice(0, Hkv)
+    o1 = oracle.attn_decode(q, kc[sel], ks[sel], Ck, oracle.STRIDED, vc[sel], vs[sel], Cv,
+                            oracle.CONTIGUOUS, cos[:1], sin[:1], scale, Hkv)
+    for a in range(Hkv * rep):
+        np.testing.assert_allclose(o1[a], vx[a // rep], rtol=1e-13, atol=1e-13)
+    # zero query / zero scale: the mean of the values
+    vm = vx.reshape(N, Hkv, hd).mean(0)
+    for qq, sc_ in ((np.zeros_like(q), scale), (q, 0.0)):
+        o0 = oracle.attn_decode(qq, kc, ks, Ck, oracle.STRIDED, vc, vs, Cv, oracle.CONTIGUOUS, cos, sin,
+                                sc_, Hkv)
+        for a in range(Hkv * rep):
+            np.testing.assert_allclose(o0[a], vm[a // rep], rtol=1e-12, atol=1e-12)
+    # a dominating key: the query is 200 x the rotated key of token 5, head 0
+    kr = oracle.decode_rope(kc, ks, Ck, hd, oracle.STRIDED, np.repeat(cos, Hkv, 0), np.repeat(sin, Hkv, 0), hd)
+    qd = q.copy()
+    qd[0] = 200.0 * kr[5 * Hkv + 0] / scale / (kr[5 * Hkv + 0] @ kr[5 * Hkv + 0]) * 5.0
+    od = oracle.attn_decode(qd, kc, ks, Ck, oracle.STRIDED, vc, vs, Cv, oracle.CONTIGUOUS, cos, sin, scale, Hkv)
+    sc5 = scale * (kr.reshape(N, Hkv, hd)[:, 0] @ qd[0])
+    if np.sort(sc5)[-1] - np.sort(sc5)[-2] > 60 and sc5.argmax() == 5:
+        np.testing.assert_allclose(od[0], vx[5 * Hkv + 0], rtol=1e-12, atol=1e-12)
+    else:  # the planted key must at least be the largest weight
+        assert sc5.argmax() == 5
+    # cut in two: merge with log-sum-exp weights
+    cut = 6
+    parts = []
+    for lo, hi in ((0, cut), (cut, N)):
+        rs = slice(lo * Hkv, hi * Hkv)
+        o = oracle.attn_decode(q, kc[rs], ks[rs], Ck, oracle.STRIDED, vc[rs], vs[rs], Cv, oracle.CONTIGUOUS,
+                               cos[lo:hi], sin[lo:hi], scale, Hkv)
+        lse = np.array([logsumexp(scale * (kr.reshape(N, Hkv, hd)[lo:hi, a // rep] @ q[a]))
+                        for a in range(Hkv * rep)])
+        parts.append((o, lse))
+    tot = np.logaddexp(parts[0][1], parts[1][1])
+    merged = sum(o * np.exp(l - tot)[:, None] for o, l in parts)
+    np.testing.assert_allclose(merged, out, rtol=1e-11, atol=1e-12)
+
+
+def test_attn_decode_rejects_bad_shapes():
+    rng = np.random.Generator(np.random.PCG64(5))
+    q, kc, ks, Ck, vc, vs, Cv, cos, sin = _attn_case(rng, 4, 2, 2)
+    with pytest.raises(ValueError):
+        oracle.attn_decode(q[:3], kc, ks, Ck, 0, vc, vs, Cv, 0, cos, sin, 1.0, 2)
+    with pytest.raises(ValueError):
+        oracle.attn_decode(q, kc[:0], ks[:0], Ck, 0, vc[:0], vs[:0], Cv, 0, cos[:0], sin[:0], 1.0, 2)
