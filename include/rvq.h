@@ -174,6 +174,42 @@ int rvq_decode_rope(rvq_ctx *ctx, const int16_t *dCodes, const void *dStd, int64
                     void *dOut, int64_t ldo, void *stream);
 
 /*
+ * Attention of one query position over a cache that holds codes instead of keys and values
+ * (Section 3: one quantizer on the key and one on the value projection of an attention block, keys
+ * quantized before the rotary embedding; the Conclusion names the cost of decoding inside
+ * attention as the open efficiency question).  Nothing is written out in between: every
+ * (token, kv head) is decoded in registers, the key is rotated and scored, the value enters an
+ * online softmax accumulation.  Head vectors are the rows of both quantizers, row n * n_kv_heads + h
+ * being head h of token n (what rvq_encode produces from [N * n_kv_heads][128] inputs):
+ *   k[n,h] = rotate(decode_k(row))   (the rotation of rvq_decode_rope with head_dim 128)
+ *   v[n,h] = decode_v(row)
+ *   out[a] = sum_n softmax_n(scale * dQ[a] . k[n, a / rep]) v[n, a / rep],  rep = n_q_heads / n_kv_heads
+ * computed in fp32 (softmax with its running maximum, in base 2), fp32 output.
+ *   kctx, vctx  contexts of the two quantizers: d == 128, dhat == 32, the same depth (1..8), any
+ *               grouping and K each, codebooks set, same device
+ *   dQ          device, float [n_q_heads][128]: the query heads, already rotated to their position
+ *   n_q_heads / n_kv_heads   1, 2, 4 or 8 query heads per kv head
+ *   dKCodes, dVCodes  device, int16 [N * n_kv_heads][4][depth]; codes outside [0, K) are clamped
+ *   dKStd, dVStd      device, [N * n_kv_heads] of the context's std_dtype; NULL (= 1) only for a
+ *                     context with cfg.scale == 0
+ *   N           tokens in the cache, >= 1
+ *   dCos, dSin  device, float [N][64]: the angles of every token's position; both NULL = no rotation
+ *   scale       softmax scale (1 / sqrt(128) in the usual formulation)
+ *   dOut        device, float [n_q_heads][128]
+ *   dWorkspace  device, workspace_bytes >= rvq_attn_workspace_bytes(N, n_q_heads, n_kv_heads)
+ *               (partial results of the splits of the cache; contents are unspecified afterwards);
+ *               caller-owned, so that the call allocates nothing
+ * Errors: RVQ_EINVAL (shapes, NULL, alignment, N < 1), RVQ_EWORKSPACE (workspace too small),
+ * RVQ_ENOCODEBOOK.  rvq_attn_workspace_bytes returns 0 for arguments that are not positive.
+ */
+int64_t rvq_attn_workspace_bytes(int64_t N, int32_t n_q_heads, int32_t n_kv_heads);
+int rvq_attn_decode(rvq_ctx *kctx, rvq_ctx *vctx, const float *dQ, int32_t n_q_heads,
+                    int32_t n_kv_heads, const int16_t *dKCodes, const void *dKStd,
+                    const int16_t *dVCodes, const void *dVStd, int64_t N, const float *dCos,
+                    const float *dSin, float scale, float *dOut, void *dWorkspace,
+                    int64_t workspace_bytes, void *stream);
+
+/*
  * Packed code storage (Section 3.2: the compression rate of 5.5x counts log2(K) bits per code and a
  * half-precision std; int16 storage gives 3.98x).  The depth codes of one (token, group) become
  * one record of rvq_packed_record_bytes() = ceil(depth * b / 8) bytes, b = the smallest number of

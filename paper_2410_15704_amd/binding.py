@@ -31,7 +31,7 @@ EXPORTS = ("rvq_create", "rvq_destroy", "rvq_set_codebooks", "rvq_get_codebooks"
            "rvq_get_counters", "rvq_packed_record_bytes", "rvq_pack_codes", "rvq_unpack_codes",
            "rvq_decode_packed", "rvq_decode_rope", "rvq_reserve", "rvq_reserved_rows",
            "rvq_check_kernels", "rvq_debug_set_wait_polls", "rvq_encode_static",
-           "rvq_probe_gather_rates")
+           "rvq_probe_gather_rates", "rvq_attn_decode", "rvq_attn_workspace_bytes")
 
 
 class rvq_config(ctypes.Structure):
@@ -72,10 +72,13 @@ def _load():
     lib.rvq_strerror.restype = ctypes.c_char_p
     lib.rvq_last_hip_error.argtypes = [vp]
     lib.rvq_version.restype = ctypes.c_int
+    lib.rvq_attn_workspace_bytes.argtypes = [i64, i32, i32]
+    lib.rvq_attn_workspace_bytes.restype = i64
+    lib.rvq_attn_decode.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, i64, vp, vp, f32, vp, vp, i64, vp]
     for name in EXPORTS:
         getattr(lib, name)
         if name not in ("rvq_strerror", "rvq_version", "rvq_packed_record_bytes",
-                        "rvq_reserved_rows"):
+                        "rvq_reserved_rows", "rvq_attn_workspace_bytes"):
             getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -215,6 +218,18 @@ def rvq_decode_packed(ctx, dPacked, dStd, N, depth_used, dOut, ldo, stream=None)
 def rvq_decode_rope(ctx, dCodes, dStd, N, depth_used, dCos, dSin, head_dim, dOut, ldo, stream=None):
     return _chk(lib.rvq_decode_rope(ctx, _ptr(dCodes), _ptr(dStd), N, depth_used, _ptr(dCos),
                                     _ptr(dSin), head_dim, _ptr(dOut), ldo, _stream(stream)), ctx)
+
+
+def rvq_attn_workspace_bytes(N, n_q_heads, n_kv_heads):
+    return int(lib.rvq_attn_workspace_bytes(N, n_q_heads, n_kv_heads))
+
+
+def rvq_attn_decode(kctx, vctx, dQ, n_q_heads, n_kv_heads, dKCodes, dKStd, dVCodes, dVStd, N, dCos,
+                    dSin, scale, dOut, dWorkspace, workspace_bytes, stream=None):
+    return _chk(lib.rvq_attn_decode(kctx, vctx, _ptr(dQ), n_q_heads, n_kv_heads, _ptr(dKCodes),
+                                    _ptr(dKStd), _ptr(dVCodes), _ptr(dVStd), N, _ptr(dCos), _ptr(dSin),
+                                    scale, _ptr(dOut), _ptr(dWorkspace), workspace_bytes,
+                                    _stream(stream)), kctx)
 
 
 def rvq_get_counters(ctx):

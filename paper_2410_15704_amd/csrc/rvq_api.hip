@@ -412,4 +412,38 @@ int rvq_ema_update(rvq_ctx *ctx, int32_t stage, const float *dR, const int16_t *
   return RVQ_OK;
 }
 
+int64_t rvq_attn_workspace_bytes(int64_t N, int32_t n_q_heads, int32_t n_kv_heads) {
+  if (N < 1 || n_q_heads < 1 || n_kv_heads < 1) return 0;
+  return (int64_t)(rvq_attn_workspace_floats(N, n_q_heads, n_kv_heads) * sizeof(float));
+}
+
+int rvq_attn_decode(rvq_ctx *kctx, rvq_ctx *vctx, const float *dQ, int32_t n_q_heads,
+                    int32_t n_kv_heads, const int16_t *dKCodes, const void *dKStd,
+                    const int16_t *dVCodes, const void *dVStd, int64_t N, const float *dCos,
+                    const float *dSin, float scale, float *dOut, void *dWorkspace,
+                    int64_t workspace_bytes, void *stream) {
+  if (!kctx || !vctx) return RVQ_EINVAL;
+  const rvq_config &kc = kctx->cfg, &vc = vctx->cfg;
+  // heads of 128 channels in four groups of 32; one to eight stages; both caches on one device
+  if (kc.d != 128 || vc.d != 128 || kc.dhat != 32 || vc.dhat != 32) return RVQ_EINVAL;
+  if (kc.depth != vc.depth || kc.depth < 1 || kc.depth > 8) return RVQ_EINVAL;
+  if (kctx->device != vctx->device) return RVQ_EINVAL;
+  if (n_kv_heads < 1 || n_q_heads < n_kv_heads || n_q_heads % n_kv_heads != 0) return RVQ_EINVAL;
+  const int rep = n_q_heads / n_kv_heads;
+  if (rep != 1 && rep != 2 && rep != 4 && rep != 8) return RVQ_EINVAL;
+  if (N < 1 || N > (INT64_MAX / 1024) / n_kv_heads) return RVQ_EINVAL;  // softmax over nothing
+  if (!(scale == scale) || !dQ || !dKCodes || !dVCodes || !dOut || !dWorkspace) return RVQ_EINVAL;
+  if ((dCos == nullptr) != (dSin == nullptr)) return RVQ_EINVAL;
+  if (!aligned16(dQ) || !aligned16(dKCodes) || !aligned16(dVCodes) || !aligned16(dOut) ||
+      !aligned16(dWorkspace))
+    return RVQ_EINVAL;
+  if ((kc.scale && !dKStd) || (vc.scale && !dVStd)) return RVQ_EINVAL;
+  if (workspace_bytes < rvq_attn_workspace_bytes(N, n_q_heads, n_kv_heads)) return RVQ_EWORKSPACE;
+  if (!kctx->have_codebooks || !vctx->have_codebooks) return RVQ_ENOCODEBOOK;
+  RVQ_HIP(kctx, rvq_launch_attn_decode(kctx, vctx, dQ, n_q_heads, n_kv_heads, dKCodes, dKStd, dVCodes,
+                                       dVStd, N, dCos, dSin, scale, kc.depth, vc.depth, dOut,
+                                       (float *)dWorkspace, (hipStream_t)stream));
+  return RVQ_OK;
+}
+
 }  // extern "C"
