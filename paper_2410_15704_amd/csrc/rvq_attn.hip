@@ -51,46 +51,80 @@ __device__ __forceinline__ float att_load_std(const void *p, int dt, int64_t row
 }
 __device__ __forceinline__ int att_clamp(int k, int K) { return k < 0 ? 0 : (k >= K ? K - 1 : k); }
 
-// the codes of one (row, group): up to eight int16
-struct AttCodes { int c[8]; };
+// The codes of one (row, group): up to eight int16, kept as four 32-bit words (two codes each).
+struct AttCodes { i32x4 w; };
 template <bool D8>
-__device__ __forceinline__ AttCodes att_load_codes(const int16_t *codes, int64_t row, int g, int depth) {
+__device__ __forceinline__ AttCodes att_load_codes(const int16_t *codes, uint32_t elem, int depth) {
   AttCodes r;
-  const int16_t *p = codes + (row * ATT_G + g) * depth;
+  const int16_t *p = codes + elem;  // elem = (row * 4 + g) * depth, below 2^31 (checked by the caller)
   if constexpr (D8) {
-    const i32x4 w = *reinterpret_cast<const i32x4 *>(p);  // depth 8: one aligned 16-byte word
-    const int ww[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      r.c[2 * i] = (int)(int16_t)(ww[i] & 0xffff);
-      r.c[2 * i + 1] = ww[i] >> 16;
-    }
+    r.w = *reinterpret_cast<const i32x4 *>(p);  // depth 8: one aligned 16-byte word
   } else {
+    int c[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) r.c[i] = i < depth ? (int)p[i] : 0;
+    for (int i = 0; i < 8; ++i) c[i] = i < depth ? (int)p[i] & 0xffff : 0;
+    r.w = i32x4{c[0] | (c[1] << 16), c[2] | (c[3] << 16), c[4] | (c[5] << 16), c[6] | (c[7] << 16)};
   }
   return r;
 }
+__device__ __forceinline__ int att_code(const AttCodes &cd, int i) {
+  const int w = i < 2 ? cd.w.x : (i < 4 ? cd.w.y : (i < 6 ? cd.w.z : cd.w.w));
+  return (i & 1) ? (w >> 16) : (int)(int16_t)(w & 0xffff);  // sign-extended, as stored
+}
 
-// sum over the stages, in stage order, of this lane's quarter of the selected codeword rows
-__device__ __forceinline__ f32x4 att_gather(const float *C, int K, const AttCodes &cd, int used, int q8) {
-  f32x4 rows[8];
+// This lane's quarter of the codeword rows that the eight codes select: the loads only.  Cq is
+// the codebook's byte address plus the lane's 16-byte offset; the row offset stays 32 bits
+// (depth * K * 128 bytes < 2^31, checked by the launcher), so a load is base + offset.
+// FULL: all eight stages are used (no condition anywhere near the loads); otherwise stages beyond
+// `used` fetch row 0 of stage 0 and later enter the sum with weight 0.
+template <bool FULL>
+__device__ __forceinline__ void att_issue(const char *Cq, int K, const AttCodes &cd, int used, f32x4 (&rows)[8]) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    // stages beyond `used` fetch row 0 of stage 0 and are left out of the sum: the eight loads
-    // stay unconditional and in flight together
-    const int64_t r = i < used ? (int64_t)i * K + att_clamp(cd.c[i], K) : 0;
-    rows[i] = *reinterpret_cast<const f32x4 *>(C + r * 32 + 4 * q8);
+    const int code = att_clamp(att_code(cd, i), K);  // (max + min: the compiler makes one v_med3 of them)
+    uint32_t off = ((uint32_t)(i * K) + (uint32_t)code) * 128u;
+    if (!FULL) off = i < used ? off : 0u;
+    rows[i] = *reinterpret_cast<const f32x4 *>(Cq + off);
   }
+}
+// their sum in stage order
+template <bool FULL>
+__device__ __forceinline__ f32x4 att_sum(const f32x4 (&rows)[8], int used) {
   f32x4 s = rows[0];
 #pragma unroll
-  for (int i = 1; i < 8; ++i)
-    if (i < used) s += rows[i];
+  for (int i = 1; i < 8; ++i) {
+    if (FULL) {
+      s += rows[i];
+    } else {
+      const float w = i < used ? 1.0f : 0.0f;  // (x * 1 + s rounds as x + s)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) s[e] = fmaf(rows[i][e], w, s[e]);
+    }
+  }
   return s;
 }
 
-template <int REP, bool D8>
+// sums over lanes without LDS traffic (data-parallel-primitive moves): within a row of 16 lanes
+// by two quad permutes and two rotations
+template <int CTRL>
+__device__ __forceinline__ float att_mov_dpp(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float att_sum16(float s) {
+  s += att_mov_dpp<0xB1>(s);   // quad_perm [1,0,3,2]
+  s += att_mov_dpp<0x4E>(s);   // quad_perm [2,3,0,1]
+  s += att_mov_dpp<0x124>(s);  // row_ror:4
+  s += att_mov_dpp<0x128>(s);  // row_ror:8
+  return s;
+}
+
+// FAST: the common case with everything that shapes the loop known at compile time: depth 8 with
+// all stages used, rotation tables given, both std buffers present in half precision.  Otherwise
+// those are run-time conditions (the loop then has branches around its loads and is slower).
+// KS / VS: strided grouping of the key / value quantizer.
+template <int REP, bool FAST, bool KS, bool VS>
 __global__ __launch_bounds__(64 * ATT_WAVES) void attn_partial_kernel(const AttnArgs a) {
+  constexpr bool D8 = FAST;
   __shared__ float sm_m[2 * ATT_WAVES][REP];
   __shared__ float sm_l[2 * ATT_WAVES][REP];
   __shared__ float sm_acc[2 * ATT_WAVES][REP][ATT_HD];
@@ -109,8 +143,8 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_partial_kernel(const Attn
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     const int j = 4 * q8 + e;
-    ck[e] = a.k_strided ? j * ATT_G + g : g * 32 + j;
-    cv[e] = a.v_strided ? j * ATT_G + g : g * 32 + j;
+    ck[e] = KS ? j * ATT_G + g : g * 32 + j;
+    cv[e] = VS ? j * ATT_G + g : g * 32 + j;
   }
   float qv[REP][4];
 #pragma unroll
@@ -127,37 +161,86 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_partial_kernel(const Attn
     for (int e = 0; e < 4; ++e) acc[r][e] = 0.f;
   }
 
+  // Everything of this workgroup's tokens is addressed with 32-bit offsets from bases that are
+  // the same for the whole workgroup (the launcher checks that a split's rows fit).
+  const int64_t row0 = nbeg * a.Hkv + h;                      // row of token nbeg
+  const int16_t *kcb = a.kcodes + row0 * ATT_G * a.depth;
+  const int16_t *vcb = a.vcodes + row0 * ATT_G * a.depth;
+  const char *ksb = a.kstd ? (const char *)a.kstd + row0 * (a.kstd_dtype == RVQ_F32 ? 4 : 2) : nullptr;
+  const char *vsb = a.vstd ? (const char *)a.vstd + row0 * (a.vstd_dtype == RVQ_F32 ? 4 : 2) : nullptr;
+  const float *cosb = a.cos ? a.cos + nbeg * (ATT_HD / 2) : nullptr;
+  const float *sinb = a.cos ? a.sin + nbeg * (ATT_HD / 2) : nullptr;
+  const char *Ckq = reinterpret_cast<const char *>(a.Ck + 4 * q8);
+  const char *Cvq = reinterpret_cast<const char *>(a.Cv + 4 * q8);
+  const uint32_t last = (uint32_t)(nend - nbeg) - 1u;         // last token of the split, relative
+  const uint32_t row_elems = (uint32_t)(a.Hkv * ATT_G * a.depth);  // code elements between tokens
+
   // what a token needs from HBM, fetched one trip ahead (the gathers depend on the codes)
   struct Pre {
     AttCodes kc, vc;
     float ks, vs, cs[4], sn[4];
   };
-  auto fetch = [&](int64_t n, Pre &p) {
-    const int64_t nc = n < nend ? n : nend - 1;  // clamped: loads carry no branch
-    const int64_t row = nc * a.Hkv + h;
-    p.kc = att_load_codes<D8>(a.kcodes, row, g, a.depth);
-    p.vc = att_load_codes<D8>(a.vcodes, row, g, a.depth);
-    p.ks = att_load_std(a.kstd, a.kstd_dtype, row);
-    p.vs = att_load_std(a.vstd, a.vstd_dtype, row);
+  auto fetch = [&](uint32_t t, Pre &p) {
+    const uint32_t tc = t < last ? t : last;  // clamped: loads carry no branch
+    const uint32_t el = tc * row_elems + (uint32_t)(g * a.depth);
+    p.kc = att_load_codes<D8>(kcb, el, a.depth);
+    p.vc = att_load_codes<D8>(vcb, el, a.depth);
+    const uint32_t ro = tc * (uint32_t)a.Hkv;
+    if constexpr (FAST) {
+      p.ks = rvq_f16_bits_to_f32(((const uint16_t *)ksb)[ro]);
+      p.vs = rvq_f16_bits_to_f32(((const uint16_t *)vsb)[ro]);
+      // the lane's four channels lie in the pairs 8 q8 + 2 e + (g >> 1) (strided: two 16-byte
+      // loads per table and a pick) or in the two pairs 16 g + 2 q8, + 1 (contiguous: one 8-byte load)
+      if constexpr (KS) {
+        const f32x4 *cp = reinterpret_cast<const f32x4 *>(cosb + tc * (ATT_HD / 2) + 8 * q8);
+        const f32x4 *sp_ = reinterpret_cast<const f32x4 *>(sinb + tc * (ATT_HD / 2) + 8 * q8);
+        const f32x4 c0 = cp[0], c1 = cp[1], s0 = sp_[0], s1 = sp_[1];
+        const bool hi = (g >> 1) != 0;
+        p.cs[0] = hi ? c0[1] : c0[0]; p.cs[1] = hi ? c0[3] : c0[2];
+        p.cs[2] = hi ? c1[1] : c1[0]; p.cs[3] = hi ? c1[3] : c1[2];
+        p.sn[0] = hi ? s0[1] : s0[0]; p.sn[1] = hi ? s0[3] : s0[2];
+        p.sn[2] = hi ? s1[1] : s1[0]; p.sn[3] = hi ? s1[3] : s1[2];
+      } else {
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        const f32x2 c2 = *reinterpret_cast<const f32x2 *>(cosb + tc * (ATT_HD / 2) + 16 * g + 2 * q8);
+        const f32x2 s2 = *reinterpret_cast<const f32x2 *>(sinb + tc * (ATT_HD / 2) + 16 * g + 2 * q8);
+        p.cs[0] = p.cs[1] = c2[0]; p.cs[2] = p.cs[3] = c2[1];
+        p.sn[0] = p.sn[1] = s2[0]; p.sn[2] = p.sn[3] = s2[1];
+      }
+    } else {
+      p.ks = !ksb ? 1.0f : (a.kstd_dtype == RVQ_F32 ? ((const float *)ksb)[ro]
+                                                    : rvq_f16_bits_to_f32(((const uint16_t *)ksb)[ro]));
+      p.vs = !vsb ? 1.0f : (a.vstd_dtype == RVQ_F32 ? ((const float *)vsb)[ro]
+                                                    : rvq_f16_bits_to_f32(((const uint16_t *)vsb)[ro]));
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      p.cs[e] = a.cos ? a.cos[nc * (ATT_HD / 2) + (ck[e] >> 1)] : 1.0f;
-      p.sn[e] = a.cos ? a.sin[nc * (ATT_HD / 2) + (ck[e] >> 1)] : 0.0f;
+      for (int e = 0; e < 4; ++e) {
+        p.cs[e] = cosb ? cosb[tc * (ATT_HD / 2) + (ck[e] >> 1)] : 1.0f;
+        p.sn[e] = cosb ? sinb[tc * (ATT_HD / 2) + (ck[e] >> 1)] : 0.0f;
+      }
     }
   };
-  auto work = [&](int64_t n, const Pre &p) {
-    const bool valid = n < nend;
-    f32x4 k4 = att_gather(a.Ck, a.Kk, p.kc, a.k_depth_used, q8);
-    f32x4 v4 = att_gather(a.Cv, a.Kv, p.vc, a.v_depth_used, q8);
+  // A wavefront's loads come back in the order they were issued.  So a trip first issues the
+  // gathers of its own token (L2), then the prefetch of the next one (HBM), and only then works on
+  // the gathered rows: waiting for the gathers does not wait for HBM.
+  struct Rows { f32x4 k[8], v[8]; };
+  auto issue = [&](const Pre &p, Rows &R) {
+    att_issue<FAST>(Ckq, a.Kk, p.kc, a.k_depth_used, R.k);
+    att_issue<FAST>(Cvq, a.Kv, p.vc, a.v_depth_used, R.v);
+  };
+  auto work = [&](uint32_t t, const Pre &p, const Rows &R) {
+    const bool valid = t <= last;
+    f32x4 k4 = att_sum<FAST>(R.k, a.k_depth_used);
+    f32x4 v4 = att_sum<FAST>(R.v, a.v_depth_used);
     k4 *= p.ks;
     v4 *= p.vs;
     // rotation: channel c and its partner c ^ 1 are one pair; the partner is element e ^ 1 of
-    // this lane (contiguous groups) or the same element of the lane of group g ^ 1 (strided)
+    // this lane (contiguous groups) or the same element of the lane of group g ^ 1, eight lanes
+    // away in the same row of 16 (strided)
     float kr[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const float mine = k4[e];
-      const float other = a.k_strided ? __shfl_xor(mine, 8, 64) : k4[e ^ 1];
+      const float other = KS ? att_mov_dpp<0x128>(mine) : k4[e ^ 1];
       // even channel: x0 cos - x1 sin; odd channel: x1 cos + x0 sin
       kr[e] = mine * p.cs[e] + ((ck[e] & 1) ? other : -other) * p.sn[e];
     }
@@ -166,13 +249,13 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_partial_kernel(const Attn
       float s = kr[0] * qv[r][0];
 #pragma unroll
       for (int e = 1; e < 4; ++e) s = fmaf(kr[e], qv[r][e], s);
-      // the token's 32 lanes: all of them end up with the whole score
-#pragma unroll
-      for (int o = 16; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+      // the token's 32 lanes = two rows of 16: all of them end up with the whole score
+      s = att_sum16(s);
+      s += __shfl_xor(s, 16, 64);
       s = valid ? s : -3.0e38f;
       const float mn = fmaxf(m[r], s);
-      const float corr = exp2f(m[r] - mn);
-      const float pw = exp2f(s - mn);  // 0 for a token beyond the end
+      const float corr = __builtin_amdgcn_exp2f(m[r] - mn);
+      const float pw = __builtin_amdgcn_exp2f(s - mn);  // 0 for a token beyond the end
       m[r] = mn;
       l[r] = fmaf(l[r], corr, pw);
 #pragma unroll
@@ -183,16 +266,19 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_partial_kernel(const Attn
   const int64_t span = nend - nbeg;
   const int trips = span > 0 ? (int)((span + 2 * ATT_WAVES - 1) / (2 * ATT_WAVES)) : 0;  // uniform
   Pre pa, pb;
-  int64_t n = nbeg + hw;
-  if (trips > 0) fetch(n, pa);
-  for (int t = 0; t < trips; t += 2) {
-    fetch(n + 2 * ATT_WAVES, pb);
-    work(n, pa);
-    n += 2 * ATT_WAVES;
-    if (t + 1 >= trips) break;
-    fetch(n + 2 * ATT_WAVES, pa);
-    work(n, pb);
-    n += 2 * ATT_WAVES;
+  Rows R;
+  uint32_t t = (uint32_t)hw;  // token of this half-wavefront, relative to nbeg
+  if (trips > 0) fetch(t, pa);
+  for (int it = 0; it < trips; it += 2) {
+    issue(pa, R);
+    fetch(t + 2 * ATT_WAVES, pb);
+    work(t, pa, R);
+    t += 2 * ATT_WAVES;
+    if (it + 1 >= trips) break;
+    issue(pb, R);
+    fetch(t + 2 * ATT_WAVES, pa);
+    work(t, pb, R);
+    t += 2 * ATT_WAVES;
   }
 
   // merge the eight half-wavefronts of the workgroup
@@ -214,7 +300,7 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_partial_kernel(const Attn
     float tot = 0.f, L = 0.f;
 #pragma unroll
     for (int w = 0; w < 2 * ATT_WAVES; ++w) {
-      const float f = exp2f(sm_m[w][r] - M);
+      const float f = __builtin_amdgcn_exp2f(sm_m[w][r] - M);
       tot = fmaf(sm_acc[w][r][c], f, tot);
       L = fmaf(sm_l[w][r], f, L);
     }
@@ -238,7 +324,7 @@ __global__ __launch_bounds__(ATT_HD) void attn_merge_kernel(const float *__restr
   for (int s = 0; s < S; ++s) M = fmaxf(M, base[s * stride]);
   float tot = 0.f, L = 0.f;
   for (int s = 0; s < S; ++s) {
-    const float f = exp2f(base[s * stride] - M);
+    const float f = __builtin_amdgcn_exp2f(base[s * stride] - M);
     tot = fmaf(base[s * stride + 2 + c], f, tot);
     L = fmaf(base[s * stride + 1], f, L);
   }
@@ -298,17 +384,30 @@ hipError_t rvq_launch_attn_decode(const rvq_ctx *kctx, const rvq_ctx *vctx, cons
   a.scale_log2e = scale * 1.4426950408889634f;
   const int rep = Hq / Hkv;
   const dim3 grid((unsigned)(a.S * Hkv)), block(64 * ATT_WAVES);
-  const bool d8 = a.depth == 8;
-#define RVQ_ATT_LAUNCH(R)                                                              \
-  if (d8) hipLaunchKernelGGL((attn_partial_kernel<R, true>), grid, block, 0, s, a);     \
-  else hipLaunchKernelGGL((attn_partial_kernel<R, false>), grid, block, 0, s, a)
+  const bool fast = a.depth == 8 && k_depth_used == 8 && v_depth_used == 8 && dCos && dKStd && dVStd &&
+                    a.kstd_dtype == RVQ_F16 && a.vstd_dtype == RVQ_F16;
+#define RVQ_ATT_LAUNCH4(R, F)                                                                        \
+  if (a.k_strided) {                                                                                 \
+    if (a.v_strided) hipLaunchKernelGGL((attn_partial_kernel<R, F, true, true>), grid, block, 0, s, a);   \
+    else hipLaunchKernelGGL((attn_partial_kernel<R, F, true, false>), grid, block, 0, s, a);         \
+  } else {                                                                                           \
+    if (a.v_strided) hipLaunchKernelGGL((attn_partial_kernel<R, F, false, true>), grid, block, 0, s, a);  \
+    else hipLaunchKernelGGL((attn_partial_kernel<R, F, false, false>), grid, block, 0, s, a);        \
+  }
+#define RVQ_ATT_LAUNCH(R)          \
+  if (fast) {                      \
+    RVQ_ATT_LAUNCH4(R, true)       \
+  } else {                         \
+    RVQ_ATT_LAUNCH4(R, false)      \
+  }
   switch (rep) {
-    case 1: RVQ_ATT_LAUNCH(1); break;
-    case 2: RVQ_ATT_LAUNCH(2); break;
-    case 4: RVQ_ATT_LAUNCH(4); break;
-    default: RVQ_ATT_LAUNCH(8); break;
+    case 1: RVQ_ATT_LAUNCH(1) break;
+    case 2: RVQ_ATT_LAUNCH(2) break;
+    case 4: RVQ_ATT_LAUNCH(4) break;
+    default: RVQ_ATT_LAUNCH(8) break;
   }
 #undef RVQ_ATT_LAUNCH
+#undef RVQ_ATT_LAUNCH4
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(attn_merge_kernel, dim3((unsigned)Hq), dim3(ATT_HD), 0, s, dWork, a.S, rep, dOut);
