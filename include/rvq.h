@@ -189,7 +189,7 @@ int rvq_decode_rope(rvq_ctx *ctx, const int16_t *dCodes, const void *dStd, int64
  *               grouping and K each, codebooks set, same device
  *   dQ          device, float [n_q_heads][128]: the query heads, already rotated to their position
  *   n_q_heads / n_kv_heads   1, 2, 4 or 8 query heads per kv head
- *   dKCodes, dVCodes  device, int16 [N * n_kv_heads][4][depth]; codes outside [0, K) are clamped
+ *   dKCodes, dVCodes  device, int16 [N * n_kv_heads][4][depth]; a code outside [0, K) is read as K - 1
  *   dKStd, dVStd      device, [N * n_kv_heads] of the context's std_dtype; NULL (= 1) only for a
  *                     context with cfg.scale == 0
  *   N           tokens in the cache, >= 1

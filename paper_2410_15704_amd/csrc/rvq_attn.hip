@@ -45,12 +45,6 @@ struct AttnArgs {
   float scale_log2e;        // softmax scale times log2(e): scores are kept in base 2
 };
 
-__device__ __forceinline__ float att_load_std(const void *p, int dt, int64_t row) {
-  if (!p) return 1.0f;
-  return dt == RVQ_F32 ? ((const float *)p)[row] : rvq_f16_bits_to_f32(((const uint16_t *)p)[row]);
-}
-__device__ __forceinline__ int att_clamp(int k, int K) { return k < 0 ? 0 : (k >= K ? K - 1 : k); }
-
 // The codes of one (row, group): up to eight int16, kept as four 32-bit words (two codes each).
 struct AttCodes { i32x4 w; };
 template <bool D8>
@@ -67,24 +61,27 @@ __device__ __forceinline__ AttCodes att_load_codes(const int16_t *codes, uint32_
   }
   return r;
 }
-__device__ __forceinline__ int att_code(const AttCodes &cd, int i) {
-  const int w = i < 2 ? cd.w.x : (i < 4 ? cd.w.y : (i < 6 ? cd.w.z : cd.w.w));
-  return (i & 1) ? (w >> 16) : (int)(int16_t)(w & 0xffff);  // sign-extended, as stored
-}
-
-// This lane's quarter of the codeword rows that the eight codes select: the loads only.  Cq is
-// the codebook's byte address plus the lane's 16-byte offset; the row offset stays 32 bits
-// (depth * K * 128 bytes < 2^31, checked by the launcher), so a load is base + offset.
+// This lane's quarter of the codeword rows that the eight codes select: the loads only.  Cb is
+// the codebook (the same for all lanes), lane_off the lane's 16-byte offset inside a row; a
+// load is (stage base, scalar) + (code * 128 + lane_off, 32 bits).  A code is read as an unsigned
+// 16-bit number and limited to K - 1, so any stored value stays inside the codebook.
 // FULL: all eight stages are used (no condition anywhere near the loads); otherwise stages beyond
 // `used` fetch row 0 of stage 0 and later enter the sum with weight 0.
 template <bool FULL>
-__device__ __forceinline__ void att_issue(const char *Cq, int K, const AttCodes &cd, int used, f32x4 (&rows)[8]) {
+__device__ __forceinline__ void att_issue(const char *Cb, uint32_t lane_off, int K, const AttCodes &cd,
+                                          int used, f32x4 (&rows)[8]) {
+  const uint32_t w4[4] = {(uint32_t)cd.w.x, (uint32_t)cd.w.y, (uint32_t)cd.w.z, (uint32_t)cd.w.w};
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const int code = att_clamp(att_code(cd, i), K);  // (max + min: the compiler makes one v_med3 of them)
-    uint32_t off = ((uint32_t)(i * K) + (uint32_t)code) * 128u;
-    if (!FULL) off = i < used ? off : 0u;
-    rows[i] = *reinterpret_cast<const f32x4 *>(Cq + off);
+    const uint32_t raw = (i & 1) ? (w4[i >> 1] >> 16) : (w4[i >> 1] & 0xffffu);
+    const uint32_t code = min(raw, (uint32_t)(K - 1));
+    const char *stage = Cb + (size_t)i * (size_t)K * 128u;  // scalar
+    uint32_t off = code * 128u + lane_off;
+    if (!FULL) {
+      off = i < used ? off : lane_off;
+      stage = i < used ? stage : Cb;
+    }
+    rows[i] = *reinterpret_cast<const f32x4 *>(stage + off);
   }
 }
 // their sum in stage order
@@ -170,8 +167,9 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_partial_kernel(const Attn
   const char *vsb = a.vstd ? (const char *)a.vstd + row0 * (a.vstd_dtype == RVQ_F32 ? 4 : 2) : nullptr;
   const float *cosb = a.cos ? a.cos + nbeg * (ATT_HD / 2) : nullptr;
   const float *sinb = a.cos ? a.sin + nbeg * (ATT_HD / 2) : nullptr;
-  const char *Ckq = reinterpret_cast<const char *>(a.Ck + 4 * q8);
-  const char *Cvq = reinterpret_cast<const char *>(a.Cv + 4 * q8);
+  const char *Ckb = reinterpret_cast<const char *>(a.Ck);
+  const char *Cvb = reinterpret_cast<const char *>(a.Cv);
+  const uint32_t lane_off = 16u * (uint32_t)q8;
   const uint32_t last = (uint32_t)(nend - nbeg) - 1u;         // last token of the split, relative
   const uint32_t row_elems = (uint32_t)(a.Hkv * ATT_G * a.depth);  // code elements between tokens
 
@@ -224,8 +222,8 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_partial_kernel(const Attn
   // the gathered rows: waiting for the gathers does not wait for HBM.
   struct Rows { f32x4 k[8], v[8]; };
   auto issue = [&](const Pre &p, Rows &R) {
-    att_issue<FAST>(Ckq, a.Kk, p.kc, a.k_depth_used, R.k);
-    att_issue<FAST>(Cvq, a.Kv, p.vc, a.v_depth_used, R.v);
+    att_issue<FAST>(Ckb, lane_off, a.Kk, p.kc, a.k_depth_used, R.k);
+    att_issue<FAST>(Cvb, lane_off, a.Kv, p.vc, a.v_depth_used, R.v);
   };
   auto work = [&](uint32_t t, const Pre &p, const Rows &R) {
     const bool valid = t <= last;
@@ -314,20 +312,48 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_partial_kernel(const Attn
 }
 
 // one workgroup per query head: merge the partial results of the splits and normalise
+constexpr int ATT_MAX_SPLITS = 2048;
 __global__ __launch_bounds__(ATT_HD) void attn_merge_kernel(const float *__restrict__ part, int S, int REP,
                                                             float *__restrict__ out) {
+  __shared__ float f[ATT_MAX_SPLITS];  // maxima of the splits, then their weights 2^(m_s - M)
+  __shared__ float red[ATT_HD];
   const int hq = blockIdx.x, c = threadIdx.x;
   const int h = hq / REP, r = hq % REP;
   const float *base = part + ((int64_t)h * S * REP + r) * ATT_PART;
   const int64_t stride = (int64_t)REP * ATT_PART;
+  // the largest maximum
   float M = ATT_NEG;
-  for (int s = 0; s < S; ++s) M = fmaxf(M, base[s * stride]);
-  float tot = 0.f, L = 0.f;
-  for (int s = 0; s < S; ++s) {
-    const float f = __builtin_amdgcn_exp2f(base[s * stride] - M);
-    tot = fmaf(base[s * stride + 2 + c], f, tot);
-    L = fmaf(base[s * stride + 1], f, L);
+  for (int s = c; s < S; s += ATT_HD) {
+    const float ms = base[s * stride];
+    f[s] = ms;
+    M = fmaxf(M, ms);
   }
+  red[c] = M;
+  __syncthreads();
+  for (int o = ATT_HD / 2; o > 0; o >>= 1) {
+    if (c < o) red[c] = fmaxf(red[c], red[c + o]);
+    __syncthreads();
+  }
+  M = red[0];
+  __syncthreads();
+  // weights of the splits and the total sum
+  float L = 0.f;
+  for (int s = c; s < S; s += ATT_HD) {
+    const float w = __builtin_amdgcn_exp2f(f[s] - M);
+    f[s] = w;
+    L = fmaf(base[s * stride + 1], w, L);
+  }
+  red[c] = L;
+  __syncthreads();
+  for (int o = ATT_HD / 2; o > 0; o >>= 1) {
+    if (c < o) red[c] += red[c + o];
+    __syncthreads();
+  }
+  L = red[0];
+  // channel c: the loads of different splits do not depend on each other
+  float tot = 0.f;
+#pragma unroll 8
+  for (int s = 0; s < S; ++s) tot = fmaf(base[s * stride + 2 + c], f[s], tot);
   out[(int64_t)hq * ATT_HD + c] = tot / L;
 }
 
