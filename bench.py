@@ -322,6 +322,70 @@ def run_workload5(args):
                 mse_per_depth=mse, mean_square_of_input=float((dX[:16384].float() ** 2).mean()))
 
 
+def run_attn_decode(args):
+    """Attention of one query position over a cache of codes (`rvq_attn_decode`): 131072 tokens x 8
+    kv heads of 128 channels, 4 query heads per kv head, keys strided / values contiguous, depth
+    8, K = 2048, seeded uniform codes.  Beside it the unfused route through the library's own
+    decode calls (fp16 keys with the rotary embedding and fp16 values written out) - the attention
+    that would then read them is not timed."""
+    import torch
+
+    from paper_2410_15704_amd import binding as b
+    from paper_2410_15704_amd import synth
+
+    N, Hkv, rep, depth, K, hd = 131072, 8, 4, 8, 2048, 128
+    Hq, rows = Hkv * rep, N * Hkv
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.BASE_SEED + 6)
+    Ck = torch.randn((depth, K, 32), device="cuda", generator=gen)
+    Cv = torch.randn((depth, K, 32), device="cuda", generator=gen)
+    kc = torch.randint(0, K, (rows, 4, depth), device="cuda", generator=gen, dtype=torch.int16)
+    vc = torch.randint(0, K, (rows, 4, depth), device="cuda", generator=gen, dtype=torch.int16)
+    ks = (torch.rand(rows, device="cuda", generator=gen) + 0.5).half()
+    vs = (torch.rand(rows, device="cuda", generator=gen) + 0.5).half()
+    qv = torch.randn((Hq, hd), device="cuda", generator=gen)
+    ang = torch.rand((N, hd // 2), device="cuda", generator=gen) * 6.2831853
+    cos, sin = torch.cos(ang), torch.sin(ang)
+    kq = b.Quantizer(d=hd, dhat=32, depth=depth, K=K, grouping=b.STRIDED)
+    vq = b.Quantizer(d=hd, dhat=32, depth=depth, K=K, grouping=b.CONTIGUOUS)
+    kq.set_codebooks(Ck)
+    vq.set_codebooks(Cv)
+    wsb = b.rvq_attn_workspace_bytes(N, Hq, Hkv)
+    ws = torch.empty(wsb // 4, device="cuda")
+    out = torch.empty((Hq, hd), device="cuda")
+    a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, reps=20):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            fn()
+        z.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(z) / reps
+
+    scale = 1.0 / hd ** 0.5
+    fused = timed(lambda: b.rvq_attn_decode(kq.ctx, vq.ctx, qv, Hq, Hkv, kc, ks, vc, vs, N, cos, sin, scale,
+                                            out, ws, wsb))
+    kx = torch.empty((rows, hd), dtype=torch.float16, device="cuda")
+    vx = torch.empty((rows, hd), dtype=torch.float16, device="cuda")
+    cosr = cos.repeat_interleave(Hkv, 0).contiguous()
+    sinr = sin.repeat_interleave(Hkv, 0).contiguous()
+    unfused = timed(lambda: (b.rvq_decode_rope(kq.ctx, kc, ks, rows, depth, cosr, sinr, hd, kx, hd),
+                             b.rvq_decode(vq.ctx, vc, vs, rows, depth, vx, hd)))
+    kq.close()
+    vq.close()
+    hbm = rows * (2 * (4 * depth * 2) + 2 * 2) + N * (hd // 2) * 4 * 2  # codes + std, rotary tables
+    gather = rows * 2 * 4 * depth * 128                                 # codeword rows from L2
+    return dict(workload="one query position over 131072 tokens x 8 kv heads (32 query heads), codes in the cache",
+                fused_ms=fused, token_heads_per_s=rows / (fused * 1e-3),
+                hbm_GBs=hbm / (fused * 1e-3) / 1e9, l2_gather_GBs=gather / (fused * 1e-3) / 1e9,
+                fp16_kv_equivalent_GBs=rows * 2 * hd * 2 / (fused * 1e-3) / 1e9,
+                decode_k_and_v_to_fp16_ms=unfused)
+
+
 def run_workload4(args):
     """Workload 4 (codebook learning): 1,048,576 mixture vectors, depth 8, K = 2048, stage by stage,
     10 (assign, update) rounds per stage + the assignment that forms the residuals; time per pass
@@ -488,6 +552,7 @@ def main():
     if not args.no_extra_workloads:
         line["workload5"] = run_workload5(args)
         line["workload4"] = run_workload4(args)
+        line["attn_decode"] = run_attn_decode(args)
     line["cpu_baseline"] = None if args.no_cpu else run_cpu_baseline(args)
     print(json.dumps(line))
 
