@@ -441,12 +441,11 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
   // A stage has two phases.  Phase L works against the stage's operands in LDS (sweep on the
   // matrix cores, fp16 re-scores); phase T touches only registers, the token's candidate list
   // and the fp32 codebook in L2 (exact scores, code, residual update, operands of the next
-  // stage).  The eight wavefronts form two teams that take the phases in opposite order: while
-  // team 0 runs L of stage i, team 1 runs T of stage i - 1, then they swap, so the matrix-core
-  // work of one team shares the SIMDs with the latency-bound work of the other, and the
-  // workgroup meets only once per stage, to swap the operands in LDS.
-  // A codebook larger than LDS is swept in chunks with workgroup barriers inside phase L:
-  // there every wavefront is in team 0.
+  // stage).  Every wavefront runs L(0) T(0) L(1) T(1) ... at its own pace; the workgroup meets
+  // only to swap the operands in LDS between stages, and not at a barrier (see the counters
+  // below).  For that swap the eight wavefronts form two teams: team 0 (wavefronts 0..3) copies,
+  // team 1 only waits for the copy.  A codebook larger than LDS is swept in chunks with workgroup
+  // barriers inside phase L: there every wavefront is in team 0.
   const int team = (single_chunk && wave >= SCR_WAVES / 2) ? 1 : 0;
 
   // ---- per-stage state of this lane's two tokens
