@@ -409,3 +409,47 @@ def test_bounded_wait_reports_instead_of_hanging(gpu_device):
     assert b.rvq_check_kernels(q.ctx, check=False) == 0
     assert b.lib.rvq_debug_set_wait_polls(q.ctx, -1) == b.RVQ_EINVAL
     q.close()
+
+
+# ------------------------------------------------------------------------- non-finite inputs
+@pytest.mark.parametrize("case", [
+    # d, dhat, K, depth, grouping: the matrix-core path (dhat 32) and the plain scan (dhat 16)
+    (256, 32, 300, 4, oracle.STRIDED),
+    (256, 32, 64, 3, oracle.CONTIGUOUS),
+    (64, 16, 50, 3, oracle.CONTIGUOUS),
+])
+def test_rows_with_nan_or_infinity_leave_the_other_rows_alone(gpu_device, case):
+    """The boundary asks for finite inputs and promises, for a row that has a NaN or an infinity,
+    codes inside [0, K), no access out of bounds and no effect on any other row.  Rows 3, 7, 100,
+    200 and the last one are poisoned; every other row must get exactly the codes and the std
+    of a run without the poison."""
+    torch, b = _torch(), _b()
+    d, dhat, K, depth, grouping = case
+    N = 1300  # more than one chunk of 1024 group vectors per workgroup and a ragged tail
+    rng = np.random.Generator(np.random.PCG64(d + K))
+    X = rng.standard_normal((N, d)).astype(np.float32)
+    C = (rng.standard_normal((depth, K, dhat)) * (0.7 ** np.arange(depth))[:, None, None]).astype(np.float32)
+    bad = X.copy()
+    bad[3, 5] = np.nan
+    bad[7, 0] = np.inf
+    bad[100, d - 1] = -np.inf
+    bad[200, :] = np.nan
+    bad[N - 1, 17] = np.inf
+    bad[N - 1, 18] = np.nan
+    poisoned = np.array([3, 7, 100, 200, N - 1])
+    clean_rows = np.setdiff1d(np.arange(N), poisoned)
+    q = b.Quantizer(d=d, dhat=dhat, depth=depth, K=K, grouping=grouping, in_dtype=b.F32, std_dtype=b.F32)
+    q.set_codebooks(torch.from_numpy(C).cuda())
+    c0, s0, _ = q.encode(torch.from_numpy(X).cuda())
+    c1, s1, _ = q.encode(torch.from_numpy(bad).cuda())
+    torch.cuda.synchronize()
+    assert b.rvq_check_kernels(q.ctx) == 0
+    # and decoding whatever codes came out stays in bounds too
+    out = q.decode(c1, s1)
+    torch.cuda.synchronize()
+    h0, h1 = c0.cpu().numpy(), c1.cpu().numpy()
+    assert h1.min() >= 0 and h1.max() < K
+    assert np.array_equal(h1[clean_rows], h0[clean_rows])
+    assert np.array_equal(s1.cpu().numpy()[clean_rows], s0.cpu().numpy()[clean_rows])
+    assert np.isfinite(out.float().cpu().numpy()[clean_rows]).all()
+    q.close()
