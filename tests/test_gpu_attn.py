@@ -92,6 +92,10 @@ def _check(c, scale=1.0 / np.sqrt(HD), tol=1e-4):  # measured: <= 2e-6
     (2500, 4, 2, 4, 1024, 2048, oracle.STRIDED, oracle.STRIDED, "fp16", 1, False),  # no rotation
     (777, 2, 4, 1, 17, 5, oracle.STRIDED, oracle.CONTIGUOUS, "fp16", 0, True),      # one stage, rows not scaled
     (40000, 8, 4, 8, 2048, 2048, oracle.STRIDED, oracle.CONTIGUOUS, "fp16", 1, True),  # several splits per head
+    # the compile-time fast case (depth 8, tables, fp16 std) in its other instantiations
+    (513, 2, 8, 8, 128, 128, oracle.CONTIGUOUS, oracle.STRIDED, "fp16", 1, True),
+    (2000, 3, 2, 8, 500, 700, oracle.CONTIGUOUS, oracle.CONTIGUOUS, "fp16", 1, True),
+    (900, 2, 1, 8, 2048, 2048, oracle.STRIDED, oracle.STRIDED, "fp16", 1, True),
 ])
 def test_attn_decode_against_oracle(gpu_device, case):
     N, Hkv, rep, depth, Kk, Kv, kg, vg, sdt, sc, rope = case
