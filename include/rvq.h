@@ -192,7 +192,7 @@ int rvq_decode_rope(rvq_ctx *ctx, const int16_t *dCodes, const void *dStd, int64
  *   dKCodes, dVCodes  device, int16 [N * n_kv_heads][4][depth]; a code outside [0, K) is read as K - 1
  *   dKStd, dVStd      device, [N * n_kv_heads] of the context's std_dtype; NULL (= 1) only for a
  *                     context with cfg.scale == 0
- *   N           tokens in the cache, >= 1
+ *   N           tokens in the cache, >= 1 (and N * n_kv_heads below about 2^33: RVQ_EINVAL beyond)
  *   dCos, dSin  device, float [N][64]: the angles of every token's position; both NULL = no rotation
  *   scale       softmax scale (1 / sqrt(128) in the usual formulation)
  *   dOut        device, float [n_q_heads][128]

@@ -439,6 +439,12 @@ int rvq_attn_decode(rvq_ctx *kctx, rvq_ctx *vctx, const float *dQ, int32_t n_q_h
     return RVQ_EINVAL;
   if ((kc.scale && !dKStd) || (vc.scale && !dVStd)) return RVQ_EINVAL;
   if (workspace_bytes < rvq_attn_workspace_bytes(N, n_q_heads, n_kv_heads)) return RVQ_EWORKSPACE;
+  {
+    // inside a split of the cache the kernel addresses codes with 32-bit element offsets
+    const int64_t splits = (int64_t)(rvq_attn_workspace_floats(N, n_q_heads, n_kv_heads) / ((size_t)n_q_heads * 130));
+    const int64_t tps = ((N + splits - 1) / splits + 7) / 8 * 8;
+    if (tps * n_kv_heads * 4 * kc.depth >= (int64_t)1 << 31) return RVQ_EINVAL;
+  }
   if (!kctx->have_codebooks || !vctx->have_codebooks) return RVQ_ENOCODEBOOK;
   RVQ_HIP(kctx, rvq_launch_attn_decode(kctx, vctx, dQ, n_q_heads, n_kv_heads, dKCodes, dKStd, dVCodes,
                                        dVStd, N, dCos, dSin, scale, kc.depth, vc.depth, dOut,
