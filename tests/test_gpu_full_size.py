@@ -453,3 +453,17 @@ def test_rows_with_nan_or_infinity_leave_the_other_rows_alone(gpu_device, case):
     assert np.array_equal(s1.cpu().numpy()[clean_rows], s0.cpu().numpy()[clean_rows])
     assert np.isfinite(out.float().cpu().numpy()[clean_rows]).all()
     q.close()
+
+
+# ------------------------------------------------------------------------- the ceiling probes
+def test_gather_rate_probes_return_plausible_rates(gpu_device):
+    """rvq_probe_gather_rates measures what this GPU delivers for the decode kernels' gathers; bench.py
+    prices the decode ceilings with it.  The three rates must be positive and ordered as the
+    hardware orders them: consecutive LDS reads faster than random ones, and all of them above the
+    HBM rate that the decode paths are compared with."""
+    b = _b()
+    r = b.rvq_probe_gather_rates()
+    assert set(r) == {"lds_random_GBs", "lds_consecutive_GBs", "l2_rows_random_GBs"}
+    assert r["lds_consecutive_GBs"] > r["lds_random_GBs"] > 8000.0
+    assert r["l2_rows_random_GBs"] > 8000.0
+    assert r["lds_consecutive_GBs"] < 400000.0  # (256 CUs x 128 B/clk x 2.4 GHz = 78,600)
