@@ -189,7 +189,10 @@ int rvq_decode_rope(rvq_ctx *ctx, const int16_t *dCodes, const void *dStd, int64
  *               grouping and K each, codebooks set, same device
  *   dQ          device, float [n_q_heads][128]: the query heads, already rotated to their position
  *   n_q_heads / n_kv_heads   1, 2, 4 or 8 query heads per kv head
- *   dKCodes, dVCodes  device, int16 [N * n_kv_heads][4][depth]; a code outside [0, K) is read as K - 1
+ *   dKCodes, dVCodes  device; packed == 0: int16 [N * n_kv_heads][4][depth]; packed == 1: the records
+ *                     of rvq_pack_codes, uint8 [N * n_kv_heads][4][record bytes], supported for
+ *                     depth 8 and 11- or 12-bit codes (1024 < K <= 4096), the same width in both
+ *                     caches (RVQ_EINVAL otherwise).  A code outside [0, K) is read as K - 1
  *   dKStd, dVStd      device, [N * n_kv_heads] of the context's std_dtype; NULL (= 1) only for a
  *                     context with cfg.scale == 0
  *   N           tokens in the cache, >= 1 (and N * n_kv_heads below about 2^33: RVQ_EINVAL beyond)
@@ -204,10 +207,10 @@ int rvq_decode_rope(rvq_ctx *ctx, const int16_t *dCodes, const void *dStd, int64
  */
 int64_t rvq_attn_workspace_bytes(int64_t N, int32_t n_q_heads, int32_t n_kv_heads);
 int rvq_attn_decode(rvq_ctx *kctx, rvq_ctx *vctx, const float *dQ, int32_t n_q_heads,
-                    int32_t n_kv_heads, const int16_t *dKCodes, const void *dKStd,
-                    const int16_t *dVCodes, const void *dVStd, int64_t N, const float *dCos,
-                    const float *dSin, float scale, float *dOut, void *dWorkspace,
-                    int64_t workspace_bytes, void *stream);
+                    int32_t n_kv_heads, const void *dKCodes, const void *dKStd,
+                    const void *dVCodes, const void *dVStd, int32_t packed, int64_t N,
+                    const float *dCos, const float *dSin, float scale, float *dOut,
+                    void *dWorkspace, int64_t workspace_bytes, void *stream);
 
 /*
  * Packed code storage (Section 3.2: the compression rate of 5.5x counts log2(K) bits per code and a

@@ -74,7 +74,7 @@ def _load():
     lib.rvq_version.restype = ctypes.c_int
     lib.rvq_attn_workspace_bytes.argtypes = [i64, i32, i32]
     lib.rvq_attn_workspace_bytes.restype = i64
-    lib.rvq_attn_decode.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, i64, vp, vp, f32, vp, vp, i64, vp]
+    lib.rvq_attn_decode.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, i32, i64, vp, vp, f32, vp, vp, i64, vp]
     for name in EXPORTS:
         getattr(lib, name)
         if name not in ("rvq_strerror", "rvq_version", "rvq_packed_record_bytes",
@@ -225,10 +225,10 @@ def rvq_attn_workspace_bytes(N, n_q_heads, n_kv_heads):
 
 
 def rvq_attn_decode(kctx, vctx, dQ, n_q_heads, n_kv_heads, dKCodes, dKStd, dVCodes, dVStd, N, dCos,
-                    dSin, scale, dOut, dWorkspace, workspace_bytes, stream=None):
+                    dSin, scale, dOut, dWorkspace, workspace_bytes, stream=None, packed=0):
     return _chk(lib.rvq_attn_decode(kctx, vctx, _ptr(dQ), n_q_heads, n_kv_heads, _ptr(dKCodes),
-                                    _ptr(dKStd), _ptr(dVCodes), _ptr(dVStd), N, _ptr(dCos), _ptr(dSin),
-                                    scale, _ptr(dOut), _ptr(dWorkspace), workspace_bytes,
+                                    _ptr(dKStd), _ptr(dVCodes), _ptr(dVStd), packed, N, _ptr(dCos),
+                                    _ptr(dSin), scale, _ptr(dOut), _ptr(dWorkspace), workspace_bytes,
                                     _stream(stream)), kctx)
 
 

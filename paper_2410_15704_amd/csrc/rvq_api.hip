@@ -418,16 +418,24 @@ int64_t rvq_attn_workspace_bytes(int64_t N, int32_t n_q_heads, int32_t n_kv_head
 }
 
 int rvq_attn_decode(rvq_ctx *kctx, rvq_ctx *vctx, const float *dQ, int32_t n_q_heads,
-                    int32_t n_kv_heads, const int16_t *dKCodes, const void *dKStd,
-                    const int16_t *dVCodes, const void *dVStd, int64_t N, const float *dCos,
-                    const float *dSin, float scale, float *dOut, void *dWorkspace,
-                    int64_t workspace_bytes, void *stream) {
+                    int32_t n_kv_heads, const void *dKCodes, const void *dKStd,
+                    const void *dVCodes, const void *dVStd, int32_t packed, int64_t N,
+                    const float *dCos, const float *dSin, float scale, float *dOut,
+                    void *dWorkspace, int64_t workspace_bytes, void *stream) {
   if (!kctx || !vctx) return RVQ_EINVAL;
   const rvq_config &kc = kctx->cfg, &vc = vctx->cfg;
   // heads of 128 channels in four groups of 32; one to eight stages; both caches on one device
   if (kc.d != 128 || vc.d != 128 || kc.dhat != 32 || vc.dhat != 32) return RVQ_EINVAL;
   if (kc.depth != vc.depth || kc.depth < 1 || kc.depth > 8) return RVQ_EINVAL;
   if (kctx->device != vctx->device) return RVQ_EINVAL;
+  int packed_bytes = 0;
+  if (packed != 0 && packed != 1) return RVQ_EINVAL;
+  if (packed) {
+    // records that the kernel reads directly: depth 8 with 11- or 12-bit codes, the same in both caches
+    const int bk = rvq_code_bits(kc.K), bv = rvq_code_bits(vc.K);
+    if (kc.depth != 8 || bk != bv || (bk != 11 && bk != 12)) return RVQ_EINVAL;
+    packed_bytes = bk;
+  }
   if (n_kv_heads < 1 || n_q_heads < n_kv_heads || n_q_heads % n_kv_heads != 0) return RVQ_EINVAL;
   const int rep = n_q_heads / n_kv_heads;
   if (rep != 1 && rep != 2 && rep != 4 && rep != 8) return RVQ_EINVAL;
@@ -443,11 +451,11 @@ int rvq_attn_decode(rvq_ctx *kctx, rvq_ctx *vctx, const float *dQ, int32_t n_q_h
     // inside a split of the cache the kernel addresses codes with 32-bit element offsets
     const int64_t splits = (int64_t)(rvq_attn_workspace_floats(N, n_q_heads, n_kv_heads) / ((size_t)n_q_heads * 130));
     const int64_t tps = ((N + splits - 1) / splits + 7) / 8 * 8;
-    if (tps * n_kv_heads * 4 * kc.depth >= (int64_t)1 << 31) return RVQ_EINVAL;
+    if (tps * n_kv_heads * 4 * (packed_bytes ? packed_bytes : 2 * kc.depth) >= (int64_t)1 << 32) return RVQ_EINVAL;
   }
   if (!kctx->have_codebooks || !vctx->have_codebooks) return RVQ_ENOCODEBOOK;
   RVQ_HIP(kctx, rvq_launch_attn_decode(kctx, vctx, dQ, n_q_heads, n_kv_heads, dKCodes, dKStd, dVCodes,
-                                       dVStd, N, dCos, dSin, scale, kc.depth, vc.depth, dOut,
+                                       dVStd, packed_bytes, N, dCos, dSin, scale, kc.depth, vc.depth, dOut,
                                        (float *)dWorkspace, (hipStream_t)stream));
   return RVQ_OK;
 }

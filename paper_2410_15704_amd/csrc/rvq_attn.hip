@@ -28,8 +28,8 @@ constexpr float ATT_NEG = -1.0e30f;    // "no token yet": finite, so that differ
 
 struct AttnArgs {
   const float *q;           // [Hq][128]
-  const int16_t *kcodes;    // [N * Hkv][4][depth]
-  const int16_t *vcodes;
+  const void *kcodes;       // int16 [N * Hkv][4][depth], or packed records [N * Hkv][4][PK bytes]
+  const void *vcodes;
   const void *kstd;         // [N * Hkv] or nullptr
   const void *vstd;
   const float *Ck;          // [depth][Kk][32]
@@ -45,35 +45,63 @@ struct AttnArgs {
   float scale_log2e;        // softmax scale times log2(e): scores are kept in base 2
 };
 
-// The codes of one (row, group): up to eight int16, kept as four 32-bit words (two codes each).
+// The codes of one (row, group) as they come from memory: four 32-bit words.
+//   PK == 0: up to eight int16, two per word.
+//   PK == 11 / 12 (depth 8): a packed record of PK bytes with eight PK-bit codes, code i in bits
+//   [PK i, PK i + PK), little endian (rvq_pack_codes), fetched as its first and its last eight
+//   bytes (two unaligned 8-byte loads that never reach beyond the record).
 struct AttCodes { i32x4 w; };
-template <bool D8>
-__device__ __forceinline__ AttCodes att_load_codes(const int16_t *codes, uint32_t elem, int depth) {
-  AttCodes r;
-  const int16_t *p = codes + elem;  // elem = (row * 4 + g) * depth, below 2^31 (checked by the caller)
-  if constexpr (D8) {
-    r.w = *reinterpret_cast<const i32x4 *>(p);  // depth 8: one aligned 16-byte word
+template <bool D8, int PK>
+__device__ __forceinline__ AttCodes att_load_codes(const void *codes, uint32_t rec, int depth) {
+  AttCodes r;  // rec = row * 4 + g, relative to the split's first record
+  if constexpr (PK != 0) {
+    const unsigned char *p = reinterpret_cast<const unsigned char *>(codes) + rec * (uint32_t)PK;
+    typedef unsigned u32x2u __attribute__((ext_vector_type(2), aligned(1)));
+    const u32x2u lo = *reinterpret_cast<const u32x2u *>(p);
+    const u32x2u hi = *reinterpret_cast<const u32x2u *>(p + PK - 8);
+    r.w = i32x4{(int)lo.x, (int)lo.y, (int)hi.x, (int)hi.y};
   } else {
-    int c[8];
+    const int16_t *p = reinterpret_cast<const int16_t *>(codes) + rec * (uint32_t)depth;
+    if constexpr (D8) {
+      r.w = *reinterpret_cast<const i32x4 *>(p);  // depth 8: one aligned 16-byte word
+    } else {
+      int c[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) c[i] = i < depth ? (int)p[i] & 0xffff : 0;
-    r.w = i32x4{c[0] | (c[1] << 16), c[2] | (c[3] << 16), c[4] | (c[5] << 16), c[6] | (c[7] << 16)};
+      for (int i = 0; i < 8; ++i) c[i] = i < depth ? (int)p[i] & 0xffff : 0;
+      r.w = i32x4{c[0] | (c[1] << 16), c[2] | (c[3] << 16), c[4] | (c[5] << 16), c[6] | (c[7] << 16)};
+    }
   }
   return r;
 }
+// code i of it, as an unsigned number (an int16 below 0 becomes a large one)
+template <int PK>
+__device__ __forceinline__ uint32_t att_code(const AttCodes &cd, int i) {
+  const uint32_t w4[4] = {(uint32_t)cd.w.x, (uint32_t)cd.w.y, (uint32_t)cd.w.z, (uint32_t)cd.w.w};
+  if constexpr (PK == 0) {
+    return (i & 1) ? (w4[i >> 1] >> 16) : (w4[i >> 1] & 0xffffu);
+  } else {
+    // bits 0..63 are the first load, bits 64.. the tail of the second (which starts at byte PK - 8)
+    const uint32_t W[3] = {w4[0], w4[1], w4[3] >> (8 * (12 - PK))};
+    const int word = (PK * i) >> 5, sh = (PK * i) & 31;
+    uint32_t v;
+    if (sh + PK <= 32) v = W[word] >> sh;                          // a code lies in one word
+    else v = __builtin_amdgcn_alignbit(W[word + 1], W[word], sh);  // or straddles two
+    return v & ((1u << PK) - 1u);
+  }
+}
+
 // This lane's quarter of the codeword rows that the eight codes select: the loads only.  Cb is
 // the codebook (the same for all lanes), lane_off the lane's 16-byte offset inside a row; a
 // load is (stage base, scalar) + (code * 128 + lane_off, 32 bits).  A code is read as an unsigned
 // 16-bit number and limited to K - 1, so any stored value stays inside the codebook.
 // FULL: all eight stages are used (no condition anywhere near the loads); otherwise stages beyond
 // `used` fetch row 0 of stage 0 and later enter the sum with weight 0.
-template <bool FULL>
+template <bool FULL, int PK>
 __device__ __forceinline__ void att_issue(const char *Cb, uint32_t lane_off, int K, const AttCodes &cd,
                                           int used, f32x4 (&rows)[8]) {
-  const uint32_t w4[4] = {(uint32_t)cd.w.x, (uint32_t)cd.w.y, (uint32_t)cd.w.z, (uint32_t)cd.w.w};
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const uint32_t raw = (i & 1) ? (w4[i >> 1] >> 16) : (w4[i >> 1] & 0xffffu);
+    const uint32_t raw = att_code<PK>(cd, i);
     const uint32_t code = min(raw, (uint32_t)(K - 1));
     const char *stage = Cb + (size_t)i * (size_t)K * 128u;  // scalar
     uint32_t off = code * 128u + lane_off;
@@ -119,7 +147,8 @@ __device__ __forceinline__ float att_sum16(float s) {
 // all stages used, rotation tables given, both std buffers present in half precision.  Otherwise
 // those are run-time conditions (the loop then has branches around its loads and is slower).
 // KS / VS: strided grouping of the key / value quantizer.
-template <int REP, bool FAST, bool KS, bool VS>
+// PK: 0 = int16 codes; 11 / 12 = packed records of that many bytes (depth 8 only).
+template <int REP, bool FAST, bool KS, bool VS, int PK>
 __global__ __launch_bounds__(64 * ATT_WAVES) void attn_partial_kernel(const AttnArgs a) {
   constexpr bool D8 = FAST;
   __shared__ float sm_m[2 * ATT_WAVES][REP];
@@ -161,8 +190,9 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_partial_kernel(const Attn
   // Everything of this workgroup's tokens is addressed with 32-bit offsets from bases that are
   // the same for the whole workgroup (the launcher checks that a split's rows fit).
   const int64_t row0 = nbeg * a.Hkv + h;                      // row of token nbeg
-  const int16_t *kcb = a.kcodes + row0 * ATT_G * a.depth;
-  const int16_t *vcb = a.vcodes + row0 * ATT_G * a.depth;
+  const int64_t rec_bytes = PK ? PK : 2 * a.depth;           // bytes of one (row, group)
+  const char *kcb = reinterpret_cast<const char *>(a.kcodes) + row0 * ATT_G * rec_bytes;
+  const char *vcb = reinterpret_cast<const char *>(a.vcodes) + row0 * ATT_G * rec_bytes;
   const char *ksb = a.kstd ? (const char *)a.kstd + row0 * (a.kstd_dtype == RVQ_F32 ? 4 : 2) : nullptr;
   const char *vsb = a.vstd ? (const char *)a.vstd + row0 * (a.vstd_dtype == RVQ_F32 ? 4 : 2) : nullptr;
   const float *cosb = a.cos ? a.cos + nbeg * (ATT_HD / 2) : nullptr;
@@ -171,7 +201,7 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_partial_kernel(const Attn
   const char *Cvb = reinterpret_cast<const char *>(a.Cv);
   const uint32_t lane_off = 16u * (uint32_t)q8;
   const uint32_t last = (uint32_t)(nend - nbeg) - 1u;         // last token of the split, relative
-  const uint32_t row_elems = (uint32_t)(a.Hkv * ATT_G * a.depth);  // code elements between tokens
+  const uint32_t row_recs = (uint32_t)(a.Hkv * ATT_G);        // (row, group) records between tokens
 
   // what a token needs from HBM, fetched one trip ahead (the gathers depend on the codes)
   struct Pre {
@@ -180,9 +210,9 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_partial_kernel(const Attn
   };
   auto fetch = [&](uint32_t t, Pre &p) {
     const uint32_t tc = t < last ? t : last;  // clamped: loads carry no branch
-    const uint32_t el = tc * row_elems + (uint32_t)(g * a.depth);
-    p.kc = att_load_codes<D8>(kcb, el, a.depth);
-    p.vc = att_load_codes<D8>(vcb, el, a.depth);
+    const uint32_t rec = tc * row_recs + (uint32_t)g;
+    p.kc = att_load_codes<D8, PK>(kcb, rec, a.depth);
+    p.vc = att_load_codes<D8, PK>(vcb, rec, a.depth);
     const uint32_t ro = tc * (uint32_t)a.Hkv;
     if constexpr (FAST) {
       p.ks = rvq_f16_bits_to_f32(((const uint16_t *)ksb)[ro]);
@@ -222,8 +252,8 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_partial_kernel(const Attn
   // the gathered rows: waiting for the gathers does not wait for HBM.
   struct Rows { f32x4 k[8], v[8]; };
   auto issue = [&](const Pre &p, Rows &R) {
-    att_issue<FAST>(Ckb, lane_off, a.Kk, p.kc, a.k_depth_used, R.k);
-    att_issue<FAST>(Cvb, lane_off, a.Kv, p.vc, a.v_depth_used, R.v);
+    att_issue<FAST, PK>(Ckb, lane_off, a.Kk, p.kc, a.k_depth_used, R.k);
+    att_issue<FAST, PK>(Cvb, lane_off, a.Kv, p.vc, a.v_depth_used, R.v);
   };
   auto work = [&](uint32_t t, const Pre &p, const Rows &R) {
     const bool valid = t <= last;
@@ -375,8 +405,8 @@ size_t rvq_attn_workspace_floats(int64_t N, int Hq, int Hkv) {
 }
 
 hipError_t rvq_launch_attn_decode(const rvq_ctx *kctx, const rvq_ctx *vctx, const float *dQ, int Hq,
-                                  int Hkv, const int16_t *dKCodes, const void *dKStd,
-                                  const int16_t *dVCodes, const void *dVStd, int64_t N,
+                                  int Hkv, const void *dKCodes, const void *dKStd,
+                                  const void *dVCodes, const void *dVStd, int packed_bytes, int64_t N,
                                   const float *dCos, const float *dSin, float scale, int k_depth_used,
                                   int v_depth_used, float *dOut, float *dWork, hipStream_t s) {
   AttnArgs a;
@@ -412,13 +442,21 @@ hipError_t rvq_launch_attn_decode(const rvq_ctx *kctx, const rvq_ctx *vctx, cons
   const dim3 grid((unsigned)(a.S * Hkv)), block(64 * ATT_WAVES);
   const bool fast = a.depth == 8 && k_depth_used == 8 && v_depth_used == 8 && dCos && dKStd && dVStd &&
                     a.kstd_dtype == RVQ_F16 && a.vstd_dtype == RVQ_F16;
-#define RVQ_ATT_LAUNCH4(R, F)                                                                        \
-  if (a.k_strided) {                                                                                 \
-    if (a.v_strided) hipLaunchKernelGGL((attn_partial_kernel<R, F, true, true>), grid, block, 0, s, a);   \
-    else hipLaunchKernelGGL((attn_partial_kernel<R, F, true, false>), grid, block, 0, s, a);         \
-  } else {                                                                                           \
-    if (a.v_strided) hipLaunchKernelGGL((attn_partial_kernel<R, F, false, true>), grid, block, 0, s, a);  \
-    else hipLaunchKernelGGL((attn_partial_kernel<R, F, false, false>), grid, block, 0, s, a);        \
+#define RVQ_ATT_LAUNCH5(R, F, P)                                                                       \
+  if (a.k_strided) {                                                                                   \
+    if (a.v_strided) hipLaunchKernelGGL((attn_partial_kernel<R, F, true, true, P>), grid, block, 0, s, a);  \
+    else hipLaunchKernelGGL((attn_partial_kernel<R, F, true, false, P>), grid, block, 0, s, a);        \
+  } else {                                                                                             \
+    if (a.v_strided) hipLaunchKernelGGL((attn_partial_kernel<R, F, false, true, P>), grid, block, 0, s, a); \
+    else hipLaunchKernelGGL((attn_partial_kernel<R, F, false, false, P>), grid, block, 0, s, a);       \
+  }
+#define RVQ_ATT_LAUNCH4(R, F)                        \
+  if (packed_bytes == 11) {                          \
+    RVQ_ATT_LAUNCH5(R, F, 11)                        \
+  } else if (packed_bytes == 12) {                   \
+    RVQ_ATT_LAUNCH5(R, F, 12)                        \
+  } else {                                           \
+    RVQ_ATT_LAUNCH5(R, F, 0)                         \
   }
 #define RVQ_ATT_LAUNCH(R)          \
   if (fast) {                      \
@@ -434,6 +472,7 @@ hipError_t rvq_launch_attn_decode(const rvq_ctx *kctx, const rvq_ctx *vctx, cons
   }
 #undef RVQ_ATT_LAUNCH
 #undef RVQ_ATT_LAUNCH4
+#undef RVQ_ATT_LAUNCH5
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(attn_merge_kernel, dim3((unsigned)Hq), dim3(ATT_HD), 0, s, dWork, a.S, rep, dOut);

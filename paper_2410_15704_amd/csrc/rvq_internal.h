@@ -126,10 +126,10 @@ hipError_t rvq_launch_ema(rvq_ctx *ctx, int stage, const float *dR, const int16_
                           float *dClusterSize, float *dEmbedSum, hipStream_t s);
 size_t rvq_ema_workspace_bytes(const rvq_ctx *ctx);
 // attention of one query position over a cache of codes (128-channel heads); dWork holds
-// rvq_attn_workspace_floats(N, Hq, Hkv) floats
+// rvq_attn_workspace_floats(N, Hq, Hkv) floats; packed_bytes: 0 (int16 codes), 11 or 12 (records)
 size_t rvq_attn_workspace_floats(int64_t N, int Hq, int Hkv);
 hipError_t rvq_launch_attn_decode(const rvq_ctx *kctx, const rvq_ctx *vctx, const float *dQ, int Hq,
-                                  int Hkv, const int16_t *dKCodes, const void *dKStd,
-                                  const int16_t *dVCodes, const void *dVStd, int64_t N,
+                                  int Hkv, const void *dKCodes, const void *dKStd,
+                                  const void *dVCodes, const void *dVStd, int packed_bytes, int64_t N,
                                   const float *dCos, const float *dSin, float scale, int k_depth_used,
                                   int v_depth_used, float *dOut, float *dWork, hipStream_t s);

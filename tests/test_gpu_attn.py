@@ -162,10 +162,10 @@ def test_attn_decode_error_codes(gpu_device):
     ws = torch.empty(wsb // 4, device="cuda")
     st = torch.cuda.current_stream().cuda_stream
 
-    def call(kctx=None, vctx=None, Hq=8, Hkv=2, N=64, wsbytes=wsb, cosp=cos, sinp=sin):
+    def call(kctx=None, vctx=None, Hq=8, Hkv=2, N=64, wsbytes=wsb, cosp=cos, sinp=sin, packed=0):
         p = lambda t: None if t is None else t.data_ptr()
         return b.lib.rvq_attn_decode(kctx or kq.ctx, vctx or vq.ctx, p(q), Hq, Hkv, p(kc), p(ks), p(vc), p(vs),
-                                     N, p(cosp), p(sinp), 0.1, p(out), p(ws), wsbytes, st)
+                                     packed, N, p(cosp), p(sinp), 0.1, p(out), p(ws), wsbytes, st)
 
     assert call() == b.RVQ_ENOCODEBOOK
     kq.set_codebooks(dev(c["Ck"]))
@@ -177,7 +177,49 @@ def test_attn_decode_error_codes(gpu_device):
     assert call(kctx=wide.ctx) == b.RVQ_EINVAL         # heads must have 128 channels
     assert call(wsbytes=wsb - 4) == b.RVQ_EWORKSPACE
     assert call(sinp=None) == b.RVQ_EINVAL             # one table without the other
+    assert call(packed=1) == b.RVQ_EINVAL              # 6-bit codes (K = 64) are not read in place
+    assert call(packed=2) == b.RVQ_EINVAL
     assert b.rvq_attn_workspace_bytes(0, 8, 2) == 0
     torch.cuda.synchronize()
     for x in (kq, vq, wide):
         x.close()
+
+
+@pytest.mark.parametrize("case", [
+    # N, Hkv, rep, K, key grouping, value grouping, rotation, std type
+    (3001, 2, 4, 2048, oracle.STRIDED, oracle.CONTIGUOUS, True, "fp16"),   # 11-bit codes, the fast case
+    (1000, 3, 2, 4096, oracle.CONTIGUOUS, oracle.STRIDED, True, "fp16"),   # 12-bit codes
+    (700, 1, 8, 1500, oracle.STRIDED, oracle.STRIDED, False, "fp32"),      # 11 bits, run-time conditions
+])
+def test_attn_decode_from_packed_records(gpu_device, case):
+    """The cache as rvq_pack_codes stores it (11 or 12 bits per code): the same output, bit for bit,
+    as from the int16 codes, and the oracle's bar against the fp64 definition."""
+    torch, b = _torch(), _b()
+    N, Hkv, rep, K, kg, vg, rope, sdt = case
+    c = _case(4000 + N, N, Hkv, rep, 8, K, K, kg, vg, sdt, 1, rope)
+    scale = 1.0 / np.sqrt(HD)
+    want = _run_oracle(c, scale)
+    sd = b.F16 if sdt == "fp16" else b.F32
+    kq = b.Quantizer(d=HD, dhat=32, depth=8, K=K, grouping=kg, std_dtype=sd)
+    vq = b.Quantizer(d=HD, dhat=32, depth=8, K=K, grouping=vg, std_dtype=sd)
+    kq.set_codebooks(torch.from_numpy(c["Ck"]).cuda())
+    vq.set_codebooks(torch.from_numpy(c["Cv"]).cuda())
+    dev = lambda a: None if a is None else torch.from_numpy(a).cuda()
+    kc, vc = dev(c["kc"]), dev(c["vc"])
+    kp, vp = kq.pack(kc), vq.pack(vc)
+    assert kp.shape[-1] == (11 if K <= 2048 else 12)
+    Hq = Hkv * rep
+    wsb = b.rvq_attn_workspace_bytes(N, Hq, Hkv)
+    ws = torch.empty(wsb // 4, dtype=torch.float32, device="cuda")
+    outs = []
+    for codes_k, codes_v, packed in ((kc, vc, 0), (kp, vp, 1)):
+        out = torch.full((Hq, HD), float("nan"), dtype=torch.float32, device="cuda")
+        b.rvq_attn_decode(kq.ctx, vq.ctx, dev(c["q"]), Hq, Hkv, codes_k, dev(c["ks"]), codes_v, dev(c["vs"]), N,
+                          dev(c["cos"]), dev(c["sin"]), scale, out, ws, wsb, packed=packed)
+        torch.cuda.synchronize()
+        outs.append(out.cpu().numpy())
+    assert np.array_equal(outs[0], outs[1])
+    err = np.abs(outs[1] - want).max(axis=1) / np.abs(want).max(axis=1)
+    assert err.max() <= 1e-4, err
+    kq.close()
+    vq.close()
