@@ -322,6 +322,52 @@ def run_workload5(args):
                 mse_per_depth=mse, mean_square_of_input=float((dX[:16384].float() ** 2).mean()))
 
 
+def run_append(args):
+    """What a serving loop does per generated token: encode the few rows that were appended
+    (1, 8, 64 rows of workload 2's shape) and decode a short cache (1024 and 8192 rows).  Times
+    per call in microseconds, stream time over 200 calls back to back (two kernels per encode:
+    std and search)."""
+    import numpy as np
+    import torch
+
+    from paper_2410_15704_amd import binding as b
+    from paper_2410_15704_amd import synth, train
+
+    d, dhat, depth, K = (W2[k] for k in ("d", "dhat", "depth", "K"))
+    G = d // dhat
+    Xb, _ = synth.llama_key(8192, d)
+    dX = torch.from_numpy(Xb.view(np.int16)).cuda().view(torch.bfloat16)
+    Zhead = train.scaled_groups(dX[:2048], d=d, dhat=dhat, grouping=b.STRIDED, in_dtype=b.BF16)
+    C = train.sample_init_codebooks(Zhead, depth, K, seed=synth.BASE_SEED + 2)
+    q = b.Quantizer(d=d, dhat=dhat, depth=depth, K=K, grouping=b.STRIDED, in_dtype=b.BF16,
+                    out_dtype=b.F16, std_dtype=b.F16)
+    q.set_codebooks(C)
+    codes = torch.empty((8192, G, depth), dtype=torch.int16, device="cuda")
+    std = torch.empty((8192,), dtype=torch.float16, device="cuda")
+    out = torch.empty((8192, d), dtype=torch.float16, device="cuda")
+    b.rvq_encode(q.ctx, dX, 8192, d, 0, depth, codes, std, None)
+    a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def us(fn, reps=200):
+        for _ in range(10):
+            fn()
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            fn()
+        z.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(z) / reps * 1e3
+
+    res = {}
+    for n in (1, 8, 64):
+        res["encode_%d_rows_us" % n] = us(lambda: b.rvq_encode(q.ctx, dX, n, d, 0, depth, codes, std, None))
+    for n in (1024, 8192):
+        res["decode_%d_rows_us" % n] = us(lambda: b.rvq_decode(q.ctx, codes, std, n, depth, out, d))
+    q.close()
+    return res
+
+
 def run_attn_decode(args):
     """Attention of one query position over a cache of codes (`rvq_attn_decode`): 131072 tokens x 8
     kv heads of 128 channels, 4 query heads per kv head, keys strided / values contiguous, depth
@@ -559,6 +605,7 @@ def main():
         line["workload5"] = run_workload5(args)
         line["workload4"] = run_workload4(args)
         line["attn_decode"] = run_attn_decode(args)
+        line["append"] = run_append(args)
     line["cpu_baseline"] = None if args.no_cpu else run_cpu_baseline(args)
     print(json.dumps(line))
 

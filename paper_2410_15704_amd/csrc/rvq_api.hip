@@ -63,7 +63,10 @@ int encode_enqueue(rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx, int sta
                    hipStream_t s) {
   const rvq_config &c = ctx->cfg;
   if (c.scale) RVQ_HIP(ctx, rvq_launch_row_std(ctx, dX, N, ldx, dStd, std32, s));
-  if (c.dhat == 32 && c.encode_path != RVQ_PATH_EXACT)
+  if (c.dhat == 32 && c.encode_path == RVQ_PATH_AUTO && N * ctx->G <= RVQ_SMALL_MAX_VECTORS)
+    RVQ_HIP(ctx, rvq_launch_encode_small(ctx, dX, N, ldx, stage_begin, stage_end, dCodes,
+                                         dResidual, std32, s));
+  else if (c.dhat == 32 && c.encode_path != RVQ_PATH_EXACT)
     RVQ_HIP(ctx, rvq_launch_encode_screen(ctx, dX, N, ldx, stage_begin, stage_end, dCodes,
                                           dResidual, std32, s));
   else

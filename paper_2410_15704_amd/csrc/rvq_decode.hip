@@ -192,7 +192,8 @@ template <bool OUT_F16, bool STRIDED, int DEPTH8, int PK, bool ROPE, int NP, boo
 __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
     const void *__restrict__ codes_v, const void *__restrict__ std_in, int std_dtype, int64_t N,
     int G, const float *__restrict__ C, int K, int depth, int depth_used, void *__restrict__ out,
-    int64_t ldo, int lds_row /* padded LDS row length in elements (strided only) */, RopeArgs rp) {
+    int64_t ldo, int lds_row /* padded LDS row length in elements (strided only) */, RopeArgs rp,
+    int split /* WIDE: wavefronts that share a fetch, 1, 2, 4 or 8 */) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -463,16 +464,23 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
     };
     i32x4 wide_n[WL];
     float sd_n[NP == 4 ? UPF : 1];
-    int64_t f = wave_global;  // units UPF f .. UPF f + UPF - 1
+    // With few rows there are fewer fetches than wavefronts: `split` wavefronts (neighbours in
+    // one workgroup) then take the same fetch and a share of its units each (whole tokens: at
+    // most 8 wavefronts share, 4 when a token is two units), so that a short cache is decoded by
+    // that many times more wavefronts.  The codes are fetched by each of them.
+    const int sh = __ffs(split) - 1;
+    const int e_lo = (int)(wave_global & (split - 1)) * (UPF >> sh), e_hi = e_lo + (UPF >> sh);
+    const int64_t fstep = wave_count >> sh;  // the launcher makes wave_count a multiple of split
+    int64_t f = wave_global >> sh;  // units UPF f .. UPF f + UPF - 1
     if (UPF * f < units) fetchw(f, wide_n, sd_n);
-    for (; UPF * f < units; f += wave_count) {
+    for (; UPF * f < units; f += fstep) {
       i32x4 wide_c[WL];
       float sd_c[NP == 4 ? UPF : 1];
 #pragma unroll
       for (int l = 0; l < WL; ++l) wide_c[l] = wide_n[l];
 #pragma unroll
       for (int e = 0; e < (NP == 4 ? UPF : 1); ++e) sd_c[e] = sd_n[e];
-      fetchw(f + wave_count, wide_n, sd_n);
+      fetchw(f + fstep, wide_n, sd_n);
       {
         // the previous fetch's records have all been read (program order within the wavefront)
         __builtin_amdgcn_wave_barrier();
@@ -489,6 +497,7 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_rows32_kernel(
 #pragma unroll UNR
         for (int eu = 0; eu < UPL; ++eu) {
           const int e = l * UPL + eu;
+          if (e < e_lo || e >= e_hi) continue;  // another wavefront's share of this fetch
           const int64_t U = UPF * f + e;
           if (U >= units) break;
           Unit cur;
@@ -816,7 +825,7 @@ hipError_t rvq_launch_decode(const rvq_ctx *ctx, const void *dCodes, int packed,
   // (with fewer than 16 groups a token's piece of a channel pair is under 64 bytes: the row kernel
   // writes whole rows instead)
   if (ctx->Csplit && strided && c.dhat == 32 && fast_codes && pk != 12 && (G % 2) == 0 && G >= 16 &&
-      tab_bytes <= RVQ_SPLIT_MAX_LDS && (ldo * osz) % 8 == 0 && N * (int64_t)G >= (1 << 19) &&
+      tab_bytes <= RVQ_SPLIT_MAX_LDS && (ldo * osz) % 8 == 0 && N * (int64_t)G >= (1 << 17) &&
       ldo < (1 << 20) &&  // offsets within a trip's rows are 32-bit
       (pk == 0 || (G % 4) == 0)) {  // packed: the buffer is a whole number of 32-bit words
     int g_shift = -1;
@@ -863,7 +872,6 @@ hipError_t rvq_launch_decode(const rvq_ctx *ctx, const void *dCodes, int packed,
     int64_t blocks = ((N + tpp - 1) / tpp + DEC_WAVES - 1) / DEC_WAVES;
     const int64_t cap = 256 * 16;  // enough waves to fill the chip; the kernel strides over rows
     if (blocks > cap) blocks = cap;
-    const dim3 grid((unsigned)blocks), block(64 * DEC_WAVES);
     const bool d8 = c.depth == 8;
     // 32 or 64 groups: two units of 32 groups are 1 KiB of codes, one load per lane, and are two
     // tokens or one (with more groups a token's units would land in different wavefronts)
@@ -876,10 +884,21 @@ hipError_t rvq_launch_decode(const rvq_ctx *ctx, const void *dCodes, int packed,
     const bool wide_pk = pk != 0 && wide_fit && ((N * G * (int64_t)pk) % 16) == 0;
     const bool wide_i16 = pk == 0 && wide_fit;
     if (wide_pk || wide_i16) lds_bytes += wide_lds;
+    // fetches of the wide variants: 8 units of 32 groups, or 32 units of 8 (token, group) pairs;
+    // while there are fewer of them than half the wavefronts, 2 or 4 wavefronts share one
+    int split = 1;
+    if (wide_pk || wide_i16) {
+      const int64_t units = wide_ok ? N * (G / 32) : (N + tpp - 1) / tpp;
+      const int64_t fetches = (units + (wide_ok ? 8 : 32) - 1) / (wide_ok ? 8 : 32);
+      const int most = G == 64 ? 4 : 8;  // a token of 64 groups is two units: they stay together
+      while (split < most && fetches * split * 2 <= blocks * DEC_WAVES) split *= 2;
+      if (split == 8) blocks = (blocks + 1) & ~(int64_t)1;  // wavefronts: a multiple of 8
+    }
+    const dim3 grid((unsigned)blocks), block(64 * DEC_WAVES);
 #define RVQ_LAUNCH_ROWS_NP(F16, STR, D8, PK, RO, NP, WD)                                         \
   hipLaunchKernelGGL((decode_rows32_kernel<F16, STR, D8, PK, RO, NP, WD>), grid, block,          \
                      lds_bytes, s, dCodes, dStd, c.std_dtype, N, G, ctx->C, c.K, c.depth,        \
-                     depth_used, dOut, ldo, lds_row, rp)
+                     depth_used, dOut, ldo, lds_row, rp, split)
 #define RVQ_LAUNCH_ROWS(F16, STR, D8, PK, RO)                                                    \
   do {                                                                                           \
     /* the wide variants exist for depth 8 without rotation; for any other instance            */ \

@@ -1,5 +1,6 @@
 // Exact encode path: Algorithm 1 with every distance evaluated in fp32 in direct form,
-// sum_j (r_j - c_j)^2.  One thread owns one group vector through all stages: the residual
+// sum_j (r_j - c_j)^2 (one running sum; for dhat == 32 eight sums of four channels added as a
+// balanced tree).  One thread owns one group vector through all stages: the residual
 // lives in its registers and is never written between stages (the paper fuses the stages for
 // the same reason, Section 3).  Codeword addresses are uniform across a wavefront, so the
 // codebook is read through the scalar cache and broadcast.
@@ -41,11 +42,27 @@ __global__ __launch_bounds__(256) void encode_exact_kernel(
     for (int k = 0; k < K; ++k) {
       const float *__restrict__ c = Ci + (int64_t)k * dhat;
       float dist = 0.f;
+      if constexpr (DH == 32) {
+        // eight partial sums of four channels, added as a balanced tree: the order in which
+        // encode_small_kernel, where eight lanes share a codeword, adds them
+        float part[8];
 #pragma unroll
-      for (int j = 0; j < CAP; ++j) {
-        if (j < dhat) {
-          const float t = r[j] - c[j];
-          dist = fmaf(t, t, dist);
+        for (int q = 0; q < 8; ++q) {
+          part[q] = 0.f;
+#pragma unroll
+          for (int j = 4 * q; j < 4 * q + 4; ++j) {
+            const float t = r[j] - c[j];
+            part[q] = fmaf(t, t, part[q]);
+          }
+        }
+        dist = ((part[0] + part[1]) + (part[2] + part[3])) + ((part[4] + part[5]) + (part[6] + part[7]));
+      } else {
+#pragma unroll
+        for (int j = 0; j < CAP; ++j) {
+          if (j < dhat) {
+            const float t = r[j] - c[j];
+            dist = fmaf(t, t, dist);
+          }
         }
       }
       if (dist < best) {  // strict: the smallest index keeps a tie
@@ -66,7 +83,181 @@ __global__ __launch_bounds__(256) void encode_exact_kernel(
   }
 }
 
+// ---- small batches (dhat == 32): a workgroup owns VPW group vectors, its threads share the K
+// codewords of a stage.  The tokens a serving loop appends per step are a few rows: too few
+// vectors to fill even one workgroup of the matrix-core kernel, whose stages take as long for
+// one token as for a thousand.  Here the 32 groups of one row already make 32 workgroups of 1024
+// threads.  Eight lanes share a codeword, four channels each, so that a wavefront's load
+// instruction covers eight whole rows of the codebook (1 KiB in a piece; with a row per lane
+// every instruction touched 64 lines and the address path, not memory, set the pace: 8 us per
+// stage).  A lane's partial sum of (r - c)^2 over its four channels meets the other seven by
+// three lane-exchange additions: the tree encode_exact_kernel adds in, same tie rule, so this
+// kernel returns that kernel's codes bit for bit.  The argmin is a minimum over (distance bits,
+// index): over the wavefront with lane moves, over the workgroup through LDS.  The residuals
+// live in LDS through all stages (Algorithm 1; Section 3 fuses the stages for the same reason);
+// the codewords of the next pass, or of the next stage's first pass, are requested as soon as
+// the registers of this one are free.
+constexpr int SM_THREADS = 1024;
+constexpr int SM_WAVES = SM_THREADS / 64;
+constexpr int SM_LOADS = 16;                      // load instructions per thread and pass
+constexpr int SM_WAVE_ROWS = 8 * SM_LOADS;        // codewords a wavefront scores per pass
+constexpr int SM_PASS = SM_WAVES * SM_WAVE_ROWS;  // codewords per workgroup and pass (2048)
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t sm_dpp(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xf, 0xf, false);
+}
+template <int CTRL>
+__device__ __forceinline__ float sm_dppf(float v) {
+  return __uint_as_float(sm_dpp<CTRL>(__float_as_uint(v)));
+}
+// minimum over the 64 lanes, the same value in every lane (and in a scalar register)
+__device__ __forceinline__ uint32_t sm_wave_min(uint32_t v) {
+  v = min(v, sm_dpp<0xB1>(v));   // quad_perm [1,0,3,2]
+  v = min(v, sm_dpp<0x4E>(v));   // quad_perm [2,3,0,1]
+  v = min(v, sm_dpp<0x124>(v));  // row_ror 4
+  v = min(v, sm_dpp<0x128>(v));  // row_ror 8: every lane has its row's minimum
+  const uint32_t r0 = (uint32_t)__builtin_amdgcn_readlane((int)v, 0);
+  const uint32_t r1 = (uint32_t)__builtin_amdgcn_readlane((int)v, 16);
+  const uint32_t r2 = (uint32_t)__builtin_amdgcn_readlane((int)v, 32);
+  const uint32_t r3 = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+  return min(min(r0, r1), min(r2, r3));
+}
+
+template <int VPW>
+__global__ __launch_bounds__(SM_THREADS) void encode_small_kernel(
+    const void *__restrict__ X, int in_dtype, int64_t N, int64_t ldx, int G, int grouping,
+    const float *__restrict__ std32, const float *__restrict__ C, int K, int depth, int stage_begin,
+    int stage_end, int16_t *__restrict__ codes, float *__restrict__ residual) {
+  constexpr int DH = 32;
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  __shared__ __align__(16) float rs[VPW][DH];               // the residuals
+  __shared__ unsigned long long wave_best[VPW][SM_WAVES];   // (distance bits, index) per wavefront
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int piece = lane & 7;  // this lane's four channels of a codeword
+  const int64_t V = N * G;
+  const int64_t v0 = (int64_t)blockIdx.x * VPW;
+  // thread (u, j) of the first VPW * 32 looks after element j of vector u: it loads it, takes the
+  // winning codeword's element off it after every stage and stores it at the end
+  const int eu = tid >> 5, ej = tid & 31;
+  const bool elem = tid < VPW * DH;
+  // a vector past the end repeats the last one: scored, never stored
+  const int64_t ev = min(v0 + eu, V - 1);
+  if (elem) {
+    const int64_t n = ev / G;
+    const int g = (int)(ev - n * G);
+    const float x = rvq_load_in_rt(X, n * ldx + channel_of(grouping, G, DH, g, ej), in_dtype);
+    rs[eu][ej] = std32 ? x / std32[n] : x;
+  }
+  constexpr unsigned long long NONE = 0x7f800000ull << 32;  // (+inf, index 0): what no codeword beats
+  // load l of a pass: rows wave_row0 + 8 l .. + 7, this lane has 16 bytes of row + (lane >> 3)
+  f32x4 c4[SM_LOADS];
+  const int lane_row = wave * SM_WAVE_ROWS + (lane >> 3);
+  auto fetch = [&](int stage, int k0) {
+    // a scalar base and 32-bit byte offsets (a stage is at most 32768 rows of 128 bytes)
+    const char *__restrict__ Ci = reinterpret_cast<const char *>(C + (int64_t)stage * K * DH);
+#pragma unroll
+    for (int l = 0; l < SM_LOADS; ++l) {
+      const int k = min(k0 + lane_row + 8 * l, K - 1);  // past the end: fetched, not scored
+      c4[l] = *reinterpret_cast<const f32x4 *>(Ci + ((uint32_t)k * 128u + (uint32_t)piece * 16u));
+    }
+  };
+  fetch(stage_begin, 0);
+  __syncthreads();
+  for (int i = stage_begin; i < stage_end; ++i) {
+    for (int k0 = 0; k0 < K; k0 += SM_PASS) {
+#pragma unroll 1  // one vector at a time
+      for (int u = 0; u < VPW; ++u) {
+        const f32x4 r4 = reinterpret_cast<const f32x4 *>(&rs[u][0])[piece];
+        uint32_t bits = 0xffffffffu, idx = 0xffffffffu;
+#pragma unroll
+        for (int l = 0; l < SM_LOADS; ++l) {
+          float part = 0.f;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const float t = r4[j] - c4[l][j];
+            part = fmaf(t, t, part);
+          }
+          part += sm_dppf<0xB1>(part);   // lanes p ^ 1
+          part += sm_dppf<0x4E>(part);   // lanes p ^ 2: the sum of the quad, in all four
+          part += sm_dppf<0x141>(part);  // mirrored half row: the other quad's sum
+          // distances are >= +0: their bits order like the values; a NaN has larger bits than
+          // +inf and never wins, as with `dist < best`
+          const int k = k0 + lane_row + 8 * l;
+          const uint32_t db = k < K ? __float_as_uint(part) : 0xffffffffu;
+          if (db < bits) {  // a lane's later codewords have the larger indices: strict
+            bits = db;
+            idx = (uint32_t)k;
+          }
+        }
+        const uint32_t m = sm_wave_min(bits);
+        const uint32_t a = sm_wave_min(bits == m ? idx : 0xffffffffu);  // smallest index among equals
+        if (lane == 0) {
+          unsigned long long key = ((unsigned long long)m << 32) | a;
+          if (k0 > 0) {
+            const unsigned long long o = wave_best[u][wave];
+            key = o < key ? o : key;
+          }
+          wave_best[u][wave] = key;
+        }
+      }
+      // registers are free again: the next pass's codewords
+      if (k0 + SM_PASS < K) fetch(i, k0 + SM_PASS);
+    }
+    __syncthreads();
+    int arg = 0;
+    float won = 0.f;
+    if (elem) {
+      unsigned long long b = NONE;
+#pragma unroll
+      for (int w = 0; w < SM_WAVES; ++w) {
+        const unsigned long long o = wave_best[eu][w];
+        b = o < b ? o : b;
+      }
+      arg = (int)(uint32_t)(b & 0xffffffffull);
+      won = C[((int64_t)i * K + arg) * DH + ej];
+    }
+    // the next stage's first codewords go out behind the winner's element: a wavefront's loads
+    // come back in the order they were issued, so the update below waits for its own load only
+    if (i + 1 < stage_end) fetch(i + 1, 0);
+    if (elem) {
+      rs[eu][ej] -= won;
+      if (ej == 0 && v0 + eu < V) codes[(v0 + eu) * depth + i] = (int16_t)arg;
+    }
+    __syncthreads();
+  }
+  if (residual && elem && v0 + eu < V) residual[(v0 + eu) * DH + ej] = rs[eu][ej];
+}
+
 }  // namespace
+
+hipError_t rvq_launch_encode_small(const rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx,
+                                   int stage_begin, int stage_end, int16_t *dCodes,
+                                   float *dResidual, const float *std32_in, hipStream_t s) {
+  const rvq_config &c = ctx->cfg;
+  const int64_t V = N * ctx->G;
+  if (V < 1) return hipSuccess;
+  if (c.dhat != 32 || V > RVQ_SMALL_MAX_VECTORS) return hipErrorInvalidValue;
+  const float *std32 = c.scale ? std32_in : nullptr;
+  // one workgroup fills a CU: a workgroup takes a second vector only when every CU has one
+  int vpw = 1;
+  while (vpw < 8 && V > (int64_t)ctx->num_cus * vpw) vpw *= 2;
+  const dim3 grid((unsigned)((V + vpw - 1) / vpw)), block(SM_THREADS);
+#define RVQ_LAUNCH_SMALL(VPW)                                                                    \
+  hipLaunchKernelGGL(encode_small_kernel<VPW>, grid, block, 0, s, dX, c.in_dtype, N, ldx, ctx->G, \
+                     c.grouping, std32, ctx->C, c.K, c.depth, stage_begin, stage_end, dCodes,    \
+                     dResidual)
+  switch (vpw) {
+    case 1: RVQ_LAUNCH_SMALL(1); break;
+    case 2: RVQ_LAUNCH_SMALL(2); break;
+    case 4: RVQ_LAUNCH_SMALL(4); break;
+    default: RVQ_LAUNCH_SMALL(8); break;
+  }
+#undef RVQ_LAUNCH_SMALL
+  return hipGetLastError();
+}
 
 hipError_t rvq_launch_encode_exact(const rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx,
                                    int stage_begin, int stage_end, int16_t *dCodes,

@@ -56,6 +56,9 @@ def _half_ulp_distance(a_bits, b_bits):
     return np.abs(key(a_bits) - key(b_bits))
 
 
+SMALL_MAX_VECTORS = 2048  # up to here rvq_encode (path chosen by the library) takes the small-batch kernel
+
+
 def check_encode(Xs, in_dtype, d, dhat, depth, K, grouping, C32, *, path=0, sample_rows=None,
                  std_dtype="fp32", min_equal=0.9999, mismatch_cap=None, ddof=0, ldx=None,
                  keep=False):
@@ -64,6 +67,12 @@ def check_encode(Xs, in_dtype, d, dhat, depth, K, grouping, C32, *, path=0, samp
     the quantizer and the device outputs as well (the caller closes the quantizer)."""
     torch, b = _torch(), _b()
     N = Xs.shape[0]
+    if path == 0 and dhat == 32 and N * (d // dhat) <= SMALL_MAX_VECTORS and not keep:
+        # so few vectors go to the small-batch kernel: hold the matrix-core kernel to the same bar
+        # on this shape as well
+        check_encode(Xs, in_dtype, d, dhat, depth, K, grouping, C32, path=2, sample_rows=sample_rows,
+                     std_dtype=std_dtype, min_equal=min_equal, mismatch_cap=mismatch_cap, ddof=ddof,
+                     ldx=ldx)
     q = b.Quantizer(d=d, dhat=dhat, depth=depth, K=K, grouping=grouping, in_dtype=b.DTYPES[in_dtype],
                     out_dtype=b.F32, std_dtype=b.DTYPES[std_dtype], encode_path=path, std_ddof=ddof)
     q.set_codebooks(torch.from_numpy(C32).cuda())
@@ -209,6 +218,77 @@ def test_encode_small_and_ragged(gpu_device, case):
         Z = np.concatenate([Z] + [Z + 0.05 * rng.standard_normal(Z.shape) for _ in range(reps)])
     C = oracle.sample_init_codebooks(Z, depth, K, np.random.Generator(np.random.PCG64(7)))
     check_encode(X, dtype, d, dhat, depth, K, grouping, C.astype(np.float32))
+
+
+@pytest.mark.parametrize("case", [
+    # N, d, depth, K, grouping, dtype, scale   (N * d / 32 <= 2048 vectors: the small-batch kernel)
+    (1, 1024, 8, 2048, oracle.STRIDED, "bf16", 1),      # one appended token: 32 workgroups
+    (8, 1024, 8, 2048, oracle.CONTIGUOUS, "fp16", 1),   # 256 vectors, one per workgroup
+    (9, 1024, 8, 2048, oracle.STRIDED, "fp32", 1),      # 288: two per workgroup
+    (33, 1024, 8, 2048, oracle.STRIDED, "bf16", 1),     # 1056: eight per workgroup
+    (64, 1024, 8, 2048, oracle.CONTIGUOUS, "bf16", 1),  # the most the kernel takes
+    (61, 128, 3, 100, oracle.STRIDED, "fp32", 1),       # a codebook that ends inside a load
+    (50, 96, 5, 1, oracle.CONTIGUOUS, "fp16", 1),       # one codeword
+    (20, 64, 2, 5000, oracle.STRIDED, "fp32", 1),       # three passes over the codebook, the last ragged
+    (3, 32, 16, 33, oracle.STRIDED, "fp32", 0),         # one group, 16 stages, rows not scaled
+])
+def test_encode_few_rows_equals_the_exact_path(gpu_device, case):
+    """The kernel for a few rows (what a serving loop appends per step) returns the codes, std and
+    residuals of the exact path bit for bit: same fp32 direct-form distances added in the same
+    order, same tie rule.  Also over a stage range that starts from given residuals.  (Both
+    paths are held to the oracle by the other tests of this file.)"""
+    torch, b = _torch(), _b()
+    N, d, depth, K, grouping, dtype, scale = case
+    G = d // 32
+    assert N * G <= SMALL_MAX_VECTORS
+    X = synth.gaussian_rows(N, d, seed=4000 + N + K, dtype=dtype, outliers=max(1, d // 50))
+    rng = np.random.Generator(np.random.PCG64(N + K))
+    C = (rng.standard_normal((depth, K, 32)) * (0.7 ** np.arange(depth))[:, None, None]).astype(np.float32)
+    if K > 1:
+        C[0, K - 1] = C[0, 0]  # an exact tie between the first and the last codeword: the first wins
+    dX = _to_dev(X, dtype)
+    got = {}
+    for path in (b.PATH_AUTO, b.PATH_EXACT):
+        q = b.Quantizer(d=d, dhat=32, depth=depth, K=K, grouping=grouping, in_dtype=b.DTYPES[dtype],
+                        std_dtype=b.F16, scale=scale, encode_path=path)
+        q.set_codebooks(torch.from_numpy(C).cuda())
+        codes = torch.full((N, G, depth), -1, dtype=torch.int16, device="cuda")
+        std = torch.zeros(N, dtype=torch.float16, device="cuda")
+        res = torch.zeros((N, G, 32), dtype=torch.float32, device="cuda")
+        b.rvq_encode(q.ctx, dX, N, d, 0, depth, codes, std, res)
+        # stages [1, depth) again, from the residuals that stage 0 left
+        codes2 = codes.clone()
+        res2 = torch.zeros_like(res)
+        if depth > 1:
+            q0 = b.Quantizer(d=d, dhat=32, depth=depth, K=K, grouping=b.CONTIGUOUS, in_dtype=b.F32,
+                             scale=0, encode_path=path)
+            q0.set_codebooks(torch.from_numpy(C).cuda())
+            r1 = torch.zeros_like(res)
+            c1 = torch.full_like(codes, -1)
+            b.rvq_encode(q0.ctx, _stage0_residual(b, q, dX, N, d, G, depth), N, d, 1, depth, c1, None, r1)
+            codes2, res2 = c1, r1
+            q0.close()
+        torch.cuda.synchronize()
+        assert b.rvq_check_kernels(q.ctx) == 0
+        got[path] = (codes.cpu(), std.cpu(), res.cpu(), codes2.cpu(), res2.cpu())
+        q.close()
+    small, exact = got[b.PATH_AUTO], got[b.PATH_EXACT]
+    assert int(exact[0].min()) >= 0 and int(exact[0].max()) < K
+    for name, x, y in zip(("codes", "std", "residual", "codes of stages 1..", "their residual"), small, exact):
+        assert torch.equal(x.view(torch.uint8), y.view(torch.uint8)), name
+    if depth > 1:  # the range call continues what the full call did
+        assert torch.equal(small[3][:, :, 1:], small[0][:, :, 1:])
+        assert torch.equal(small[4], small[2])
+
+
+def _stage0_residual(b, q, dX, N, d, G, depth):
+    """Residuals after stage 0, in group order [N][G * 32], from a one-stage call."""
+    torch = _torch()
+    c = torch.zeros((N, G, depth), dtype=torch.int16, device="cuda")
+    s = torch.zeros(N, dtype=torch.float16, device="cuda")
+    r = torch.zeros((N, G, 32), dtype=torch.float32, device="cuda")
+    b.rvq_encode(q.ctx, dX, N, d, 0, 1, c, s, r)
+    return r.view(N, d)
 
 
 def test_encode_std_in_half_precision_and_bessel(gpu_device):
