@@ -124,7 +124,7 @@ int rvq_get_codebooks(rvq_ctx *ctx, float *dC, void *stream);
  *             (z_{i+1} of Algorithm 1, in group order); NULL to skip
  * Nearest = smallest squared Euclidean distance; ties go to the smallest index.  A row whose std
  * is below 1e-30 is scaled by 1.
- * With dhat == 32 and encode_path RVQ_PATH_AUTO, calls of at most 2048 group vectors (N * d / 32:
+ * With dhat == 32 and encode_path RVQ_PATH_AUTO, calls of at most 4096 group vectors (N * d / 32:
  * the few rows a serving loop appends per step) run a kernel built for latency that returns the
  * codes of RVQ_PATH_EXACT bit for bit; larger calls run the matrix-core kernel.
  * With cfg.scale == 1, N must not exceed rvq_reserved_rows(): RVQ_EWORKSPACE otherwise (nothing

@@ -87,11 +87,12 @@ __global__ __launch_bounds__(256) void encode_exact_kernel(
 // codewords of a stage.  The tokens a serving loop appends per step are a few rows: too few
 // vectors to fill even one workgroup of the matrix-core kernel, whose stages take as long for
 // one token as for a thousand.  Here the 32 groups of one row already make 32 workgroups of 1024
-// threads.  Eight lanes share a codeword, four channels each, so that a wavefront's load
-// instruction covers eight whole rows of the codebook (1 KiB in a piece; with a row per lane
+// threads.  LPC lanes share a codeword, 32 / LPC channels each: with four, the loads of a
+// wavefront instruction cover sixteen codebook rows half a line at a time (with a row per lane
 // every instruction touched 64 lines and the address path, not memory, set the pace: 8 us per
-// stage).  A lane's partial sum of (r - c)^2 over its four channels meets the other seven by
-// three lane-exchange additions: the tree encode_exact_kernel adds in, same tie rule, so this
+// stage instead of 3.5).  A lane's partial sums of (r - c)^2 over four channels each meet the
+// others in a balanced tree, inside the lane first and then by lane-exchange additions: the
+// tree encode_exact_kernel adds in, same tie rule, so for every LPC this
 // kernel returns that kernel's codes bit for bit.  The argmin is a minimum over (distance bits,
 // index): over the wavefront with lane moves, over the workgroup through LDS.  The residuals
 // live in LDS through all stages (Algorithm 1; Section 3 fuses the stages for the same reason);
@@ -124,7 +125,10 @@ __device__ __forceinline__ uint32_t sm_wave_min(uint32_t v) {
   return min(min(r0, r1), min(r2, r3));
 }
 
-template <int VPW>
+// VPW: vectors per workgroup.  LPC: lanes that share a codeword (8, 4, 2 or 1), each with
+// 32 / LPC channels.  The partial sums meet in the same tree whatever LPC is (inside the lane
+// first, then by lane exchanges), so every instantiation returns the same bits.
+template <int VPW, int LPC>
 __global__ __launch_bounds__(SM_THREADS) void encode_small_kernel(
     const void *__restrict__ X, int in_dtype, int64_t N, int64_t ldx, int G, int grouping,
     const float *__restrict__ std32, const float *__restrict__ C, int K, int depth, int stage_begin,
@@ -136,7 +140,10 @@ __global__ __launch_bounds__(SM_THREADS) void encode_small_kernel(
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int piece = lane & 7;  // this lane's four channels of a codeword
+  constexpr int NQ = 8 / LPC;         // 16-byte pieces of a codeword in this lane
+  constexpr int RPL = SM_LOADS / NQ;  // codewords per lane and pass
+  constexpr int RSTEP = 64 / LPC;     // codewords a load instruction of the wavefront covers
+  const int piece = (lane & (LPC - 1)) * NQ;  // this lane's first piece of four channels
   const int64_t V = N * G;
   const int64_t v0 = (int64_t)blockIdx.x * VPW;
   // thread (u, j) of the first VPW * 32 looks after element j of vector u: it loads it, takes the
@@ -152,16 +159,20 @@ __global__ __launch_bounds__(SM_THREADS) void encode_small_kernel(
     rs[eu][ej] = std32 ? x / std32[n] : x;
   }
   constexpr unsigned long long NONE = 0x7f800000ull << 32;  // (+inf, index 0): what no codeword beats
-  // load l of a pass: rows wave_row0 + 8 l .. + 7, this lane has 16 bytes of row + (lane >> 3)
+  // codeword slot j of a pass: rows wave_row0 + RSTEP j .. + RSTEP - 1, this lane has NQ pieces of
+  // row + lane / LPC
   f32x4 c4[SM_LOADS];
-  const int lane_row = wave * SM_WAVE_ROWS + (lane >> 3);
+  const int lane_row = wave * SM_WAVE_ROWS + lane / LPC;
   auto fetch = [&](int stage, int k0) {
     // a scalar base and 32-bit byte offsets (a stage is at most 32768 rows of 128 bytes)
     const char *__restrict__ Ci = reinterpret_cast<const char *>(C + (int64_t)stage * K * DH);
 #pragma unroll
-    for (int l = 0; l < SM_LOADS; ++l) {
-      const int k = min(k0 + lane_row + 8 * l, K - 1);  // past the end: fetched, not scored
-      c4[l] = *reinterpret_cast<const f32x4 *>(Ci + ((uint32_t)k * 128u + (uint32_t)piece * 16u));
+    for (int j = 0; j < RPL; ++j) {
+      const int k = min(k0 + lane_row + RSTEP * j, K - 1);  // past the end: fetched, not scored
+#pragma unroll
+      for (int t = 0; t < NQ; ++t)
+        c4[j * NQ + t] =
+            *reinterpret_cast<const f32x4 *>(Ci + ((uint32_t)k * 128u + (uint32_t)(piece + t) * 16u));
     }
   };
   fetch(stage_begin, 0);
@@ -170,22 +181,34 @@ __global__ __launch_bounds__(SM_THREADS) void encode_small_kernel(
     for (int k0 = 0; k0 < K; k0 += SM_PASS) {
 #pragma unroll 1  // one vector at a time
       for (int u = 0; u < VPW; ++u) {
-        const f32x4 r4 = reinterpret_cast<const f32x4 *>(&rs[u][0])[piece];
+        f32x4 r4[NQ];
+#pragma unroll
+        for (int t = 0; t < NQ; ++t) r4[t] = reinterpret_cast<const f32x4 *>(&rs[u][0])[piece + t];
         uint32_t bits = 0xffffffffu, idx = 0xffffffffu;
 #pragma unroll
-        for (int l = 0; l < SM_LOADS; ++l) {
-          float part = 0.f;
+        for (int l = 0; l < RPL; ++l) {
+          float pq[NQ];
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const float t = r4[j] - c4[l][j];
-            part = fmaf(t, t, part);
+          for (int t = 0; t < NQ; ++t) {
+            pq[t] = 0.f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const float d = r4[t][j] - c4[l * NQ + t][j];
+              pq[t] = fmaf(d, d, pq[t]);
+            }
           }
-          part += sm_dppf<0xB1>(part);   // lanes p ^ 1
-          part += sm_dppf<0x4E>(part);   // lanes p ^ 2: the sum of the quad, in all four
-          part += sm_dppf<0x141>(part);  // mirrored half row: the other quad's sum
+          // the tree over the eight sums of four channels: levels inside the lane, then lanes
+#pragma unroll
+          for (int w = 1; w < NQ; w *= 2)
+#pragma unroll
+            for (int t = 0; t < NQ; t += 2 * w) pq[t] += pq[t + w];
+          float part = pq[0];
+          if constexpr (LPC >= 2) part += sm_dppf<0xB1>(part);   // lanes p ^ 1
+          if constexpr (LPC >= 4) part += sm_dppf<0x4E>(part);   // lanes p ^ 2: the quad's sum, in all four
+          if constexpr (LPC >= 8) part += sm_dppf<0x141>(part);  // mirrored half row: the other quad's sum
           // distances are >= +0: their bits order like the values; a NaN has larger bits than
           // +inf and never wins, as with `dist < best`
-          const int k = k0 + lane_row + 8 * l;
+          const int k = k0 + lane_row + RSTEP * l;
           const uint32_t db = k < K ? __float_as_uint(part) : 0xffffffffu;
           if (db < bits) {  // a lane's later codewords have the larger indices: strict
             bits = db;
@@ -243,17 +266,21 @@ hipError_t rvq_launch_encode_small(const rvq_ctx *ctx, const void *dX, int64_t N
   const float *std32 = c.scale ? std32_in : nullptr;
   // one workgroup fills a CU: a workgroup takes a second vector only when every CU has one
   int vpw = 1;
-  while (vpw < 8 && V > (int64_t)ctx->num_cus * vpw) vpw *= 2;
+  while (vpw < 16 && V > (int64_t)ctx->num_cus * vpw) vpw *= 2;
   const dim3 grid((unsigned)((V + vpw - 1) / vpw)), block(SM_THREADS);
-#define RVQ_LAUNCH_SMALL(VPW)                                                                    \
-  hipLaunchKernelGGL(encode_small_kernel<VPW>, grid, block, 0, s, dX, c.in_dtype, N, ldx, ctx->G, \
-                     c.grouping, std32, ctx->C, c.K, c.depth, stage_begin, stage_end, dCodes,    \
-                     dResidual)
+#define RVQ_LAUNCH_SMALL(VPW, LPC)                                                               \
+  hipLaunchKernelGGL((encode_small_kernel<VPW, LPC>), grid, block, 0, s, dX, c.in_dtype, N, ldx, \
+                     ctx->G, c.grouping, std32, ctx->C, c.K, c.depth, stage_begin, stage_end,    \
+                     dCodes, dResidual)
+  // lanes per codeword, measured: four while a workgroup has up to four vectors (the loads of a
+  // wavefront instruction then cover whole lines in pairs, and two of the three tree levels
+  // between lanes remain), fewer as the arithmetic per fetched codeword grows
   switch (vpw) {
-    case 1: RVQ_LAUNCH_SMALL(1); break;
-    case 2: RVQ_LAUNCH_SMALL(2); break;
-    case 4: RVQ_LAUNCH_SMALL(4); break;
-    default: RVQ_LAUNCH_SMALL(8); break;
+    case 1: RVQ_LAUNCH_SMALL(1, 4); break;
+    case 2: RVQ_LAUNCH_SMALL(2, 4); break;
+    case 4: RVQ_LAUNCH_SMALL(4, 4); break;
+    case 8: RVQ_LAUNCH_SMALL(8, 2); break;
+    default: RVQ_LAUNCH_SMALL(16, 1); break;
   }
 #undef RVQ_LAUNCH_SMALL
   return hipGetLastError();

@@ -111,7 +111,7 @@ hipError_t rvq_launch_encode_exact(const rvq_ctx *ctx, const void *dX, int64_t N
                                    float *dResidual, const float *std32, hipStream_t s);
 // dhat == 32 and at most RVQ_SMALL_MAX_VECTORS group vectors: the codes of the exact kernel, with
 // the codebook of a stage split over the threads of a workgroup (latency of a few rows)
-constexpr int64_t RVQ_SMALL_MAX_VECTORS = 2048;
+constexpr int64_t RVQ_SMALL_MAX_VECTORS = 4096;
 hipError_t rvq_launch_encode_small(const rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx,
                                    int stage_begin, int stage_end, int16_t *dCodes,
                                    float *dResidual, const float *std32, hipStream_t s);

@@ -56,7 +56,7 @@ def _half_ulp_distance(a_bits, b_bits):
     return np.abs(key(a_bits) - key(b_bits))
 
 
-SMALL_MAX_VECTORS = 2048  # up to here rvq_encode (path chosen by the library) takes the small-batch kernel
+SMALL_MAX_VECTORS = 4096  # up to here rvq_encode (path chosen by the library) takes the small-batch kernel
 
 
 def check_encode(Xs, in_dtype, d, dhat, depth, K, grouping, C32, *, path=0, sample_rows=None,
@@ -221,12 +221,14 @@ def test_encode_small_and_ragged(gpu_device, case):
 
 
 @pytest.mark.parametrize("case", [
-    # N, d, depth, K, grouping, dtype, scale   (N * d / 32 <= 2048 vectors: the small-batch kernel)
+    # N, d, depth, K, grouping, dtype, scale   (N * d / 32 <= 4096 vectors: the small-batch kernel)
     (1, 1024, 8, 2048, oracle.STRIDED, "bf16", 1),      # one appended token: 32 workgroups
     (8, 1024, 8, 2048, oracle.CONTIGUOUS, "fp16", 1),   # 256 vectors, one per workgroup
-    (9, 1024, 8, 2048, oracle.STRIDED, "fp32", 1),      # 288: two per workgroup
-    (33, 1024, 8, 2048, oracle.STRIDED, "bf16", 1),     # 1056: eight per workgroup
-    (64, 1024, 8, 2048, oracle.CONTIGUOUS, "bf16", 1),  # the most the kernel takes
+    (9, 1024, 8, 2048, oracle.STRIDED, "fp32", 1),      # 288: two per workgroup, four lanes a codeword
+    (30, 1024, 8, 2048, oracle.CONTIGUOUS, "fp16", 1),  # 960: four per workgroup
+    (33, 1024, 8, 2048, oracle.STRIDED, "bf16", 1),     # 1056: eight per workgroup, two lanes a codeword
+    (100, 1024, 8, 2048, oracle.STRIDED, "bf16", 1),    # 3200: sixteen per workgroup, a codeword a lane
+    (128, 1024, 8, 2048, oracle.CONTIGUOUS, "bf16", 1),  # the most the kernel takes
     (61, 128, 3, 100, oracle.STRIDED, "fp32", 1),       # a codebook that ends inside a load
     (50, 96, 5, 1, oracle.CONTIGUOUS, "fp16", 1),       # one codeword
     (20, 64, 2, 5000, oracle.STRIDED, "fp32", 1),       # three passes over the codebook, the last ragged
