@@ -1055,14 +1055,14 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
     const int i = sg % nst;
     if (single_chunk && sg > 0 && nst > 1) {  // (one stage per call: the operands stay)
       if (team == 0) {
-        spin_ge(0, 4u * sg);
-        spin_ge(1, 4u * sg);
+        spin_ge(0, (unsigned)(SCR_WAVES / 2) * sg);
+        spin_ge(1, (unsigned)(SCR_WAVES / 2) * sg);
         PHASE_MARK(8);  // waiting for the end of the previous stage's phase L
         stage_to_lds(a.stage_begin + i, 0, a.Kpad, wave, SCR_WAVES / 2);
         __builtin_amdgcn_s_waitcnt(0x0f70);
         signal(2);
       }
-      spin_ge(2, 4u * sg);
+      spin_ge(2, (unsigned)(SCR_WAVES / 2) * sg);
       PHASE_MARK(2);  // staging
     }
     lds_phase(a.stage_begin + i);
