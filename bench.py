@@ -51,7 +51,7 @@ def parse():
     ap.add_argument("--decode-slices", type=int, default=64)
     ap.add_argument("--cpu-rows", type=int, default=32768)
     ap.add_argument("--encode-path", type=int, default=0)
-    ap.add_argument("--profile", choices=["encode", "decode", "ema", "attn", "copy"], default=None,
+    ap.add_argument("--profile", choices=["encode", "decode", "ema", "attn", "append", "copy"], default=None,
                     help="run only one kernel a few times (for rocprofv3 runs; prints no JSON)")
     return ap.parse_args()
 
@@ -527,6 +527,9 @@ def run_profile(args):
         return
     if args.profile == "attn":
         print(run_attn_decode(args))
+        return
+    if args.profile == "append":
+        print(run_append(args))
         return
     if args.profile == "decode":
         T, d, G, depth, K = 16 * 32768, 1024, 32, 8, 2048
