@@ -624,7 +624,7 @@ __global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
   // trips c = xcd (mod 8) belong to this XCD; its `parts` workgroups per channel pair take them
   // in turn.  Everything inside a trip is addressed with 32-bit offsets from per-trip bases that
   // are the same for the whole workgroup (scalar registers).
-  // Codes and std of a trip are fetched one trip ahead, into two register sets used in turn.
+  // Codes and std of a trip are fetched two trips ahead, into three register sets used in turn.
   // Loads carry no bounds branch: a pair index beyond the end is clamped to the last pair (V >= 1
   // on this path), whose data is fetched and never stored.
   constexpr int REC = PK ? PK : 16;  // bytes of one pair's codes (this kernel is for depth 8)
@@ -786,17 +786,24 @@ __global__ __launch_bounds__(SPL_THREADS) void decode_split_kernel(
       }
     }
   };
-  i32x4 bufA[SPL_UNROLL], bufB[SPL_UNROLL];
-  float sdA[SPL_UNROLL], sdB[SPL_UNROLL];
-  int sbA[SPL_UNROLL], sbB[SPL_UNROLL];  // packed records only
+  // three register sets in turn: a trip's codes are requested two trips before they are used
+  // (one trip is about as long as a read from HBM takes under load)
+  i32x4 bufA[SPL_UNROLL], bufB[SPL_UNROLL], bufC[SPL_UNROLL];
+  float sdA[SPL_UNROLL], sdB[SPL_UNROLL], sdC[SPL_UNROLL];
+  int sbA[SPL_UNROLL], sbB[SPL_UNROLL], sbC[SPL_UNROLL];  // packed records only
   load_trip(c, bufA, sdA, sbA);
+  load_trip(c + step, bufB, sdB, sbB);
   while (c < trips) {
-    load_trip(c + step, bufB, sdB, sbB);
+    load_trip(c + 2 * step, bufC, sdC, sbC);
     do_trip(bufA, sdA, sbA);
     c += step;
     if (c >= trips) break;
-    load_trip(c + step, bufA, sdA, sbA);
+    load_trip(c + 2 * step, bufA, sdA, sbA);
     do_trip(bufB, sdB, sbB);
+    c += step;
+    if (c >= trips) break;
+    load_trip(c + 2 * step, bufB, sdB, sbB);
+    do_trip(bufC, sdC, sbC);
     c += step;
   }
 }
