@@ -325,8 +325,8 @@ def run_workload5(args):
 def run_append(args):
     """What a serving loop does per generated token: encode the few rows that were appended
     (1, 8, 64 rows of workload 2's shape) and decode a short cache (1024 and 8192 rows).  Times
-    per call in microseconds, stream time over 200 calls back to back (two kernels per encode:
-    std and search)."""
+    per call in microseconds, stream time over 200 calls back to back (one kernel per encode of so
+    few rows: std and search together)."""
     import numpy as np
     import torch
 

@@ -56,17 +56,20 @@ int validate_config(const rvq_config *c) {
   return RVQ_OK;
 }
 
-// the two kernels of an encode call: per-row std into std32 (and the caller's buffer), then
-// Algorithm 1 over the stage range
+// the kernels of an encode call: per-row std into std32 (and the caller's buffer), then
+// Algorithm 1 over the stage range; a few rows take one kernel that does both
 int encode_enqueue(rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx, int stage_begin,
                    int stage_end, int16_t *dCodes, void *dStd, float *dResidual, float *std32,
                    hipStream_t s) {
   const rvq_config &c = ctx->cfg;
-  if (c.scale) RVQ_HIP(ctx, rvq_launch_row_std(ctx, dX, N, ldx, dStd, std32, s));
-  if (c.dhat == 32 && c.encode_path == RVQ_PATH_AUTO && N * ctx->G <= RVQ_SMALL_MAX_VECTORS)
+  if (c.dhat == 32 && c.encode_path == RVQ_PATH_AUTO && N * ctx->G <= RVQ_SMALL_MAX_VECTORS) {
+    // a few rows: one kernel, which computes the rows' std itself
     RVQ_HIP(ctx, rvq_launch_encode_small(ctx, dX, N, ldx, stage_begin, stage_end, dCodes,
-                                         dResidual, std32, s));
-  else if (c.dhat == 32 && c.encode_path != RVQ_PATH_EXACT)
+                                         dResidual, dStd, s));
+    return RVQ_OK;
+  }
+  if (c.scale) RVQ_HIP(ctx, rvq_launch_row_std(ctx, dX, N, ldx, dStd, std32, s));
+  if (c.dhat == 32 && c.encode_path != RVQ_PATH_EXACT)
     RVQ_HIP(ctx, rvq_launch_encode_screen(ctx, dX, N, ldx, stage_begin, stage_end, dCodes,
                                           dResidual, std32, s));
   else

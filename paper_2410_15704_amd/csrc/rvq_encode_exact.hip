@@ -131,12 +131,14 @@ __device__ __forceinline__ uint32_t sm_wave_min(uint32_t v) {
 template <int VPW, int LPC>
 __global__ __launch_bounds__(SM_THREADS) void encode_small_kernel(
     const void *__restrict__ X, int in_dtype, int64_t N, int64_t ldx, int G, int grouping,
-    const float *__restrict__ std32, const float *__restrict__ C, int K, int depth, int stage_begin,
-    int stage_end, int16_t *__restrict__ codes, float *__restrict__ residual) {
+    int scale /* rows are divided by their std, computed here */, int ddof, bool vec_rows,
+    void *__restrict__ std_out, int std_dtype, const float *__restrict__ C, int K, int depth,
+    int stage_begin, int stage_end, int16_t *__restrict__ codes, float *__restrict__ residual) {
   constexpr int DH = 32;
   typedef float f32x4 __attribute__((ext_vector_type(4)));
   __shared__ __align__(16) float rs[VPW][DH];               // the residuals
   __shared__ unsigned long long wave_best[VPW][SM_WAVES];   // (distance bits, index) per wavefront
+  __shared__ float row_sd[SM_WAVES];                        // std of the rows this workgroup touches
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -152,12 +154,6 @@ __global__ __launch_bounds__(SM_THREADS) void encode_small_kernel(
   const bool elem = tid < VPW * DH;
   // a vector past the end repeats the last one: scored, never stored
   const int64_t ev = min(v0 + eu, V - 1);
-  if (elem) {
-    const int64_t n = ev / G;
-    const int g = (int)(ev - n * G);
-    const float x = rvq_load_in_rt(X, n * ldx + channel_of(grouping, G, DH, g, ej), in_dtype);
-    rs[eu][ej] = std32 ? x / std32[n] : x;
-  }
   constexpr unsigned long long NONE = 0x7f800000ull << 32;  // (+inf, index 0): what no codeword beats
   // codeword slot j of a pass: rows wave_row0 + RSTEP j .. + RSTEP - 1, this lane has NQ pieces of
   // row + lane / LPC
@@ -175,7 +171,43 @@ __global__ __launch_bounds__(SM_THREADS) void encode_small_kernel(
             *reinterpret_cast<const f32x4 *>(Ci + ((uint32_t)k * 128u + (uint32_t)(piece + t) * 16u));
     }
   };
+  // requested first: the loads below come back behind these, which stage 0 needs anyway
   fetch(stage_begin, 0);
+  // The rows of this workgroup's vectors (at most VPW <= 16 of them): wavefront w takes row
+  // n_first + w, with the arithmetic of row_std_kernel; the workgroup that holds a row's group 0
+  // stores the value.
+  const int64_t n_first = v0 / G;
+  const int64_t en = ev / G;  // row and group of this thread's element
+  const int eg = (int)(ev - en * G);
+  float ex = 0.f;
+  if (elem) ex = rvq_load_in_rt(X, en * ldx + channel_of(grouping, G, DH, eg, ej), in_dtype);
+  if (scale) {
+    const int64_t n_last = min(v0 + VPW - 1, V - 1) / G;
+    const int64_t n = n_first + wave;
+    if (n <= n_last) {
+      const int d = G * DH;
+      float sd;
+      const int64_t base = n * ldx;
+      if (vec_rows) {
+        sd = in_dtype == RVQ_F32    ? rvq_row_std<RVQ_F32, true>(X, base, d, ddof, lane)
+             : in_dtype == RVQ_BF16 ? rvq_row_std<RVQ_BF16, true>(X, base, d, ddof, lane)
+                                    : rvq_row_std<RVQ_F16, true>(X, base, d, ddof, lane);
+      } else {
+        sd = in_dtype == RVQ_F32    ? rvq_row_std<RVQ_F32, false>(X, base, d, ddof, lane)
+             : in_dtype == RVQ_BF16 ? rvq_row_std<RVQ_BF16, false>(X, base, d, ddof, lane)
+                                    : rvq_row_std<RVQ_F16, false>(X, base, d, ddof, lane);
+      }
+      if (lane == 0) {
+        row_sd[wave] = sd;
+        if (std_out && n * G >= v0 && n * G < v0 + VPW) {
+          if (std_dtype == RVQ_F32) reinterpret_cast<float *>(std_out)[n] = sd;
+          else reinterpret_cast<uint16_t *>(std_out)[n] = rvq_f32_to_f16_bits_sat(sd);
+        }
+      }
+    }
+    __syncthreads();
+  }
+  if (elem) rs[eu][ej] = scale ? ex / row_sd[en - n_first] : ex;
   __syncthreads();
   for (int i = stage_begin; i < stage_end; ++i) {
     for (int k0 = 0; k0 < K; k0 += SM_PASS) {
@@ -258,20 +290,20 @@ __global__ __launch_bounds__(SM_THREADS) void encode_small_kernel(
 
 hipError_t rvq_launch_encode_small(const rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx,
                                    int stage_begin, int stage_end, int16_t *dCodes,
-                                   float *dResidual, const float *std32_in, hipStream_t s) {
+                                   float *dResidual, void *dStd, hipStream_t s) {
   const rvq_config &c = ctx->cfg;
   const int64_t V = N * ctx->G;
   if (V < 1) return hipSuccess;
   if (c.dhat != 32 || V > RVQ_SMALL_MAX_VECTORS) return hipErrorInvalidValue;
-  const float *std32 = c.scale ? std32_in : nullptr;
+  const bool vec_rows = rvq_rows_vectorizable(dX, ldx, c.d, c.in_dtype);
   // one workgroup fills a CU: a workgroup takes a second vector only when every CU has one
   int vpw = 1;
   while (vpw < 16 && V > (int64_t)ctx->num_cus * vpw) vpw *= 2;
   const dim3 grid((unsigned)((V + vpw - 1) / vpw)), block(SM_THREADS);
 #define RVQ_LAUNCH_SMALL(VPW, LPC)                                                               \
   hipLaunchKernelGGL((encode_small_kernel<VPW, LPC>), grid, block, 0, s, dX, c.in_dtype, N, ldx, \
-                     ctx->G, c.grouping, std32, ctx->C, c.K, c.depth, stage_begin, stage_end,    \
-                     dCodes, dResidual)
+                     ctx->G, c.grouping, c.scale, c.std_ddof, vec_rows, dStd, c.std_dtype,       \
+                     ctx->C, c.K, c.depth, stage_begin, stage_end, dCodes, dResidual)
   // lanes per codeword, measured: four while a workgroup has up to four vectors (the loads of a
   // wavefront instruction then cover whole lines in pairs, and two of the three tree levels
   // between lanes remain), fewer as the arithmetic per fetched codeword grows

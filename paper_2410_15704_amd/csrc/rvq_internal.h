@@ -99,6 +99,79 @@ __device__ __forceinline__ uint16_t rvq_f32_to_f16_bits_sat(float v) {
   return __half_as_ushort(__float2half_rn(v));
 }
 
+// ---- per-row standard deviation (Section 2.2: every vector is scaled by its own std) -----------
+// One 64-lane wavefront per row, two passes over the row (mean, then squared deviations; the
+// second pass hits in cache): std = sqrt(sum (x - mean)^2 / (d - ddof)); below 1e-30 -> 1.  Every
+// lane returns the value.  VEC: the row is read in 16-byte pieces (the caller has checked that
+// rows start on 16-byte boundaries and hold a whole number of pieces).  row_std_kernel and the
+// encode kernel for a few rows both call this, so their values are the same bits.
+__device__ __forceinline__ float rvq_wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+template <int DT, bool VEC>
+__device__ __forceinline__ float rvq_row_std(const void *__restrict__ X, int64_t base, int d,
+                                             int ddof, int lane) {
+  constexpr int EPP = DT == RVQ_F32 ? 4 : 8;  // elements per 16-byte piece
+  // the values of piece `pc` of the row, widened
+  auto piece = [&](int pc, float *v) {
+    const uint4 w = reinterpret_cast<const uint4 *>(
+        reinterpret_cast<const char *>(X) + base * (DT == RVQ_F32 ? 4 : 2))[pc];
+    const uint32_t u[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if constexpr (DT == RVQ_F32) {
+        v[i] = __uint_as_float(u[i]);
+      } else if constexpr (DT == RVQ_BF16) {
+        v[2 * i] = rvq_bf16_bits_to_f32((uint16_t)(u[i] & 0xffffu));
+        v[2 * i + 1] = rvq_bf16_bits_to_f32((uint16_t)(u[i] >> 16));
+      } else {
+        v[2 * i] = rvq_f16_bits_to_f32((uint16_t)(u[i] & 0xffffu));
+        v[2 * i + 1] = rvq_f16_bits_to_f32((uint16_t)(u[i] >> 16));
+      }
+    }
+  };
+  float sum = 0.f;
+  if constexpr (VEC) {
+    for (int pc = lane; pc < d / EPP; pc += 64) {
+      float v[EPP];
+      piece(pc, v);
+#pragma unroll
+      for (int i = 0; i < EPP; ++i) sum += v[i];
+    }
+  } else {
+    for (int c = lane; c < d; c += 64) sum += rvq_load_in<DT>(X, base + c);
+  }
+  const float mean = rvq_wave_sum(sum) / (float)d;
+  float ss = 0.f;
+  if constexpr (VEC) {
+    for (int pc = lane; pc < d / EPP; pc += 64) {
+      float v[EPP];
+      piece(pc, v);
+#pragma unroll
+      for (int i = 0; i < EPP; ++i) {
+        const float t = v[i] - mean;
+        ss = fmaf(t, t, ss);
+      }
+    }
+  } else {
+    for (int c = lane; c < d; c += 64) {
+      const float t = rvq_load_in<DT>(X, base + c) - mean;
+      ss = fmaf(t, t, ss);
+    }
+  }
+  ss = rvq_wave_sum(ss);
+  float sd = sqrtf(ss / (float)(d - ddof));
+  if (!(sd >= 1e-30f)) sd = 1.0f;
+  return sd;
+}
+// whether rows can be read in 16-byte pieces (host)
+inline bool rvq_rows_vectorizable(const void *dX, int64_t ldx, int d, int in_dtype) {
+  const int esz = in_dtype == RVQ_F32 ? 4 : 2;
+  return (reinterpret_cast<uintptr_t>(dX) % 16) == 0 && (ldx * esz) % 16 == 0 && (d * esz) % 16 == 0;
+}
+
 // ---- kernel launchers (each returns a hipError_t from the launch) -----------------------------
 hipError_t rvq_launch_prepare_codebook(const rvq_ctx *ctx, int stage_begin, int stage_end,
                                        hipStream_t s);
@@ -112,9 +185,10 @@ hipError_t rvq_launch_encode_exact(const rvq_ctx *ctx, const void *dX, int64_t N
 // dhat == 32 and at most RVQ_SMALL_MAX_VECTORS group vectors: the codes of the exact kernel, with
 // the codebook of a stage split over the threads of a workgroup (latency of a few rows)
 constexpr int64_t RVQ_SMALL_MAX_VECTORS = 4096;
+// (computes the rows' std itself when cfg.scale is set and writes it to dStd; no row_std launch)
 hipError_t rvq_launch_encode_small(const rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx,
                                    int stage_begin, int stage_end, int16_t *dCodes,
-                                   float *dResidual, const float *std32, hipStream_t s);
+                                   float *dResidual, void *dStd, hipStream_t s);
 hipError_t rvq_launch_encode_screen(const rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx,
                                     int stage_begin, int stage_end, int16_t *dCodes,
                                     float *dResidual, const float *std32, hipStream_t s);
