@@ -125,7 +125,7 @@ __device__ __forceinline__ uint32_t sm_wave_min(uint32_t v) {
   return min(min(r0, r1), min(r2, r3));
 }
 
-// VPW: vectors per workgroup.  LPC: lanes that share a codeword (8, 4, 2 or 1), each with
+// VPW: vectors per workgroup.  LPC: lanes that share a codeword (8, 4 or 2), each with
 // 32 / LPC channels.  The partial sums meet in the same tree whatever LPC is (inside the lane
 // first, then by lane exchanges), so every instantiation returns the same bits.
 template <int VPW, int LPC>
@@ -159,17 +159,18 @@ __global__ __launch_bounds__(SM_THREADS) void encode_small_kernel(
   // row + lane / LPC
   f32x4 c4[SM_LOADS];
   const int lane_row = wave * SM_WAVE_ROWS + lane / LPC;
-  auto fetch = [&](int stage, int k0) {
+  auto fetch_slot = [&](int stage, int k0, int j) {
     // a scalar base and 32-bit byte offsets (a stage is at most 32768 rows of 128 bytes)
     const char *__restrict__ Ci = reinterpret_cast<const char *>(C + (int64_t)stage * K * DH);
+    const int k = min(k0 + lane_row + RSTEP * j, K - 1);  // past the end: fetched, not scored
 #pragma unroll
-    for (int j = 0; j < RPL; ++j) {
-      const int k = min(k0 + lane_row + RSTEP * j, K - 1);  // past the end: fetched, not scored
+    for (int t = 0; t < NQ; ++t)
+      c4[j * NQ + t] =
+          *reinterpret_cast<const f32x4 *>(Ci + ((uint32_t)k * 128u + (uint32_t)(piece + t) * 16u));
+  };
+  auto fetch = [&](int stage, int k0) {
 #pragma unroll
-      for (int t = 0; t < NQ; ++t)
-        c4[j * NQ + t] =
-            *reinterpret_cast<const f32x4 *>(Ci + ((uint32_t)k * 128u + (uint32_t)(piece + t) * 16u));
-    }
+    for (int j = 0; j < RPL; ++j) fetch_slot(stage, k0, j);
   };
   // requested first: the loads below come back behind these, which stage 0 needs anyway
   fetch(stage_begin, 0);
@@ -211,8 +212,20 @@ __global__ __launch_bounds__(SM_THREADS) void encode_small_kernel(
   __syncthreads();
   for (int i = stage_begin; i < stage_end; ++i) {
     for (int k0 = 0; k0 < K; k0 += SM_PASS) {
+      // What the registers hold next: the next pass of this stage, or the next stage's first
+      // pass.  Each codeword slot is requested as soon as the last vector has been scored
+      // against it, so the requests run under the scoring and the reduction; the winner's row,
+      // requested after them, comes back behind them (a wavefront's loads return in order), by
+      // which time the next pass can start at once.
+      // (With a codeword per lane, LPC == 1, the two slots of 32 registers each make the
+      // compiler spill 91 values: that layout is not instantiated.)
+      static_assert(LPC >= 2, "requests are interleaved with the scoring slot by slot");
+      const bool more = k0 + SM_PASS < K;
+      const bool have_next = more || i + 1 < stage_end;
+      const int nstage = more ? i : i + 1, nk0 = more ? k0 + SM_PASS : 0;
 #pragma unroll 1  // one vector at a time
       for (int u = 0; u < VPW; ++u) {
+        const bool last_u = VPW == 1 || u == VPW - 1;
         f32x4 r4[NQ];
 #pragma unroll
         for (int t = 0; t < NQ; ++t) r4[t] = reinterpret_cast<const f32x4 *>(&rs[u][0])[piece + t];
@@ -246,6 +259,7 @@ __global__ __launch_bounds__(SM_THREADS) void encode_small_kernel(
             bits = db;
             idx = (uint32_t)k;
           }
+          if (last_u && have_next) fetch_slot(nstage, nk0, l);
         }
         const uint32_t m = sm_wave_min(bits);
         const uint32_t a = sm_wave_min(bits == m ? idx : 0xffffffffu);  // smallest index among equals
@@ -258,8 +272,6 @@ __global__ __launch_bounds__(SM_THREADS) void encode_small_kernel(
           wave_best[u][wave] = key;
         }
       }
-      // registers are free again: the next pass's codewords
-      if (k0 + SM_PASS < K) fetch(i, k0 + SM_PASS);
     }
     __syncthreads();
     int arg = 0;
@@ -274,9 +286,6 @@ __global__ __launch_bounds__(SM_THREADS) void encode_small_kernel(
       arg = (int)(uint32_t)(b & 0xffffffffull);
       won = C[((int64_t)i * K + arg) * DH + ej];
     }
-    // the next stage's first codewords go out behind the winner's element: a wavefront's loads
-    // come back in the order they were issued, so the update below waits for its own load only
-    if (i + 1 < stage_end) fetch(i + 1, 0);
     if (elem) {
       rs[eu][ej] -= won;
       if (ej == 0 && v0 + eu < V) codes[(v0 + eu) * depth + i] = (int16_t)arg;
@@ -304,15 +313,15 @@ hipError_t rvq_launch_encode_small(const rvq_ctx *ctx, const void *dX, int64_t N
   hipLaunchKernelGGL((encode_small_kernel<VPW, LPC>), grid, block, 0, s, dX, c.in_dtype, N, ldx, \
                      ctx->G, c.grouping, c.scale, c.std_ddof, vec_rows, dStd, c.std_dtype,       \
                      ctx->C, c.K, c.depth, stage_begin, stage_end, dCodes, dResidual)
-  // lanes per codeword, measured: four while a workgroup has up to four vectors (the loads of a
-  // wavefront instruction then cover whole lines in pairs, and two of the three tree levels
-  // between lanes remain), fewer as the arithmetic per fetched codeword grows
+  // lanes per codeword, measured: four while a workgroup has up to four vectors (a wavefront's
+  // load instruction then covers sixteen rows half a line at a time, and two of the three tree
+  // levels between lanes remain), two when there is more arithmetic per fetched codeword
   switch (vpw) {
     case 1: RVQ_LAUNCH_SMALL(1, 4); break;
     case 2: RVQ_LAUNCH_SMALL(2, 4); break;
     case 4: RVQ_LAUNCH_SMALL(4, 4); break;
     case 8: RVQ_LAUNCH_SMALL(8, 2); break;
-    default: RVQ_LAUNCH_SMALL(16, 1); break;
+    default: RVQ_LAUNCH_SMALL(16, 2); break;
   }
 #undef RVQ_LAUNCH_SMALL
   return hipGetLastError();

@@ -227,7 +227,7 @@ def test_encode_small_and_ragged(gpu_device, case):
     (9, 1024, 8, 2048, oracle.STRIDED, "fp32", 1),      # 288: two per workgroup, four lanes a codeword
     (30, 1024, 8, 2048, oracle.CONTIGUOUS, "fp16", 1),  # 960: four per workgroup
     (33, 1024, 8, 2048, oracle.STRIDED, "bf16", 1),     # 1056: eight per workgroup, two lanes a codeword
-    (100, 1024, 8, 2048, oracle.STRIDED, "bf16", 1),    # 3200: sixteen per workgroup, a codeword a lane
+    (100, 1024, 8, 2048, oracle.STRIDED, "bf16", 1),    # 3200: sixteen per workgroup
     (128, 1024, 8, 2048, oracle.CONTIGUOUS, "bf16", 1),  # the most the kernel takes
     (61, 128, 3, 100, oracle.STRIDED, "fp32", 1),       # a codebook that ends inside a load
     (50, 96, 5, 1, oracle.CONTIGUOUS, "fp16", 1),       # one codeword
