@@ -389,13 +389,20 @@ __global__ __launch_bounds__(ATT_HD) void attn_merge_kernel(const float *__restr
 
 }  // namespace
 
-// splits of a cache of N tokens over Hkv kv heads: enough workgroups to fill the chip, at least
-// 128 tokens each; the same rule sizes the workspace
+// splits of a cache of N tokens over Hkv kv heads; the same rule sizes the workspace.  A long
+// cache: enough workgroups to fill the chip several times, at least 128 tokens each.  A short
+// one is a matter of latency (a wavefront's trips are a chain of dependent loads): splits down to
+// 32 tokens, four trips of a workgroup, as long as that makes no more than 512 workgroups
+// (measured: 2048 tokens x 8 heads 32 -> 19 us; with 2048 workgroups of 32 tokens at 8192 tokens
+// 43 -> 57 us, so not beyond 512).
 static int attn_splits(int64_t N, int Hkv) {
-  int64_t s = (N + 127) / 128;
-  int64_t cap = 2048 / (Hkv > 0 ? Hkv : 1);
+  const int h = Hkv > 0 ? Hkv : 1;
+  int64_t lng = (N + 127) / 128, cap = 2048 / h;
   if (cap < 1) cap = 1;
-  if (s > cap) s = cap;
+  if (lng > cap) lng = cap;
+  int64_t shrt = (N + 31) / 32, cap_s = 512 / h;
+  if (shrt > cap_s) shrt = cap_s;
+  int64_t s = lng > shrt ? lng : shrt;
   if (s < 1) s = 1;
   return (int)s;
 }
