@@ -146,43 +146,86 @@ __device__ __forceinline__ float dot8(const uint4 w, const half8 b, float acc) {
 #define PHASE_MARK(i) do { } while (0)
 #endif
 
+// minimum of an unsigned value over the 64 lanes (lane moves inside rows of 16, then the four
+// rows through scalar registers); the same value in every lane
+template <int CTRL>
+__device__ __forceinline__ uint32_t scr_dpp(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xf, 0xf, false);
+}
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+  v = min(v, scr_dpp<0xB1>(v));   // quad_perm [1,0,3,2]
+  v = min(v, scr_dpp<0x4E>(v));   // quad_perm [2,3,0,1]
+  v = min(v, scr_dpp<0x124>(v));  // row_ror 4
+  v = min(v, scr_dpp<0x128>(v));  // row_ror 8
+  const uint32_t r0 = (uint32_t)__builtin_amdgcn_readlane((int)v, 0);
+  const uint32_t r1 = (uint32_t)__builtin_amdgcn_readlane((int)v, 16);
+  const uint32_t r2 = (uint32_t)__builtin_amdgcn_readlane((int)v, 32);
+  const uint32_t r3 = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+  return min(min(r0, r1), min(r2, r3));
+}
+// nearest of the lanes' (distance >= +0 or +inf, index) pairs, ties to the smallest index;
+// 0x7fffffff when no lane has a finite distance
+__device__ __forceinline__ int wave_nearest(float bd, int bk) {
+  const uint32_t bits = __float_as_uint(bd);
+  const uint32_t m = wave_min_u32(bits);
+  const uint32_t k = wave_min_u32(bits == m ? (uint32_t)bk : 0x7fffffffu);
+  return m >= 0x7f800000u ? 0x7fffffff : (int)k;
+}
+
 // Exact nearest codeword of one vector among the K codewords of a stage, by the whole wavefront
-// (every lane passes the same vector; two codewords per lane in flight; ties to the smallest
-// index).  Kept out of line: it is needed for 0.02 % of the searches, and inlined its 100
-// registers of rows would be made room for on the common path.
+// (every lane passes the same vector; ties to the smallest index).  Four lanes share a codeword,
+// eight channels each: a load instruction of the wavefront then covers sixteen rows half a line
+// at a time (with a row per lane it touched 64 lines, and the address path made a scan of 2048
+// rows take 35 us), and the rows of the next pass are requested slot by slot as soon as this
+// pass has used the registers.  The four partial sums of (r - c)^2 meet by two lane exchanges.
+// Kept out of line: it is needed for 0.02 % of the searches of the benchmark (1 % with codebooks
+// crowded into tight clusters), and inlined its registers would be made room for on the common
+// path.
 __device__ __noinline__ int exact_scan(const float *__restrict__ Cs, int K, const float *vec, int lane) {
-  float rr32[32];
+  constexpr int SLOTS = 8;                 // codewords per lane and pass
+  constexpr int PASS = 16 * SLOTS;         // codewords per pass of the wavefront (128)
+  const int piece = (lane & 3) * 2;        // this lane's two 16-byte pieces of a codeword
+  const int row = lane >> 2;
+  f32x4 rv[2];
 #pragma unroll
-  for (int j = 0; j < 32; ++j) rr32[j] = vec[j];
+  for (int t = 0; t < 2; ++t)
+    rv[t] = f32x4{vec[(piece + t) * 4], vec[(piece + t) * 4 + 1], vec[(piece + t) * 4 + 2],
+                  vec[(piece + t) * 4 + 3]};
+  f32x4 cw[SLOTS][2];
+  auto fetch_slot = [&](int k0, int j) {
+    const int k = min(k0 + row + 16 * j, K - 1);  // past the end: fetched, not scored
+    const char *base = reinterpret_cast<const char *>(Cs);
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+      cw[j][t] = *reinterpret_cast<const f32x4 *>(base + ((uint32_t)k * 128u + (uint32_t)(piece + t) * 16u));
+  };
+#pragma unroll
+  for (int j = 0; j < SLOTS; ++j) fetch_slot(0, j);
   float bd = INFINITY;
   int bk = 0x7fffffff;
-  for (int k0 = lane; k0 < K; k0 += 128) {
-    f32x4 cw[2][8];
+  for (int k0 = 0; k0 < K; k0 += PASS) {
+    const bool more = k0 + PASS < K;
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int k = min(k0 + 64 * q, K - 1);
-      const f32x4 *crow = reinterpret_cast<const f32x4 *>(Cs + (int64_t)k * 32);
+    for (int j = 0; j < SLOTS; ++j) {
+      float p[2];
 #pragma unroll
-      for (int c4 = 0; c4 < 8; ++c4) cw[q][c4] = crow[c4];
-    }
+      for (int t = 0; t < 2; ++t) {
+        p[t] = 0.f;
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int k = k0 + 64 * q;
-      float dist = 0.f;
-#pragma unroll
-      for (int j = 0; j < 32; ++j) {
-        const float dlt = rr32[j] - cw[q][j >> 2][j & 3];
-        dist = fmaf(dlt, dlt, dist);
+        for (int e = 0; e < 4; ++e) {
+          const float dlt = rv[t][e] - cw[j][t][e];
+          p[t] = fmaf(dlt, dlt, p[t]);
+        }
       }
-      if (k < K && dist < bd) { bd = dist; bk = k; }
+      float dist = p[0] + p[1];
+      dist += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(dist), 0xB1, 0xf, 0xf, false));
+      dist += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(dist), 0x4E, 0xf, 0xf, false));
+      const int k = k0 + row + 16 * j;
+      if (k < K && dist < bd) { bd = dist; bk = k; }  // a lane's later rows have larger indices
+      if (more) fetch_slot(k0 + PASS, j);
     }
   }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const float od = __shfl_xor(bd, o, 64);
-    const int ok = __shfl_xor(bk, o, 64);
-    if (od < bd || (od == bd && ok < bk)) { bd = od; bk = ok; }
-  }
+  bk = wave_nearest(bd, bk);
   return bk == 0x7fffffff ? 0 : bk;
 }
 
@@ -857,10 +900,13 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
                 ovm &= ovm - 1;
                 n_over += 1;
                 const int gi = lane >> 4, rw = lane & 15;  // lane -> (group of the window, row)
-                const float ge0 = __shfl(w.e0, src, 64), ge1 = __shfl(w.e1, src, 64);
-                const float ge2 = __shfl(w.e2, src, 64), ge3 = __shfl(w.e3, src, 64);
-                const unsigned gpend = (unsigned)__shfl((int)w.pend, src, 64);
-                const int gaf = __shfl((int)w.afirst, src, 64);
+                // (src is the same in every lane: the values come through scalar registers)
+                auto bcast = [&](float x) {
+                  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), src));
+                };
+                const float ge0 = bcast(w.e0), ge1 = bcast(w.e1), ge2 = bcast(w.e2), ge3 = bcast(w.e3);
+                const unsigned gpend = (unsigned)__builtin_amdgcn_readlane((int)w.pend, src);
+                const int gaf = __builtin_amdgcn_readlane((int)w.afirst, src);
                 const float gval = gi == 0 ? ge0 : (gi == 1 ? ge1 : (gi == 2 ? ge2 : ge3));
                 const int ghh = (gaf ? gi : gi + 1) & 1;
                 const int gtl = tile_of(gval);
@@ -886,14 +932,8 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
                   }
                 }
                 static_assert(SCR_DT == 2, "the double tile is picked with one select");
-                float bd = gvalid ? dist : INFINITY;
-                int bk = gvalid ? (int)gk : 0x7fffffff;
-#pragma unroll
-                for (int o = 32; o > 0; o >>= 1) {  // nearest over the wavefront, ties to the smallest index
-                  const float od = __shfl_xor(bd, o, 64);
-                  const int ok2 = __shfl_xor(bk, o, 64);
-                  if (od < bd || (od == bd && ok2 < bk)) { bd = od; bk = ok2; }
-                }
+                // nearest over the wavefront, ties to the smallest index
+                const int bk = wave_nearest(gvalid ? dist : INFINITY, gvalid ? (int)gk : 0x7fffffff);
                 // bk == 0x7fffffff cannot happen for a token with candidates; it would leave the
                 // token without one and send it to the wavefront search below
                 if (lane == src) {
