@@ -33,7 +33,7 @@ PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 # `--profile decode`, scaled by the readings of a plain 1 GiB copy: FETCH_SIZE counts 2 KiB units,
 # WRITE_SIZE 1 KiB units (the readings are in profiles/rvq_encode_workload2.txt and
 # profiles/rvq_decode_workload3_slice.txt)
-TRAFFIC_ENCODE_W2 = 9.6073e4 * 2048 + 1.1745e5 * 1024            # encode_screen_kernel, workload 2
+TRAFFIC_ENCODE_W2 = 1.1563e5 * 2048 + 1.2123e5 * 1024            # encode_screen_kernel, workload 2
 TRAFFIC_DECODE_SLICE = 0.5 * ((1.4005e5 + 1.4058e5) * 2048) + 1.0486e6 * 1024  # mean of both kernels
 
 W2 = dict(N=32768, d=1024, dhat=32, depth=8, K=2048)
