@@ -143,7 +143,8 @@ int rvq_encode(rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx, int32_t sta
  * RVQ_EWORKSPACE and nothing is enqueued.  All contexts on one GPU share that array: calls that
  * may overlap on one GPU (two streams, or two contexts) race on it and must be ordered by the
  * caller.  The array needs no clearing between calls: every entry a call reads it has written
- * itself.
+ * itself.  (Calls of at most 4096 group vectors with dhat == 32 and RVQ_PATH_AUTO take the
+ * latency kernel, which keeps the std inside the kernel and does not touch the array.)
  */
 int rvq_encode_static(rvq_ctx *ctx, const void *dX, int64_t N, int64_t ldx, int32_t stage_begin,
                       int32_t stage_end, int16_t *dCodes, void *dStd, float *dResidual,
