@@ -320,6 +320,37 @@ __device__ __noinline__ int exact_scan(const float *__restrict__ Cs, int K, cons
     Agp = Agc;                                                                                  \
   }
 
+// The same for two token tiles (one token per lane): set A is tile 0, set B tile 1.
+//   MFMA      A(0) a0   A(0) a1   B(1) a0   B(1) a1
+//   reduce    -         B(1)' R1  B(1)' R2  A(0) R1, then A(0) R2
+#define SWEEP_TILE_H(A0, A1, N0, N1, t_)                                                        \
+  {                                                                                             \
+    const unsigned tid_p = (unsigned)(tile0 + max((t_) - 1, 0)), tid_c = (unsigned)(tile0 + (t_)); \
+    const float Agc = Ag;                                                                       \
+    const int tn = min((t_) + 1, ntiles - 1);                                                   \
+    SWEEP_FENCE();                                                                              \
+    accA = __builtin_amdgcn_mfma_f32_32x32x16_f16(A0, B0[0], cn, 0, 0, 0);                      \
+    SWEEP_FENCE();                                                                              \
+    SWEEP_LOAD_A(N0, N1, tn)                                                                    \
+    SWEEP_FENCE();                                                                              \
+    accA = __builtin_amdgcn_mfma_f32_32x32x16_f16(A1, B1[0], accA, 0, 0, 0);                    \
+    SWEEP_FENCE();                                                                              \
+    SWEEP_R1(accB, u1)                                                                          \
+    SWEEP_FENCE();                                                                              \
+    accB = __builtin_amdgcn_mfma_f32_32x32x16_f16(A0, B0[1], cn, 0, 0, 0);                      \
+    SWEEP_FENCE();                                                                              \
+    /* the norms were last used by the instruction above: fetch the next tile's in place */     \
+    SWEEP_LOAD_N(tn)                                                                            \
+    SWEEP_R2(u1, 1, tid_p, Agp)                                                                 \
+    SWEEP_FENCE();                                                                              \
+    accB = __builtin_amdgcn_mfma_f32_32x32x16_f16(A1, B1[1], accB, 0, 0, 0);                    \
+    SWEEP_FENCE();                                                                              \
+    SWEEP_R1(accA, u0)                                                                          \
+    SWEEP_R2(u0, 0, tid_c, Agc)                                                                 \
+    SWEEP_FENCE();                                                                              \
+    Agp = Agc;                                                                                  \
+  }
+
 // trade the upper half (lanes 32..63) of a for the lower half (lanes 0..31) of b
 __device__ __forceinline__ void swap_halves(unsigned &a, unsigned &b) {
   const auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
@@ -340,8 +371,13 @@ constexpr int SCR_DT = 2;          // double tiles (64 tokens, one per lane) per
 constexpr int SCR_WTOK = 64 * SCR_DT;  // tokens per wavefront
 
 // SC: the (padded) codebook fits the LDS copy whole; otherwise it is swept in pieces of SCR_KC
-template <int DT, bool SC>
+// HALF: every lane owns one token instead of two (chunks of 512 vectors).  A stage then takes
+// about 0.6 of the time and a call with fewer chunks than CUs spreads over twice as many of them:
+// the instantiation for calls between the few rows of encode_small_kernel and a full chip.
+template <int DT, bool SC, bool HALF = false>
 __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const ScreenArgs a) {
+  constexpr int NDT = HALF ? 1 : SCR_DT;            // double tiles (tokens per lane) in use
+  constexpr int CHUNK = SCR_WAVES * 64 * NDT;       // group vectors per workgroup and chunk
 #ifdef RVQ_PHASE_CLOCKS
   long long phase_acc[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
   long long phase_t = RVQ_PHASE_CLOCK_FN();
@@ -369,7 +405,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
   // A workgroup walks the chunks of SCR_TOKENS vectors blockIdx.x, blockIdx.x + gridDim.x, ...;
   // vbase is the first vector of this wavefront in the chunk it is working on (the two teams may
   // be in different chunks for a while).
-  const int64_t nchunks_all = (a.V + SCR_TOKENS - 1) / SCR_TOKENS;
+  const int64_t nchunks_all = (a.V + CHUNK - 1) / CHUNK;
   const int nmy = (int)((nchunks_all - blockIdx.x + gridDim.x - 1) / gridDim.x);  // chunks of this workgroup
   int64_t vbase = 0;
   const int wtok = wave * SCR_WTOK;  // first token slot of this wavefront in the workgroup
@@ -379,9 +415,9 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
   // ---- the 32 channels of this lane's two tokens, scaled by the row std (Section 2.2)
   float r[SCR_DT][32];
   auto load_chunk = [&](int64_t chunk) {
-    vbase = chunk * SCR_TOKENS + wtok;
+    vbase = chunk * CHUNK + wave * (64 * NDT);
 #pragma unroll
-    for (int k = 0; k < SCR_DT; ++k) {
+    for (int k = 0; k < NDT; ++k) {
       // no branch around the loads, so that all 32 of a token are in flight together: a vector
       // beyond the end reads the last vector (V >= 1) and is set to zero afterwards
       const int64_t v = vbase + k * 64 + lane;
@@ -434,7 +470,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
   auto store_chunk = [&]() {
     if (a.residual) {
 #pragma unroll
-      for (int k = 0; k < SCR_DT; ++k) {
+      for (int k = 0; k < NDT; ++k) {
         const int64_t v = vbase + k * 64 + lane;
         if (v < a.V) {
           f32x4 *dst = reinterpret_cast<f32x4 *>(a.residual + v * 32);
@@ -513,7 +549,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
     const float Tscale = a.stats[stage * 8 + 4];  // power of two applied to the residuals
     const float tiny = 6.103515625e-5f / Tscale;  // below this the scaled value is no normal half
 #pragma unroll
-    for (int k = 0; k < SCR_DT; ++k) {
+    for (int k = 0; k < NDT; ++k) {
       bestd[k] = INFINITY;
       bestk[k] = 0;
       done[k] = 0;
@@ -558,12 +594,12 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
     for (int slot = 0; slot < SCR_CAND; ++slot) {
       bool need = false;
 #pragma unroll
-      for (int k = 0; k < SCR_DT; ++k) need = need || (nc[k] > slot && !slow[k]);
+      for (int k = 0; k < NDT; ++k) need = need || (nc[k] > slot && !slow[k]);
       if (!__any(need)) break;
       f32x4 cw[SCR_DT][8];
       int kk[SCR_DT];
 #pragma unroll
-      for (int k = 0; k < SCR_DT; ++k) {
+      for (int k = 0; k < NDT; ++k) {
         const int cand = lds_c[(wtok + k * 64 + lane) * SCR_CAND + slot];
         kk[k] = (nc[k] > slot && cand < a.K) ? cand : 0;
         const f32x4 *crow = reinterpret_cast<const f32x4 *>(a.C32 + ((int64_t)stage * a.K + kk[k]) * 32);
@@ -571,7 +607,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
         for (int c4 = 0; c4 < 8; ++c4) cw[k][c4] = crow[c4];
       }
 #pragma unroll
-      for (int k = 0; k < SCR_DT; ++k) {
+      for (int k = 0; k < NDT; ++k) {
         const bool valid = nc[k] > slot && !slow[k];
         const bool commit = single_chunk && slot == 0 && valid && nc[k] == 1;
         const float sel = commit ? 1.0f : 0.0f;
@@ -599,7 +635,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
     for (int j = 0; j < 32; ++j) {
       float rj = r[0][j];
 #pragma unroll
-      for (int k2 = 1; k2 < SCR_DT; ++k2) rj = k == k2 ? r[k2][j] : rj;
+      for (int k2 = 1; k2 < NDT; ++k2) rj = k == k2 ? r[k2][j] : rj;
       vec[j] = __shfl(rj, src, 64);
     }
   };
@@ -627,13 +663,44 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
 #pragma unroll
       for (int tt = 0; tt < SCR_TT; ++tt) m1[tt] = m2[tt] = m3[tt] = BIG;
       const int tile0 = cbase >> 5;
-      {
+      if constexpr (HALF) {
+        // two token tiles (the halves of the one double tile): accumulator set A holds tile 0,
+        // B tile 1, and a set is reduced two matrix instructions after it has been finished
+        half8 B0[2], B1[2];
+        float g1t[2];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) swap_halves(Bw[0][j], Bw[0][8 + j]);
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          B0[e] = __builtin_bit_cast(
+              half8, make_uint4(Bw[0][8 * e + 0], Bw[0][8 * e + 1], Bw[0][8 * e + 2], Bw[0][8 * e + 3]));
+          B1[e] = __builtin_bit_cast(
+              half8, make_uint4(Bw[0][8 * e + 4], Bw[0][8 * e + 5], Bw[0][8 * e + 6], Bw[0][8 * e + 7]));
+        }
+        halves32f(g1[0], g1t[0], g1t[1]);
+        f32x16 accA, accB, cn;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) { accA[e] = BIG; accB[e] = BIG; }
+        float Agp = 0.f;  // group bound of the previous tile
+        float Ag;
+        half8 ax0, ax1, ay0, ay1;
+        SWEEP_LOAD_A(ax0, ax1, 0)
+        SWEEP_LOAD_N(0)
+        for (int t = 0; t < ntiles; t += 2) {  // the tile count of a chunk is even
+          SWEEP_TILE_H(ax0, ax1, ay0, ay1, t)
+          SWEEP_TILE_H(ay0, ay1, ax0, ax1, t + 1)
+        }
+        const unsigned tid_l = (unsigned)(tile0 + ntiles - 1);
+        { SWEEP_R1(accB, u1) SWEEP_R2(u1, 1, tid_l, Agp) }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) swap_halves(Bw[0][j], Bw[0][8 + j]);
+      } else {
         static_assert(SCR_TT == 4 && SCR_DT == 2, "the sweep pipeline is written for four token tiles");
         // the matrix-core arrangement of the fp16 residuals and of the tokens' bound terms
         half8 B0[SCR_TT], B1[SCR_TT];
         float g1t[SCR_TT];
 #pragma unroll
-        for (int k = 0; k < SCR_DT; ++k) {
+        for (int k = 0; k < NDT; ++k) {
 #pragma unroll
           for (int j = 0; j < 8; ++j) swap_halves(Bw[k][j], Bw[k][8 + j]);
 #pragma unroll
@@ -663,7 +730,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
         { SWEEP_R1(accB, u3) SWEEP_R2(u3, 3, tid_l, Agp) }
         // back to the owner's arrangement
 #pragma unroll
-        for (int k = 0; k < SCR_DT; ++k)
+        for (int k = 0; k < NDT; ++k)
 #pragma unroll
           for (int j = 0; j < 8; ++j) swap_halves(Bw[k][j], Bw[k][8 + j]);
       }
@@ -671,7 +738,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
       // lower bounds among the groups of tile rows with lane half 0, tb = those of lane half 1
       float ta[SCR_DT][3], tb[SCR_DT][3];
 #pragma unroll
-      for (int k = 0; k < SCR_DT; ++k) {
+      for (int k = 0; k < NDT; ++k) {
         ta[k][0] = m1[2 * k]; tb[k][0] = m1[2 * k + 1];
         ta[k][1] = m2[2 * k]; tb[k][1] = m2[2 * k + 1];
         ta[k][2] = m3[2 * k]; tb[k][2] = m3[2 * k + 1];
@@ -771,7 +838,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
       // instead of one extra pass per double tile.
       int qn = 0;  // queue entries of this wavefront (wave-uniform)
 #pragma unroll
-      for (int k = 0; k < SCR_DT; ++k) {
+      for (int k = 0; k < NDT; ++k) {
         const int tok = k * 64 + lane;
         const Window w = window(k);
         {
@@ -823,7 +890,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
       // the owners publish their counts first and read them back after.
       if (qn > 0) {
 #pragma unroll
-        for (int k = 0; k < SCR_DT; ++k)
+        for (int k = 0; k < NDT; ++k)
           reinterpret_cast<uint16_t *>(lds_cnt)[wtok + k * 64 + lane] = (uint16_t)nc[k];
         __builtin_amdgcn_wave_barrier();
         const int rq = lane & 15;  // accumulator position 4 b + i of this lane's row
@@ -870,7 +937,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
         }
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int k = 0; k < SCR_DT; ++k)
+        for (int k = 0; k < NDT; ++k)
           nc[k] = (int)reinterpret_cast<uint16_t *>(lds_cnt)[wtok + k * 64 + lane];
       }
 
@@ -882,18 +949,18 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
       {
         bool any_over = false;
 #pragma unroll
-        for (int k = 0; k < SCR_DT; ++k) any_over = any_over || (nc[k] > SCR_CAND && !slow[k]);
+        for (int k = 0; k < NDT; ++k) any_over = any_over || (nc[k] > SCR_CAND && !slow[k]);
         if (__any(any_over)) {
 #pragma unroll 1
-          for (int k = 0; k < SCR_DT; ++k) {
+          for (int k = 0; k < NDT; ++k) {
             int nck = nc[0], slowk = slow[0];
 #pragma unroll
-            for (int k2 = 1; k2 < SCR_DT; ++k2) { nck = k == k2 ? nc[k2] : nck; slowk = k == k2 ? slow[k2] : slowk; }
+            for (int k2 = 1; k2 < NDT; ++k2) { nck = k == k2 ? nc[k2] : nck; slowk = k == k2 ? slow[k2] : slowk; }
             unsigned long long ovm = __ballot(nck > SCR_CAND && !slowk);
             if (ovm) {
               Window w = window(0);
 #pragma unroll
-              for (int k2 = 1; k2 < SCR_DT; ++k2)
+              for (int k2 = 1; k2 < NDT; ++k2)
                 if (k == k2) w = window(k2);
               while (ovm) {
                 const int src = __ffsll((long long)ovm) - 1;
@@ -939,7 +1006,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
                 if (lane == src) {
                   lds_c[(wtok + k * 64 + src) * SCR_CAND] = (uint16_t)(bk == 0x7fffffff ? 0 : bk);
 #pragma unroll
-                  for (int k2 = 0; k2 < SCR_DT; ++k2)
+                  for (int k2 = 0; k2 < NDT; ++k2)
                     if (k == k2) nc[k2] = bk == 0x7fffffff ? 0 : 1;
                 }
               }
@@ -952,7 +1019,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
       if (!single_chunk) {
         exact_candidates(stage);
 #pragma unroll
-        for (int k = 0; k < SCR_DT; ++k) nc[k] = 0;  // new lists per chunk of the codebook
+        for (int k = 0; k < NDT; ++k) nc[k] = 0;  // new lists per chunk of the codebook
       }
     }
   };
@@ -966,18 +1033,18 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
     {
       bool any_slow = false;
 #pragma unroll
-      for (int k = 0; k < SCR_DT; ++k) {
+      for (int k = 0; k < NDT; ++k) {
         if (!(bestd[k] < INFINITY)) slow[k] = 1;  // no candidate in any chunk
         any_slow = any_slow || slow[k];
       }
       if (__any(any_slow)) {  // seldom: 0.02 % of the searches
 #pragma unroll 1
-        for (int k = 0; k < SCR_DT; ++k) {
+        for (int k = 0; k < NDT; ++k) {
           // double tile k is picked with selects, so that the common path never moves the
           // register arrays around
           int slow_k = slow[0];
 #pragma unroll
-          for (int k2 = 1; k2 < SCR_DT; ++k2) slow_k = k == k2 ? slow[k2] : slow_k;
+          for (int k2 = 1; k2 < NDT; ++k2) slow_k = k == k2 ? slow[k2] : slow_k;
           unsigned long long pending = __ballot(slow_k != 0);
           n_slow += __popcll(pending);
           while (pending) {
@@ -987,19 +1054,19 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
             broadcast_token(k, src, rr32);
             const int bk = exact_scan(a.C32 + (int64_t)stage * a.K * 32, a.K, rr32, lane);
 #pragma unroll
-            for (int k2 = 0; k2 < SCR_DT; ++k2) bestk[k2] = (lane == src && k == k2) ? bk : bestk[k2];
+            for (int k2 = 0; k2 < NDT; ++k2) bestk[k2] = (lane == src && k == k2) ? bk : bestk[k2];
           }
         }
       }
     }
-    n_search += SCR_WTOK;
+    n_search += 64 * NDT;
 
     // ---- emit the code and subtract the fp32 codeword from the residual (Algorithm 1) where
     // that has not happened yet (the tokens with several candidates and those searched exactly)
     {
       int kq[SCR_DT];
 #pragma unroll
-      for (int k = 0; k < SCR_DT; ++k) {
+      for (int k = 0; k < NDT; ++k) {
         const int64_t v = vbase + k * 64 + lane;
         int kk = bestk[k];
         kk = kk < 0 ? 0 : (kk >= a.K ? a.K - 1 : kk);
@@ -1008,11 +1075,11 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
       }
       bool any_left = false;
 #pragma unroll
-      for (int k = 0; k < SCR_DT; ++k) any_left = any_left || !done[k];
+      for (int k = 0; k < NDT; ++k) any_left = any_left || !done[k];
       if (__any(any_left)) {
         f32x4 cw[SCR_DT][8];
 #pragma unroll
-        for (int k = 0; k < SCR_DT; ++k) {
+        for (int k = 0; k < NDT; ++k) {
           // row 0 stands in for the tokens that are done: one line for all of their lanes
           const f32x4 *crow = reinterpret_cast<const f32x4 *>(
               a.C32 + ((int64_t)stage * a.K + (done[k] ? 0 : kq[k])) * 32);
@@ -1020,7 +1087,7 @@ __global__ __launch_bounds__(64 * SCR_WAVES) void encode_screen_kernel(const Scr
           for (int c4 = 0; c4 < 8; ++c4) cw[k][c4] = crow[c4];
         }
 #pragma unroll
-        for (int k = 0; k < SCR_DT; ++k) {
+        for (int k = 0; k < NDT; ++k) {
           const float sel = done[k] ? 0.0f : 1.0f;
 #pragma unroll
           for (int j = 0; j < 32; ++j) r[k][j] = fmaf(-sel, cw[k][j >> 2][j & 3], r[k][j]);
@@ -1173,17 +1240,28 @@ hipError_t rvq_launch_encode_screen(const rvq_ctx *ctx, const void *dX, int64_t 
   }
   a.wait_polls = ctx->wait_polls;
   // one workgroup fills a CU (LDS): as many workgroups as CUs, each walking its share of the chunks
-  const int64_t nchunks = (a.V + SCR_TOKENS - 1) / SCR_TOKENS;
+  // A call with so few vectors that chunks of 512 still leave no CU with a second one takes the
+  // instantiation with one token per lane (codebooks that fit LDS): twice the workgroups, each
+  // with stages of about 0.6 of the time.
+  const bool half = a.Kpad <= SCR_KC && (a.V + SCR_TOKENS / 2 - 1) / (SCR_TOKENS / 2) <= ctx->num_cus;
+  const int64_t chunk = half ? SCR_TOKENS / 2 : SCR_TOKENS;
+  const int64_t nchunks = (a.V + chunk - 1) / chunk;
   const int64_t grid64 = nchunks < ctx->num_cus ? nchunks : ctx->num_cus;
   if (grid64 < 1) return hipSuccess;
   const dim3 grid((unsigned)grid64), block(64 * SCR_WAVES);
   hipError_t e;
-#define RVQ_LAUNCH_SCREEN(DT, SC)                                                               \
-  e = hipFuncSetAttribute(reinterpret_cast<const void *>(&encode_screen_kernel<DT, SC>),        \
+#define RVQ_LAUNCH_SCREEN(DT, SC, ...)                                                          \
+  e = hipFuncSetAttribute(reinterpret_cast<const void *>(&encode_screen_kernel<DT, SC, ##__VA_ARGS__>), \
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)SCR_LDS_BYTES);      \
   if (e != hipSuccess) return e;                                                                \
-  hipLaunchKernelGGL((encode_screen_kernel<DT, SC>), grid, block, SCR_LDS_BYTES, s, a)
-  if (a.Kpad <= SCR_KC) {
+  hipLaunchKernelGGL((encode_screen_kernel<DT, SC, ##__VA_ARGS__>), grid, block, SCR_LDS_BYTES, s, a)
+  if (half) {
+    switch (c.in_dtype) {
+      case RVQ_F32: RVQ_LAUNCH_SCREEN(RVQ_F32, true, true); break;
+      case RVQ_BF16: RVQ_LAUNCH_SCREEN(RVQ_BF16, true, true); break;
+      default: RVQ_LAUNCH_SCREEN(RVQ_F16, true, true); break;
+    }
+  } else if (a.Kpad <= SCR_KC) {
     switch (c.in_dtype) {
       case RVQ_F32: RVQ_LAUNCH_SCREEN(RVQ_F32, true); break;
       case RVQ_BF16: RVQ_LAUNCH_SCREEN(RVQ_BF16, true); break;

@@ -283,6 +283,30 @@ def test_encode_few_rows_equals_the_exact_path(gpu_device, case):
         assert torch.equal(small[4], small[2])
 
 
+def test_encode_chunks_of_512_and_of_1024_agree(gpu_device):
+    """A call with at most 512 vectors per CU runs the matrix-core kernel with one token per lane
+    (chunks of 512), a larger one with two (chunks of 1024).  A token's codes do not depend on
+    who shares its workgroup: 4096 rows encoded alone (131072 vectors: the first form) and as the
+    head of 4100 rows (the second) must give the same codes, std and residuals bit for bit; the
+    oracle check of the shorter call is in the other tests of this file."""
+    torch, b = _torch(), _b()
+    N, d, depth, K = 4100, 1024, 8, 2048
+    Xb, _ = synth.llama_key(N, d)
+    C = _codebooks_from_samples(synth.widen(Xb[:512], "bf16"), 32, oracle.STRIDED, depth, K, seed=21)
+    q = b.Quantizer(d=d, dhat=32, depth=depth, K=K, grouping=b.STRIDED, in_dtype=b.BF16, std_dtype=b.F16,
+                    encode_path=b.PATH_SCREEN)
+    q.set_codebooks(torch.from_numpy(C).cuda())
+    dX = _to_dev(Xb, "bf16")
+    short = q.encode(dX[:4096], want_residual=True)
+    long_ = q.encode(dX, want_residual=True)
+    torch.cuda.synchronize()
+    assert b.rvq_check_kernels(q.ctx) == 0
+    for name, x, y in zip(("codes", "std", "residual"), short, long_):
+        assert torch.equal(x.view(torch.uint8), y[:4096].view(torch.uint8)), name
+    assert int(short[0].max()) > 0
+    q.close()
+
+
 def _stage0_residual(b, q, dX, N, d, G, depth):
     """Residuals after stage 0, in group order [N][G * 32], from a one-stage call."""
     torch = _torch()
