@@ -324,7 +324,8 @@ def run_workload5(args):
 
 def run_append(args):
     """What a serving loop does per generated token: encode the few rows that were appended
-    (1, 8, 64 rows of workload 2's shape) and decode a short cache (1024 and 8192 rows).  Times
+    (1, 8, 64 rows of workload 2's shape; 2048 rows for a prefill chunk) and decode a short cache
+    (1024 and 8192 rows).  Times
     per call in microseconds, stream time over 200 calls back to back (one kernel per encode of so
     few rows: std and search together)."""
     import numpy as np
@@ -360,7 +361,7 @@ def run_append(args):
         return a.elapsed_time(z) / reps * 1e3
 
     res = {}
-    for n in (1, 8, 64):
+    for n in (1, 8, 64, 2048):  # 2048: a prefill chunk (matrix-core kernel, one token per lane)
         res["encode_%d_rows_us" % n] = us(lambda: b.rvq_encode(q.ctx, dX, n, d, 0, depth, codes, std, None))
     for n in (1024, 8192):
         res["decode_%d_rows_us" % n] = us(lambda: b.rvq_decode(q.ctx, codes, std, n, depth, out, d))
