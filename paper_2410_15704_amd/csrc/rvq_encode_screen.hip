@@ -1240,10 +1240,16 @@ hipError_t rvq_launch_encode_screen(const rvq_ctx *ctx, const void *dX, int64_t 
   }
   a.wait_polls = ctx->wait_polls;
   // one workgroup fills a CU (LDS): as many workgroups as CUs, each walking its share of the chunks
-  // A call with so few vectors that chunks of 512 still leave no CU with a second one takes the
-  // instantiation with one token per lane (codebooks that fit LDS): twice the workgroups, each
-  // with stages of about 0.6 of the time.
-  const bool half = a.Kpad <= SCR_KC && (a.V + SCR_TOKENS / 2 - 1) / (SCR_TOKENS / 2) <= ctx->num_cus;
+  // Two tokens per lane (chunks of 1024) or one (chunks of 512; codebooks that fit LDS)?  A
+  // workgroup takes its chunks one after the other, and the call lasts as long as the workgroup
+  // with the most of them: measured, 350 us per chunk of 1024 and 190 us per chunk of 512.  The
+  // form with the shorter estimate runs: one token per lane for calls that leave CUs idle
+  // otherwise, and where it evens out a ragged last round (9000 rows of 32 groups: three rounds
+  // of 512 instead of two of 1024).
+  const int64_t cus = ctx->num_cus > 0 ? ctx->num_cus : 1;
+  const int64_t rounds_full = ((a.V + SCR_TOKENS - 1) / SCR_TOKENS + cus - 1) / cus;
+  const int64_t rounds_half = ((a.V + SCR_TOKENS / 2 - 1) / (SCR_TOKENS / 2) + cus - 1) / cus;
+  const bool half = a.Kpad <= SCR_KC && rounds_half * 19 < rounds_full * 35;
   const int64_t chunk = half ? SCR_TOKENS / 2 : SCR_TOKENS;
   const int64_t nchunks = (a.V + chunk - 1) / chunk;
   const int64_t grid64 = nchunks < ctx->num_cus ? nchunks : ctx->num_cus;
