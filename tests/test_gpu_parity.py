@@ -307,6 +307,52 @@ def test_encode_chunks_of_512_and_of_1024_agree(gpu_device):
     q.close()
 
 
+@pytest.mark.parametrize("V", [511, 513, 1023, 1025, 4097, 130561, 131071, 131073, 262145, 300000])
+def test_encode_chunk_boundaries_against_the_exact_path(gpu_device, V):
+    """Vector counts one off the chunk sizes of the matrix-core kernel (512 with one token per
+    lane, 1024 with two), off a full round of 256 workgroups, and a ragged count that takes three
+    rounds of 512: rows of one group (d = 32), so the row count is the vector count.  The codes
+    must equal the exact path's except for near-ties (first stage where they differ: the two
+    codewords' exact distances within 1e-5 of the residual's squared norm), and the last
+    vector, the one a partial chunk ends on, must be encoded."""
+    torch, b = _torch(), _b()
+    depth, K = 4, 256
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(V)
+    X = torch.randn((V, 32), device="cuda", generator=gen)
+    # (codewords that are no rows of X: a row that is its own codeword leaves a residual of exactly
+    # zero, and the next stage's choice is then a matter of the last bit of the codeword norms)
+    C = torch.stack([torch.randn((K, 32), device="cuda", generator=gen) * (0.7 ** i) for i in range(depth)])
+    got = {}
+    for path in (b.PATH_SCREEN, b.PATH_EXACT):
+        q = b.Quantizer(d=32, dhat=32, depth=depth, K=K, scale=0, encode_path=path)
+        q.set_codebooks(C.contiguous())
+        codes = torch.full((V, 1, depth), -1, dtype=torch.int16, device="cuda")
+        res = torch.zeros((V, 1, 32), dtype=torch.float32, device="cuda")
+        b.rvq_encode(q.ctx, X, V, 32, 0, depth, codes, None, res)
+        torch.cuda.synchronize()
+        assert b.rvq_check_kernels(q.ctx) == 0
+        got[path] = (codes[:, 0].long(), res[:, 0].double())
+        q.close()
+    cs, ce = got[b.PATH_SCREEN][0], got[b.PATH_EXACT][0]
+    assert int(cs.min()) >= 0 and int(cs.max()) < K and int(cs[-1].min()) >= 0
+    diff = (cs != ce).any(dim=1)
+    assert int(diff.sum()) <= max(2, int(1e-4 * V))
+    if bool(diff.any()):
+        rows = torch.nonzero(diff)[:, 0]
+        first = (cs[rows] != ce[rows]).long().argmax(dim=1)
+        r = X[rows].double()
+        for i in range(depth):  # residual entering the first stage where the codes differ
+            sel = first > i
+            r = r - torch.where(sel[:, None], C[i][ce[rows, i]].double(), torch.zeros_like(r))
+        da = ((r - C[first, cs[rows, first]].double()) ** 2).sum(1)
+        db = ((r - C[first, ce[rows, first]].double()) ** 2).sum(1)
+        assert bool(((da - db).abs() <= 1e-5 * (r ** 2).sum(1)).all())
+    # where the codes agree the residuals do too (both subtract the same fp32 codewords)
+    same = ~diff
+    assert torch.equal(got[b.PATH_SCREEN][1][same], got[b.PATH_EXACT][1][same])
+
+
 def _stage0_residual(b, q, dX, N, d, G, depth):
     """Residuals after stage 0, in group order [N][G * 32], from a one-stage call."""
     torch = _torch()
