@@ -1240,7 +1240,7 @@ hipError_t rvq_launch_encode_screen(const rvq_ctx *ctx, const void *dX, int64_t 
   }
   a.wait_polls = ctx->wait_polls;
   // one workgroup fills a CU (LDS): as many workgroups as CUs, each walking its share of the chunks
-  // Two tokens per lane (chunks of 1024) or one (chunks of 512; codebooks that fit LDS)?  A
+  // Two tokens per lane (chunks of 1024) or one (chunks of 512)?  A
   // workgroup takes its chunks one after the other, and the call lasts as long as the workgroup
   // with the most of them: measured, 350 us per chunk of 1024 and 190 us per chunk of 512.  The
   // form with the shorter estimate runs: one token per lane for calls that leave CUs idle
@@ -1249,7 +1249,9 @@ hipError_t rvq_launch_encode_screen(const rvq_ctx *ctx, const void *dX, int64_t 
   const int64_t cus = ctx->num_cus > 0 ? ctx->num_cus : 1;
   const int64_t rounds_full = ((a.V + SCR_TOKENS - 1) / SCR_TOKENS + cus - 1) / cus;
   const int64_t rounds_half = ((a.V + SCR_TOKENS / 2 - 1) / (SCR_TOKENS / 2) + cus - 1) / cus;
-  const bool half = a.Kpad <= SCR_KC && rounds_half * 19 < rounds_full * 35;
+  // (a codebook swept in pieces pays its copies and barriers per chunk: there the one-token form
+  // is taken only where it is a single round)
+  const bool half = a.Kpad <= SCR_KC ? rounds_half * 19 < rounds_full * 35 : rounds_half == 1;
   const int64_t chunk = half ? SCR_TOKENS / 2 : SCR_TOKENS;
   const int64_t nchunks = (a.V + chunk - 1) / chunk;
   const int64_t grid64 = nchunks < ctx->num_cus ? nchunks : ctx->num_cus;
@@ -1261,11 +1263,17 @@ hipError_t rvq_launch_encode_screen(const rvq_ctx *ctx, const void *dX, int64_t 
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)SCR_LDS_BYTES);      \
   if (e != hipSuccess) return e;                                                                \
   hipLaunchKernelGGL((encode_screen_kernel<DT, SC, ##__VA_ARGS__>), grid, block, SCR_LDS_BYTES, s, a)
-  if (half) {
+  if (half && a.Kpad <= SCR_KC) {
     switch (c.in_dtype) {
       case RVQ_F32: RVQ_LAUNCH_SCREEN(RVQ_F32, true, true); break;
       case RVQ_BF16: RVQ_LAUNCH_SCREEN(RVQ_BF16, true, true); break;
       default: RVQ_LAUNCH_SCREEN(RVQ_F16, true, true); break;
+    }
+  } else if (half) {
+    switch (c.in_dtype) {
+      case RVQ_F32: RVQ_LAUNCH_SCREEN(RVQ_F32, false, true); break;
+      case RVQ_BF16: RVQ_LAUNCH_SCREEN(RVQ_BF16, false, true); break;
+      default: RVQ_LAUNCH_SCREEN(RVQ_F16, false, true); break;
     }
   } else if (a.Kpad <= SCR_KC) {
     switch (c.in_dtype) {

@@ -307,8 +307,11 @@ def test_encode_chunks_of_512_and_of_1024_agree(gpu_device):
     q.close()
 
 
-@pytest.mark.parametrize("V", [511, 513, 1023, 1025, 4097, 130561, 131071, 131073, 262145, 300000])
-def test_encode_chunk_boundaries_against_the_exact_path(gpu_device, V):
+@pytest.mark.parametrize("V,K", [(511, 256), (513, 256), (1023, 256), (1025, 256), (4097, 256),
+                                 (130561, 256), (131071, 256), (131073, 256), (262145, 256), (300000, 256),
+                                 # codebooks swept in two pieces of LDS, in both chunk forms
+                                 (513, 2304), (70001, 2304), (131073, 2304)])
+def test_encode_chunk_boundaries_against_the_exact_path(gpu_device, V, K):
     """Vector counts one off the chunk sizes of the matrix-core kernel (512 with one token per
     lane, 1024 with two), off a full round of 256 workgroups, and a ragged count that takes three
     rounds of 512: rows of one group (d = 32), so the row count is the vector count.  The codes
@@ -316,7 +319,7 @@ def test_encode_chunk_boundaries_against_the_exact_path(gpu_device, V):
     codewords' exact distances within 1e-5 of the residual's squared norm), and the last
     vector, the one a partial chunk ends on, must be encoded."""
     torch, b = _torch(), _b()
-    depth, K = 4, 256
+    depth = 4 if K <= 256 else 2
     gen = torch.Generator(device="cuda")
     gen.manual_seed(V)
     X = torch.randn((V, 32), device="cuda", generator=gen)
